@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the libentro hot path on one MI355X.
+
+A step is one entro_decode_dequant pass (-> bf16) over the whole mistral-7B-shaped
+8-bit weight set (32 layers x 7 linears = 224 tensors, one prepared launch), with
+the compressed streams and offset tables already resident in HBM.  The same run
+also times the two other sinks of the path on the same compressed set -- integer
+output (entro_decode -> u8) and the fused batch-1 GEMV (entro_decode_gemv, four
+launches per layer as the layer's data dependencies allow) -- and reports them
+as extra fields.  One JSON line is printed at the end.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=32, help="layers of the mistral-7B-shaped set (32 = the full workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the u8 and GEMV legs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no collectives; see DESIGN.md); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2505_02380_amd as E
+    from paper_2505_02380_amd.workload import prepare_config, default_threads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    E.lib()
+
+    # ------------------------------------------------------------------ inputs
+    t0 = time.time()
+    done = [0]
+
+    def progress(i, total):
+        done[0] += 1
+        if done[0] % 28 == 0 or done[0] == total:
+            log(f"encoded {done[0]}/{total} tensors ({time.time() - t0:.0f} s)")
+
+    log(f"preparing mistral-7B-shaped set, {args.layers} layers, {default_threads()} host threads")
+    encs = prepare_config(4, layers=args.layers, progress=progress)
+    n_sym = sum(e.n for e in encs)
+    stream_bytes = sum(e.stream.size for e in encs)
+    offset_bytes = sum(e.offsets.size * 8 for e in encs)
+    total_bits = sum(e.total_bits for e in encs)
+    mean_len = total_bits / n_sym
+    log(f"{n_sym} symbols, {stream_bytes / 1e9:.3f} GB compressed, mean code length {mean_len:.3f} bits, "
+        f"prepared in {time.time() - t0:.0f} s")
+
+    dts = [E.to_device(e, dev) for e in encs]
+    out_bf16 = torch.empty(n_sym, dtype=torch.bfloat16, device=dev)
+    views, pos = [], 0
+    for e in encs:
+        views.append(out_bf16[pos:pos + e.n])
+        pos += e.n
+    ts = [d.ctensor(v) for d, v in zip(dts, views)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=dev)
+    plan = E.entro_plan_init(ts, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws)
+
+    def timed(fn, steps, warmup):
+        """(wall ms per step, event ms per step) over exactly `steps` calls after `warmup` calls."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t_start = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t_start) * 1e3 / steps
+        return wall, sum(a.elapsed_time(b) for a, b in ev) / steps
+
+    # ------------------------------------------------- headline: decode + dequant -> bf16
+    log("timing entro_decode_dequant -> bf16")
+    wall_ms, kern_ms = timed(lambda: E.entro_plan_run(plan), args.steps, args.warmup)
+    out_bytes = n_sym * 2
+    algo_bytes = stream_bytes + offset_bytes + out_bytes
+    decoded_gbps = out_bytes / (wall_ms * 1e-3) / 1e9
+    achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
+    log(f"dequant: {wall_ms:.3f} ms/step wall, {kern_ms:.3f} ms kernel, {achieved:.0f} GB/s algorithmic")
+
+    # ---------------------------------------------- check sampled segments against the oracle
+    import oracle
+    rng = np.random.default_rng(2024)
+    checked = 0
+    for _ in range(24):
+        i = int(rng.integers(0, len(encs)))
+        e = encs[i]
+        k = int(rng.integers(0, e.offsets.size - 1))
+        lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
+        q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
+                                 out=np.zeros(e.n, np.uint8))[lo:hi]
+        ref = oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
+        got = views[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+        if not np.array_equal(got, ref):
+            print(f"bench.py: GPU output differs from the oracle in tensor {e.name} segment {k}", file=sys.stderr)
+            sys.exit(1)
+        checked += 1
+    log(f"{checked} sampled segments match the oracle")
+
+    result = {
+        "metric": "decoded weights GB/s (entro_decode_dequant -> bf16, mistral-7B-shaped 8-bit set)",
+        "value": round(decoded_gbps, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": f"configs[3]: mistral-7B-shaped, {args.layers} layers x 7 linears, Student-t(5)*0.02, "
+                               "asymmetric 8-bit, chunks of 4096 symbols, decode+dequant to bf16",
+                   "symbols": n_sym, "tensors": len(encs), "compressed_bytes": stream_bytes,
+                   "mean_code_len_bits": round(mean_len, 4),
+                   "bits_saved": round(E.entro_bits_saved(8, mean_len), 4),
+                   "theoretical_speedup": round(E.entro_theoretical_speedup(8, mean_len), 4)},
+        "symbols_per_s": round(n_sym / (wall_ms * 1e-3), 0),
+        "compressed_GBps": round(stream_bytes / (wall_ms * 1e-3) / 1e9, 2),
+        "hbm_fraction_wall": round(algo_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "verified_segments": checked,
+        "roofline": {"bound": "hbm", "kernel": "k_batch<bf16>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": round(kern_ms, 4),
+                     "traffic": None},
+    }
+
+    # ------------------------------------------------------------ extra legs: u8 and GEMV
+    if not args.no_extras:
+        log("timing entro_decode -> u8")
+        out_u8 = torch.empty(n_sym, dtype=torch.uint8, device=dev)
+        v8, pos = [], 0
+        for e in encs:
+            v8.append(out_u8[pos:pos + e.n])
+            pos += e.n
+        ts8 = [d.ctensor(v) for d, v in zip(dts, v8)]
+        ws8 = torch.zeros(E.entro_workspace_bytes(ts8, E.ENTRO_OP_DECODE), dtype=torch.uint8, device=dev)
+        plan8 = E.entro_plan_init(ts8, E.ENTRO_OP_DECODE, E.ENTRO_U8, ws8)
+        w8, k8 = timed(lambda: E.entro_plan_run(plan8), args.steps, args.warmup)
+        result["decode_u8"] = {"ms_per_step": round(w8, 4), "kernel_ms": round(k8, 4),
+                               "symbols_per_s": round(n_sym / (w8 * 1e-3), 0),
+                               "hbm_frac": round((stream_bytes + offset_bytes + n_sym) / (k8 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del out_u8, v8, ts8, plan8
+
+        log("timing entro_decode_gemv (batch-1 token step, 4 launches per layer)")
+        groups = [(0, 3), (3, 4), (4, 6), (6, 7)]          # q,k,v | o | gate,up | down
+        layers = args.layers
+        plans = []
+        keep = []
+        for layer in range(layers):
+            base = 7 * layer
+            for a, b in groups:
+                tl = []
+                for j in range(a, b):
+                    e = encs[base + j]
+                    xb = synth.make_x_bf16(layer, j, e.cols)
+                    x = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
+                    y = torch.zeros(e.rows, dtype=torch.float32, device=dev)
+                    keep.append((x, y, base + j, xb))
+                    tl.append(dts[base + j].ctensor(y, x))
+                wsg = torch.zeros(E.entro_workspace_bytes(tl, E.ENTRO_OP_GEMV), dtype=torch.uint8, device=dev)
+                keep.append(wsg)
+                plans.append(E.entro_plan_init(tl, E.ENTRO_OP_GEMV, E.ENTRO_F32, wsg))
+
+        def token_step():
+            for p in plans:
+                E.entro_plan_run(p)
+
+        wg, kg = timed(token_step, args.steps, args.warmup)
+        # check a few rows of the last layer's `down` and first layer's `q` against the oracle
+        for (x, y, idx, xb) in [k for k in keep if isinstance(k, tuple)][:1] + [k for k in keep if isinstance(k, tuple)][-1:]:
+            e = encs[idx]
+            yh = y.cpu().numpy().astype(np.float64)
+            rows = [0, e.rows // 2, e.rows - 1]
+            sub = np.empty((len(rows), e.cols), np.uint8)
+            for j, r in enumerate(rows):
+                k0, k1 = (r * e.cols) // e.chunk_symbols, ((r + 1) * e.cols - 1) // e.chunk_symbols
+                q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(),
+                                         k0, k1 - k0 + 1)
+                sub[j] = q[r * e.cols:(r + 1) * e.cols]
+            y_ref, _ = oracle.gemv(sub, len(rows), e.cols, e.qp.scale, e.qp.zero_point, xb)
+            rms = np.sqrt(np.mean(yh ** 2))
+            if np.max(np.abs(yh[rows] - y_ref) / np.maximum(np.abs(y_ref), rms)) > 1e-3:
+                print(f"bench.py: GEMV output differs from the oracle in tensor {e.name}", file=sys.stderr)
+                sys.exit(1)
+        result["gemv"] = {"us_per_layer": round(wg * 1e3 / layers, 2), "kernel_us_per_layer": round(kg * 1e3 / layers, 2),
+                          "launches_per_layer": len(groups),
+                          "compressed_GBps": round(stream_bytes / (wg * 1e-3) / 1e9, 2),
+                          "effective_uint8_GBps": round(n_sym / (wg * 1e-3) / 1e9, 2),
+                          "hbm_frac": round((stream_bytes + offset_bytes) / (kg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        log(f"gemv: {result['gemv']['us_per_layer']} us/layer")
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        wc, kc = timed(lambda: dst.copy_(src), 3, 1)
+        result["copy_calibration"] = {"bytes_each_way": 1 << 30, "kernel_ms": round(kc, 4),
+                                      "GBps_read_plus_write": round(2 * (1 << 30) / (kc * 1e-3) / 1e9, 1)}
+
+    # -------------------------------------------------------------- oracle on the host cores
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample")
+        budget_syms = 400_000_000
+        t_cpu, syms = 0.0, 0
+        sample = []
+        for e in encs:
+            if syms + e.n > budget_syms and syms > 0:
+                break
+            ln, code = e.cb.lengths(), e.cb.codes()
+            t1 = time.perf_counter()
+            q = oracle.decode(e.stream, e.offsets, e.n, e.chunk_symbols, ln, code)
+            oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
+            t_cpu += time.perf_counter() - t1
+            syms += e.n
+            sample.append(e.name)
+        result["cpu_baseline"] = {"value": round(syms * 2 / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1,
+                                  "kind": "oracle",
+                                  "sample": f"{len(sample)} tensors ({sample[0]}..{sample[-1]}), {syms} symbols, "
+                                            f"{t_cpu:.1f} s: bit-at-a-time tree-walk decode + (q-z)*s -> bf16",
+                                  "symbols_per_s": round(syms / t_cpu, 0)}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

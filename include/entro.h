@@ -1,0 +1,232 @@
+/*
+ * libentro -- entropy-coded LLM weights decoded on MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of EntroLLM (arxiv 2505.02380):
+ *   offline, host:  quantize a tensor to 8 or 4 bits with one (s, z) pair
+ *                   (Proposed Method, "Mixed Quantization Scheme", Eq. 1,
+ *                   Fig. 2), build a Huffman code over the 256 / 16 symbols
+ *                   ("Huffman weight encoding"), encode the symbols into
+ *                   independently decodable segments ("Segmentation for
+ *                   parallel Huffman decoding", Fig. 3);
+ *   on the GPU:     decode all segments in parallel back to integers, or
+ *                   straight to dequantised fp32 / bf16 weights, or straight
+ *                   into a batch-1 matrix-vector product of the
+ *                   bandwidth-bound token-generation phase ("Latency Reduction
+ *                   from Huffman Coding").
+ *
+ * Conventions
+ *   - Plain pointers and sizes only.  "host" pointers are ordinary memory,
+ *     "device" pointers are HIP device memory of the current device.
+ *   - The caller owns every buffer.  The library allocates no device memory
+ *     and keeps no state between calls.
+ *   - Device entry points only enqueue work on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and return without waiting.
+ *   - Every failure is a return code; nothing is thrown, nothing aborts.  All
+ *     argument checks happen on the host before any launch.  A corrupt stream
+ *     can decode to wrong symbols but is never read outside
+ *     [stream, stream + stream_bytes) nor written outside the output tensor.
+ *   - Device pointers (stream, offsets, x, out, workspace) must be 16-byte
+ *     aligned.
+ *
+ * Stream format (the paper fixes none; this is the library's own)
+ *   - One stream, one codebook, one offset table per tensor.
+ *   - A segment ("chunk") is `chunk_symbols` consecutive symbols of the
+ *     flattened row-major tensor; the last one may be shorter.  Segments are
+ *     bit-packed back to back without alignment.
+ *   - Bit k of a stream is (stream[k >> 3] >> (k & 7)) & 1.  A code of length
+ *     L is written first code bit first, i.e. its most significant bit goes
+ *     to the lowest stream position.
+ *   - offsets[k], k = 0..n_chunks, is the stream bit at which segment k
+ *     starts; offsets[n_chunks] is the total bit count.
+ *   - After the last code the stream is zero-padded to a whole byte, then to a
+ *     multiple of 16 bytes, then by 16 more bytes; stream_bytes includes all
+ *     padding.
+ *   - Codes are canonical: present symbols ordered by (length, symbol value)
+ *     receive increasing code values, first code 0, next = (prev + 1) shifted
+ *     left by the increase in length.
+ */
+#ifndef ENTRO_H
+#define ENTRO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ENTRO_MAX_CODE_LEN 32
+#define ENTRO_MAX_SYMBOLS 256
+
+typedef enum {
+    ENTRO_OK = 0,
+    ENTRO_ERR_NULL = 1,          /* a required pointer is NULL */
+    ENTRO_ERR_BITS = 2,          /* bits is neither 4 nor 8 */
+    ENTRO_ERR_SCHEME = 3,        /* unknown quantisation scheme / output type not valid for the call */
+    ENTRO_ERR_SIZE = 4,          /* n == 0, chunk_symbols == 0, rows*cols != n, odd chunk for packed 4-bit, ... */
+    ENTRO_ERR_NONFINITE = 5,     /* NaN or Inf in the weights */
+    ENTRO_ERR_RANGE = 6,         /* negative weight under the unsigned scheme; constant tensor */
+    ENTRO_ERR_SYMBOL = 7,        /* symbol >= 2^bits, or symbol without a code */
+    ENTRO_ERR_CODE_TOO_LONG = 8, /* a code would exceed ENTRO_MAX_CODE_LEN bits */
+    ENTRO_ERR_CAPACITY = 9,      /* an output buffer or workspace is too small */
+    ENTRO_ERR_CORRUPT = 10,      /* inconsistent codebook or offset table */
+    ENTRO_ERR_ALIGN = 11,        /* a device pointer is not 16-byte aligned */
+    ENTRO_ERR_DEVICE = 12        /* a HIP call failed; see entro_last_device_error() */
+} entro_status;
+
+typedef enum { ENTRO_UNSIGNED = 0, ENTRO_ASYMMETRIC = 1 } entro_scheme;
+typedef enum { ENTRO_U8 = 0, ENTRO_U4_PACKED = 1, ENTRO_F32 = 2, ENTRO_BF16 = 3 } entro_dtype;
+typedef enum { ENTRO_OP_DECODE = 0, ENTRO_OP_DEQUANT = 1, ENTRO_OP_GEMV = 2 } entro_op;
+
+/* One scale and zero-point per tensor (Eq. 1, Fig. 2).  w ~ (q - zero_point) * scale. */
+typedef struct {
+    float scale;
+    int32_t zero_point;   /* 0 for the unsigned scheme; may lie outside [0, 2^bits) */
+    int32_t bits;         /* 4 or 8 */
+    int32_t scheme;       /* entro_scheme */
+} entro_qparams;
+
+/* Canonical Huffman code over 2^bits symbols.  len[s] == 0: symbol s has no code. */
+typedef struct {
+    int32_t bits;                        /* 4 or 8 */
+    int32_t n_used;                      /* symbols with a code */
+    int32_t max_len;                     /* longest code, <= ENTRO_MAX_CODE_LEN */
+    int32_t reserved;
+    uint8_t len[ENTRO_MAX_SYMBOLS];
+    uint32_t code[ENTRO_MAX_SYMBOLS];    /* code value, read as a len-bit integer, MSB = first bit */
+} entro_codebook;
+
+/* One encoded tensor as the device entry points see it. */
+typedef struct {
+    const void *stream;          /* device: encoded bytes, padded as described above */
+    uint64_t stream_bytes;       /* < 2^32 */
+    const uint64_t *offsets;     /* device: n_chunks + 1 bit offsets */
+    uint64_t n;                  /* symbols (= rows * cols for the GEMV) */
+    uint32_t chunk_symbols;      /* symbols per segment; even when the output is ENTRO_U4_PACKED */
+    uint32_t rows, cols;         /* GEMV only: W is [rows][cols] row-major */
+    uint32_t reserved;
+    const entro_codebook *cb;    /* host */
+    entro_qparams qp;            /* dequant and GEMV: scale and zero_point; bits must equal cb->bits */
+    const void *x;               /* GEMV only, device: bf16[cols] */
+    void *out;                   /* device: u8[n] | u8[(n+1)/2] | f32[n] | bf16[n]; GEMV: f32[rows] | bf16[rows] */
+} entro_tensor;
+
+/* A prepared launch over `count` tensors.  Filled by entro_plan_init; plain data, caller-owned.
+ * The workspace it points to (device memory) must stay untouched while the plan is in use. */
+typedef struct {
+    void *workspace;
+    uint64_t workspace_bytes;
+    uint32_t op;          /* entro_op */
+    uint32_t out;         /* entro_dtype */
+    uint32_t count;       /* tensors */
+    uint32_t n_items;     /* workgroup-sized work items in the launch */
+    uint32_t n_fix;       /* GEMV: rows that need the second-stage sum */
+    uint32_t flags;
+    uint64_t off_tensors, off_items, off_partials, off_fix;   /* byte offsets inside the workspace */
+} entro_plan;
+
+/* ------------------------------------------------------------------ host side
+ * Synchronous, no allocation visible to the caller, safe to call from several
+ * threads on different buffers. */
+
+/* Eq. 1 with Q = 2^bits - 1, binary32 arithmetic, round-half-even:
+ *   unsigned:   s = max/Q, z = 0;   asymmetric: s = (max - min)/Q, z = rint(-min/s);
+ *   q = clamp(rint(w/s) + z, 0, Q), one symbol per output byte.
+ * w: host, n floats.  q: host, n bytes.  qp: receives scale, zero_point, bits, scheme. */
+entro_status entro_quantize(const float *w, uint64_t n, int bits, entro_scheme scheme,
+                            uint8_t *q, entro_qparams *qp);
+
+/* "Huffman weight encoding": count the symbols, build an optimal prefix code
+ * (length = depth in the merge tree), assign canonical code values.
+ * q: host, n symbols one per byte, each < 2^bits.  A lone symbol gets a 1-bit code. */
+entro_status entro_build_codebook(const uint8_t *q, uint64_t n, int bits, entro_codebook *cb);
+
+/* Same, from a ready histogram of 2^bits counts. */
+entro_status entro_codebook_from_counts(const uint64_t *counts, int bits, entro_codebook *cb);
+
+/* Canonical code values for given lengths (0 = absent).  Rejects lengths above
+ * ENTRO_MAX_CODE_LEN and length sets whose Kraft sum exceeds 1. */
+entro_status entro_codebook_from_lengths(const uint8_t *len, int bits, entro_codebook *cb);
+
+/* ceil(n / chunk_symbols); 0 if chunk_symbols == 0. */
+uint64_t entro_num_chunks(uint64_t n, uint32_t chunk_symbols);
+
+/* Upper bound in bytes (padding included) of the stream entro_encode writes; 0 on bad arguments. */
+uint64_t entro_encode_bound(uint64_t n, const entro_codebook *cb);
+
+/* Encode q (host, n symbols) into stream (host, stream_cap bytes) and fill
+ * offsets (host, entro_num_chunks + 1 entries).  *stream_bytes receives the
+ * padded size.  ENTRO_ERR_SYMBOL if a symbol has no code, ENTRO_ERR_CAPACITY
+ * if stream_cap is too small (nothing useful is written then). */
+entro_status entro_encode(const uint8_t *q, uint64_t n, const entro_codebook *cb,
+                          uint32_t chunk_symbols, uint8_t *stream, uint64_t stream_cap,
+                          uint64_t *stream_bytes, uint64_t *offsets);
+
+/* Consistency check of a host copy of an offset table against a stream size:
+ * offsets[0] == 0, non-decreasing, each segment no longer than
+ * chunk_symbols * max_len bits and no shorter than its symbol count times the
+ * shortest code, last offset within stream_bytes minus the 16 trailing pad
+ * bytes.  ENTRO_ERR_CORRUPT otherwise. */
+entro_status entro_check_offsets(const uint64_t *offsets, uint64_t n, uint32_t chunk_symbols,
+                                 uint64_t stream_bytes, const entro_codebook *cb);
+
+/* Reporting helpers for the quantities the paper tabulates (Table 2 "bits
+ * saved" = bits - mean code length; theoretical token-generation speed-up =
+ * bits / mean code length, as in "Latency Reduction from Huffman Coding"). */
+double entro_bits_saved(int bits, double mean_code_len);
+double entro_theoretical_speedup(int bits, double mean_code_len);
+
+const char *entro_status_string(entro_status s);
+
+/* ---------------------------------------------------------------- device side
+ * One tensor per call, descriptor passed in kernel arguments (no workspace
+ * needed except for the GEMV's second-stage sum). */
+
+/* Segment-parallel decode back to integers.  out_type: ENTRO_U8 (one symbol
+ * per byte) or ENTRO_U4_PACKED (4-bit codebooks only; symbol 2i in the low
+ * nibble of byte i, 2i+1 in the high nibble, last high nibble zero if n is odd). */
+entro_status entro_decode(const entro_tensor *t, entro_dtype out_type, void *hip_stream);
+
+/* Decode fused with the inverse grid map w = (q - z) * s (integer difference,
+ * exact conversion, one binary32 multiply).  out_type: ENTRO_F32 (bit-exact)
+ * or ENTRO_BF16 (the binary32 value rounded to nearest even). */
+entro_status entro_decode_dequant(const entro_tensor *t, entro_dtype out_type, void *hip_stream);
+
+/* Bytes of device workspace entro_decode_gemv needs for this tensor (may be 0). */
+uint64_t entro_gemv_workspace_bytes(const entro_tensor *t);
+
+/* y = W x for batch-1 token generation without materialising W:
+ * y[r] = s * sum_j (q[r][j] - z) * x[j], fp32 accumulation, x bf16, W row-major.
+ * y_type: ENTRO_F32 or ENTRO_BF16.  Rows that straddle segments are summed in
+ * segment order by a second small kernel (deterministic). */
+entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *workspace,
+                               uint64_t workspace_bytes, void *hip_stream);
+
+/* Batched forms: ONE launch over `count` tensors (a single tensor has too few
+ * segments to fill 256 compute units).  The descriptor table, the work list
+ * and the GEMV partial sums live in `workspace` (device). */
+uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
+
+/* Validate, build the table on the host and copy it into the workspace
+ * (stream-ordered).  The tensors' device buffers are referenced, not copied. */
+entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
+                             entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
+                             void *hip_stream);
+
+/* Enqueue the prepared launch; no host-side table work, no copies. */
+entro_status entro_plan_run(const entro_plan *plan, void *hip_stream);
+
+/* entro_plan_init followed by entro_plan_run. */
+entro_status entro_decode_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,
+                                void *workspace, uint64_t workspace_bytes, void *hip_stream);
+entro_status entro_decode_dequant_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,
+                                        void *workspace, uint64_t workspace_bytes, void *hip_stream);
+entro_status entro_decode_gemv_batch(const entro_tensor *ts, uint32_t count, entro_dtype y_type,
+                                     void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *entro_last_device_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENTRO_H */

@@ -1,0 +1,288 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bars: decoded integers bit-exact; fp32 dequant bit-exact; bf16 within 1 ulp
+(the kernels round to nearest even, so equality is expected and asserted as
+<= 1 ulp); GEMV relative error <= 1e-3 against the fp64 oracle, both as
+||y - y*||_2 / ||y*||_2 and as max_r |y_r - y*_r| <= 1e-3 * max(|y*_r|, rms(y*)).
+Inputs never come from the HIP path: symbols, codebooks and streams are built
+by the oracle (or by the host library and re-decoded by the oracle)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+import paper_2505_02380_amd as E
+from paper_2505_02380_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _oracle_encoded(sym, bits, chunk, rows=0, cols=0, s=1.0, z=0):
+    """EncodedTensor whose codebook and stream both come from the oracle."""
+    ln, code, _ = oracle.codebook_from_symbols(sym, bits)
+    stream, off = oracle.encode(sym, ln, code, chunk)
+    full = np.zeros(1 << bits, np.uint8)
+    full[: ln.size] = ln
+    cb = E.entro_codebook_from_lengths(full, bits)
+    assert np.array_equal(cb.codes(), code)
+    qp = B.QParams(np.float32(s), int(z), bits, E.ENTRO_ASYMMETRIC)
+    return B.EncodedTensor(stream, off, sym.size, chunk, cb, qp, rows, cols)
+
+
+def _bf16_ulp_diff(a_bits, b_bits):
+    def key(u):
+        u = u.astype(np.int32)
+        return np.where(u & 0x8000, 0x8000 - u, u)       # monotone integer order of bf16 patterns
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+def _gpu_decode(enc, out_type, batch=False):
+    dt = E.to_device(enc, DEV)
+    nbytes = enc.n if out_type == E.ENTRO_U8 else (enc.n + 1) // 2
+    out = torch.full((nbytes + 64,), 0xAB, dtype=torch.uint8, device=DEV)      # guard bytes behind the output
+    t = dt.ctensor(out)
+    if batch:
+        ws = torch.zeros(E.entro_workspace_bytes([t], E.ENTRO_OP_DECODE), dtype=torch.uint8, device=DEV)
+        E.entro_decode_batch([t], out_type, ws)
+    else:
+        E.entro_decode(t, out_type)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    assert np.all(res[nbytes:] == 0xAB), "wrote past the end of the output"
+    return res[:nbytes]
+
+
+def _gpu_dequant(enc, out_type, batch=False):
+    dt = E.to_device(enc, DEV)
+    dtype = torch.float32 if out_type == E.ENTRO_F32 else torch.bfloat16
+    out = torch.zeros(enc.n + 16, dtype=dtype, device=DEV)
+    t = dt.ctensor(out)
+    if batch:
+        ws = torch.zeros(E.entro_workspace_bytes([t], E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=DEV)
+        E.entro_decode_dequant_batch([t], out_type, ws)
+    else:
+        E.entro_decode_dequant(t, out_type)
+    torch.cuda.synchronize()
+    assert torch.all(out[enc.n:] == 0), "wrote past the end of the output"
+    if out_type == E.ENTRO_F32:
+        return out[: enc.n].cpu().numpy()
+    return out[: enc.n].view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _gpu_gemv(enc, xb, y_type, batch=False):
+    dt = E.to_device(enc, DEV)
+    x = torch.from_numpy(xb.view(np.int16)).to(DEV).view(torch.bfloat16)
+    y = torch.zeros(enc.rows + 8, dtype=torch.float32 if y_type == E.ENTRO_F32 else torch.bfloat16, device=DEV)
+    t = dt.ctensor(y, x)
+    if batch:
+        ws = torch.zeros(max(E.entro_workspace_bytes([t], E.ENTRO_OP_GEMV), 16), dtype=torch.uint8, device=DEV)
+        E.entro_decode_gemv_batch([t], y_type, ws)
+    else:
+        need = E.entro_gemv_workspace_bytes(t)
+        ws = torch.zeros(need, dtype=torch.uint8, device=DEV) if need else None
+        E.entro_decode_gemv(t, y_type, ws)
+    torch.cuda.synchronize()
+    assert torch.all(y[enc.rows:] == 0)
+    return y[: enc.rows].float().cpu().numpy().astype(np.float64)
+
+
+def _assert_gemv_close(y, y_ref, tol=1e-3):
+    rel = np.linalg.norm(y - y_ref) / np.linalg.norm(y_ref)
+    rms = np.sqrt(np.mean(y_ref ** 2))
+    worst = np.max(np.abs(y - y_ref) / np.maximum(np.abs(y_ref), rms))
+    assert rel <= tol and worst <= tol, (rel, worst)
+
+
+# ---------------------------------------------------------------- integer decode
+@pytest.mark.parametrize("batch", [False, True])
+def test_config1_round_trip_bit_exact(batch):
+    spec = synth.config_tensors(1)[0]
+    w = synth.make_tensor(spec)
+    q, s, z = oracle.quantize(w, 8, oracle.ASYMMETRIC)
+    enc = _oracle_encoded(q, 8, 4096, s=s, z=z)
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch), q)
+    # the host library's own chain, re-decoded by the oracle
+    enc2 = E.encode_tensor(w, 8, E.ENTRO_ASYMMETRIC, 4096)
+    ref = oracle.decode(enc2.stream, enc2.offsets, enc2.n, 4096, enc2.cb.lengths(), enc2.cb.codes())
+    assert np.array_equal(_gpu_decode(enc2, E.ENTRO_U8, batch), ref)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_adversarial_streams_bit_exact(bits):
+    for name, sym, chunk in synth.adversarial_symbol_cases(bits):
+        enc = _oracle_encoded(sym, bits, chunk)
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), sym), name
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch=True), sym), name
+        if bits == 4:
+            assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED), oracle.pack_u4(sym)), name
+
+
+def test_odd_chunk_sizes_take_the_scalar_store_path():
+    rng = np.random.default_rng(31)
+    sym = np.minimum(rng.geometric(0.4, 40001) - 1, 255).astype(np.uint8)
+    for chunk in (1, 7, 1000, 4100):
+        enc = _oracle_encoded(sym, 8, chunk)
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), sym), chunk
+    sym4 = (sym & 15).astype(np.uint8)
+    for chunk in (2, 30, 1002):
+        enc = _oracle_encoded(sym4, 4, chunk)
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED), oracle.pack_u4(sym4)), chunk
+
+
+def test_codes_of_every_length_up_to_32():
+    # lengths 1..31, 32, 32: the deepest code the format allows; symbols drawn so long codes are common
+    ln = np.zeros(256, np.uint8)
+    ln[:33] = list(range(1, 32)) + [32, 32]
+    rng = np.random.default_rng(32)
+    sym = rng.integers(0, 33, 30000).astype(np.uint8)
+    code = oracle.canonical_codes(ln)
+    stream, off = oracle.encode(sym, ln, code, 512)
+    cb = E.entro_codebook_from_lengths(ln, 8)
+    enc = B.EncodedTensor(stream, off, sym.size, 512, cb, B.QParams(1.0, 0, 8, 1))
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), sym)
+
+
+def test_phi3_shaped_4bit_packed():
+    spec = synth.config_tensors(3)[1]                          # o: 3072 x 3072, Laplace, 4-bit
+    w = synth.make_tensor(spec)
+    q, s, z = oracle.quantize(w, 4, oracle.ASYMMETRIC)
+    enc = _oracle_encoded(q, 4, 8192, s=s, z=z)
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED, batch=True), oracle.pack_u4(q))
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), q)
+
+
+# ----------------------------------------------------------------------- dequant
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("batch", [False, True])
+def test_dequant_fp32_bit_exact_and_bf16_within_one_ulp(bits, batch):
+    spec = synth.TensorSpec(4, 0, 1, "k", 1024, 4096, "student_t", 5.0, 0.02, 0.0, bits, 1, 4242 + bits)
+    w = synth.make_tensor(spec)
+    q, s, z = oracle.quantize(w, bits, oracle.ASYMMETRIC)
+    enc = _oracle_encoded(q, bits, 4096, s=s, z=z)
+    f = _gpu_dequant(enc, E.ENTRO_F32, batch)
+    assert np.array_equal(f.view(np.uint32), oracle.dequant_f32(q, s, z).view(np.uint32))
+    b = _gpu_dequant(enc, E.ENTRO_BF16, batch)
+    assert _bf16_ulp_diff(b, oracle.dequant_bf16(q, s, z)).max() <= 1
+
+
+def test_dequant_ragged_and_unsigned_and_offgrid_zero_point():
+    rng = np.random.default_rng(5)
+    sym = rng.integers(170, 256, 2048).astype(np.uint8)        # norm-gain-like, one half-full segment
+    enc = _oracle_encoded(sym, 8, 4096, s=np.float32(1.2 / 255), z=0)
+    assert np.array_equal(_gpu_dequant(enc, E.ENTRO_F32).view(np.uint32),
+                          oracle.dequant_f32(sym, enc.qp.scale, 0).view(np.uint32))
+    sym = np.minimum(rng.geometric(0.2, 3 * 4096 + 5) - 1, 255).astype(np.uint8)
+    for z in (-255, 300, 17):
+        enc = _oracle_encoded(sym, 8, 4096, s=np.float32(0.37), z=z)
+        assert np.array_equal(_gpu_dequant(enc, E.ENTRO_F32).view(np.uint32),
+                              oracle.dequant_f32(sym, enc.qp.scale, z).view(np.uint32))
+        assert _bf16_ulp_diff(_gpu_dequant(enc, E.ENTRO_BF16), oracle.dequant_bf16(sym, enc.qp.scale, z)).max() <= 1
+
+
+# -------------------------------------------------------------------------- gemv
+@pytest.mark.parametrize("rows,cols,chunk", [
+    (96, 4096, 4096),        # one row per segment
+    (40, 14336, 4096),       # a row is 3.5 segments (the `down` projection)
+    (300, 2048, 4096),       # two rows per segment
+    (77, 300, 4096),         # rows do not divide segments
+    (5, 9000, 1024),         # long rows, ragged last segment
+    (1, 100, 4096),          # a single short row
+])
+@pytest.mark.parametrize("batch", [False, True])
+def test_gemv_against_fp64_oracle(rows, cols, chunk, batch):
+    spec = synth.TensorSpec(4, 0, 0, "g", rows, cols, "student_t", 5.0, 0.02, 0.0, 8, 1, 9000 + rows)
+    w = synth.make_tensor(spec)
+    q, s, z = oracle.quantize(w, 8, oracle.ASYMMETRIC)
+    enc = _oracle_encoded(q, 8, chunk, rows, cols, s, z)
+    xb = synth.make_x_bf16(0, rows % 7, cols)
+    y_ref, _ = oracle.gemv(q, rows, cols, s, z, xb)
+    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), y_ref)
+    y_bf = _gpu_gemv(enc, xb, E.ENTRO_BF16, batch)
+    assert np.all(np.abs(y_bf - y_ref) <= 2.0 ** -7 * np.abs(y_ref) + 1e-3 * np.sqrt(np.mean(y_ref ** 2)))
+
+
+def test_gemv_unit_vector_picks_a_column_exactly():
+    rows, cols = 64, 4096
+    rng = np.random.default_rng(1)
+    q = rng.integers(0, 256, rows * cols).astype(np.uint8)
+    s, z = np.float32(0.0123), 131
+    enc = _oracle_encoded(q, 8, 4096, rows, cols, s, z)
+    e = np.zeros(cols, np.float32)
+    e[1234] = 1.0
+    y = _gpu_gemv(enc, synth.f32_to_bf16_bits(e), E.ENTRO_F32)
+    col = oracle.dequant_f32(q, s, z).reshape(rows, cols)[:, 1234]
+    assert np.array_equal(y.astype(np.float32), col)
+
+
+# ------------------------------------------------------------- batched launches
+def test_many_tensors_in_one_launch():
+    rng = np.random.default_rng(12)
+    encs, refs = [], []
+    for i, (n, chunk) in enumerate([(300000, 4096), (2048, 4096), (4096 * 300 + 1, 4096), (70000, 1000), (5, 4096)]):
+        sym = np.minimum(rng.geometric(0.1 + 0.15 * i, n) - 1, 255).astype(np.uint8)
+        encs.append(_oracle_encoded(sym, 8, chunk, s=np.float32(0.01 * (i + 1)), z=10 * i))
+        refs.append(sym)
+    dts = [E.to_device(e, DEV) for e in encs]
+    outs = [torch.zeros(e.n, dtype=torch.uint8, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DECODE), dtype=torch.uint8, device=DEV)
+    plan = E.entro_plan_init(ts, E.ENTRO_OP_DECODE, E.ENTRO_U8, ws)
+    for _ in range(2):                                         # a prepared plan can be replayed
+        for o in outs:
+            o.zero_()
+        E.entro_plan_run(plan)
+        torch.cuda.synchronize()
+        for o, r in zip(outs, refs):
+            assert np.array_equal(o.cpu().numpy(), r)
+    fouts = [torch.zeros(e.n, dtype=torch.bfloat16, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, fouts)]
+    E.entro_decode_dequant_batch(ts, E.ENTRO_BF16, ws)
+    torch.cuda.synchronize()
+    for e, o, r in zip(encs, fouts, refs):
+        got = o.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert _bf16_ulp_diff(got, oracle.dequant_bf16(r, e.qp.scale, e.qp.zero_point)).max() <= 1
+
+
+def test_mistral_layer_launch_shape_sampled_against_oracle():
+    """One mistral-7B-shaped layer in the batched launch bench.py uses; sampled segments vs the oracle."""
+    from paper_2505_02380_amd.workload import prepare_config
+    encs = prepare_config(4, layers=1)
+    dts = [E.to_device(e, DEV) for e in encs]
+    outs = [torch.zeros(e.n, dtype=torch.bfloat16, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=DEV)
+    E.entro_decode_dequant_batch(ts, E.ENTRO_BF16, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    for e, o in zip(encs, outs):
+        n_chunks = e.offsets.size - 1
+        picks = sorted(set([0, n_chunks - 1] + rng.integers(0, n_chunks, 6).tolist()))
+        host = o.view(torch.int16).cpu().numpy().view(np.uint16)
+        for k in picks:
+            q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1)
+            lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
+            ref = oracle.dequant_bf16(q[lo:hi], e.qp.scale, e.qp.zero_point)
+            assert _bf16_ulp_diff(host[lo:hi], ref).max() <= 1, (e.name, k)
+    # the same layer through the fused GEMV (7 linears in one launch)
+    xs = [torch.from_numpy(synth.make_x_bf16(0, i, e.cols).view(np.int16)).to(DEV).view(torch.bfloat16)
+          for i, e in enumerate(encs)]
+    ys = [torch.zeros(e.rows, dtype=torch.float32, device=DEV) for e in encs]
+    ts = [d.ctensor(y, x) for d, y, x in zip(dts, ys, xs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_GEMV), dtype=torch.uint8, device=DEV)
+    E.entro_decode_gemv_batch(ts, E.ENTRO_F32, ws)
+    torch.cuda.synchronize()
+    for i, (e, y) in enumerate(zip(encs, ys)):
+        rows = sorted(set([0, e.rows - 1] + rng.integers(0, e.rows, 4).tolist()))
+        yh = y.cpu().numpy().astype(np.float64)
+        xb = synth.make_x_bf16(0, i, e.cols)
+        sub = np.empty((len(rows), e.cols), np.uint8)
+        for j, r in enumerate(rows):
+            k0, k1 = (r * e.cols) // e.chunk_symbols, ((r + 1) * e.cols - 1) // e.chunk_symbols
+            q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(),
+                                     k0, k1 - k0 + 1)
+            sub[j] = q[r * e.cols:(r + 1) * e.cols]
+        y_ref, _ = oracle.gemv(sub, len(rows), e.cols, e.qp.scale, e.qp.zero_point, xb)
+        rms = np.sqrt(np.mean(yh ** 2))
+        assert np.max(np.abs(yh[rows] - y_ref) / np.maximum(np.abs(y_ref), rms)) <= 1e-3, e.name
