@@ -4,8 +4,15 @@
 // EntroLLM ("Segmentation for parallel Huffman decoding", Fig. 3) cuts the
 // encoded parameter space into segments with known boundaries and decodes
 // them independently; here a segment is a fixed number of symbols and one
-// GPU lane owns one segment, so a 256-lane workgroup decodes 256 consecutive
+// GPU lane owns one segment, so a 704-lane workgroup decodes 704 consecutive
 // segments of one tensor with one shared set of lookup tables in LDS.
+//
+// Data flow of the decode / dequant kernels, per lane:
+//   HBM --16-byte blocks--> four-slot ring in LDS --96-bit reads--> 62-bit window
+//   window --11 bits--> first-level table (LDS) --> symbol, length, bf16 value
+//   symbols --packed--> the lane's 128-byte row of the wave's LDS tile --> HBM,
+// the tile being written out row-wise so that every global store instruction
+// of a wave covers whole 128-byte lines.
 #include "entro.h"
 
 #include <hip/hip_runtime.h>
@@ -14,14 +21,23 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <utility>
 #include <vector>
 
 namespace {
 
-constexpr int kWG = 256;            // lanes (= segments) per workgroup
-constexpr int kL1 = 11;             // bits resolved by the first-level table
+constexpr int kWG = 704;                 // lanes (= segments) per workgroup: 11 waves fill the 160 KB of LDS
+constexpr int kWaves = kWG / 64;
+constexpr int kL1 = 11;                  // bits resolved by the first-level table
 constexpr uint32_t kL1Mask = (1u << kL1) - 1u;
-constexpr int kBatch = 3;           // symbols decoded per 64-bit refill: 64 - 31 >= 3 * kL1
+constexpr int kL2Cap = 1024;             // second-level entries (all long prefixes together)
+constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 17 bits
+constexpr int kL2MaxPrefixes = 64;       // more long prefixes than this: second level unused
+constexpr int kGroup = 5;                // symbols per ring read: 62 valid bits >= 4 * 11 + 17
+constexpr int kCheck = 10;               // symbols between two refill checks (see ring_check)
+constexpr int kTrio = 3;                 // scalar reader: symbols per 64-bit load, 64 - 31 >= 3 * kL1
+constexpr int kRingStride = 19;          // dwords per lane: 4 x 16-byte slots, 2 mirror dwords, pad (odd)
+constexpr int kTileStride = 33;          // dwords per lane in the output tile: a 128-byte row plus one (odd)
 constexpr uint32_t kMaxChunkSymbols = 1u << 20;
 
 // What the kernels read about one tensor.  Lives in kernel arguments (single
@@ -53,16 +69,38 @@ struct WorkItem {
 
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5 };
 
-// LDS tables of one workgroup.  First-level entry: symbol | len << 8 | payload << 16,
-// len == 0 marks a prefix whose code is longer than kL1 bits.
-struct Tables {
+// Lookup tables of one workgroup (LDS).
+// Symbol entry: len | symbol << 8 | payload << 16 (the length sits in the low
+// byte so that it can feed a shift directly; payload = bf16 of the dequantised
+// value in bf16 mode).
+// First level: indexed by the next kL1 stream bits.  len == 0 marks a prefix
+// whose codes are longer than kL1 bits; the entry then is
+// depth << 8 | base << 16: the prefix owns lut2[base .. base + 2^depth).
+// Second level: indexed by the following `depth` stream bits; len == 0 there
+// sends the lane to the canonical search (first / cnt / offs / sorted).
+struct alignas(16) Tables {
     uint32_t lut[1 << kL1];
+    uint32_t lut2[kL2Cap];
     uint32_t cnt[ENTRO_MAX_CODE_LEN + 2];
     uint32_t first[ENTRO_MAX_CODE_LEN + 2];
     uint32_t offs[ENTRO_MAX_CODE_LEN + 2];
+    uint32_t pdepth[kL2MaxPrefixes];     // per long prefix: bits its second-level block resolves
+    uint32_t pbase[kL2MaxPrefixes];
+    uint32_t first_prefix;               // smallest kL1-bit prefix of a long code; 2^kL1 if level 2 is unused
+    uint32_t pad[3];
     uint8_t sorted[256];
     uint8_t lens[256];
 };
+
+// Per-wave LDS: the lanes' stream windows and their output rows.
+struct alignas(16) WaveMem {
+    uint32_t ring[64 * kRingStride];
+    uint32_t tile[64 * kTileStride];
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const u32x4 __attribute__((address_space(1))) *global_u4_ptr;
+typedef u32x4 __attribute__((address_space(1))) *global_u4_wptr;
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -76,69 +114,108 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
 
 template <int MODE>
 __device__ __forceinline__ uint32_t make_entry(uint32_t sym, uint32_t len, int32_t z, float s) {
-    uint32_t e = sym | (len << 8);
+    uint32_t e = len | (sym << 8);
     if (MODE == kModeBF16) e |= bf16_bits(dequant(sym, z, s)) << 16;
     return e;
 }
 
-// Canonical code tables and the first-level lookup table, built from the 256
-// (or 16) code lengths by the whole workgroup.
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Canonical code tables and both lookup levels, built from the 256 (or 16)
+// code lengths by the whole workgroup.
 template <int MODE>
 __device__ void build_tables(const DevTensor &t, Tables &tb) {
     const int tid = threadIdx.x;
-    const uint32_t l = t.len[tid];
-    tb.lens[tid] = static_cast<uint8_t>(l);
+    const uint32_t l = tid < 256 ? t.len[tid] : 0u;
+    if (tid < 256) tb.lens[tid] = static_cast<uint8_t>(l);
     if (tid < ENTRO_MAX_CODE_LEN + 2) tb.cnt[tid] = 0;
+    if (tid < kL2MaxPrefixes) tb.pdepth[tid] = 0;
     const uint32_t filler = make_entry<MODE>(0, 1, t.zero_point, t.scale);
     for (int i = tid; i < (1 << kL1); i += kWG) tb.lut[i] = filler;
+    for (int i = tid; i < kL2Cap; i += kWG) tb.lut2[i] = 0;
     __syncthreads();
     if (l) atomicAdd(&tb.cnt[l], 1u);
     __syncthreads();
     if (tid == 0) {
         uint64_t code = 0;
         uint32_t off = 0;
+        uint32_t first_prefix = 1u << kL1;                        // no long code seen yet
         for (int b = 1; b <= ENTRO_MAX_CODE_LEN; ++b) {
             code = (code + (b > 1 ? tb.cnt[b - 1] : 0u)) << 1;
             tb.first[b] = static_cast<uint32_t>(code);
             tb.offs[b] = off;
             off += tb.cnt[b];
+            if (b > kL1 && tb.cnt[b] && first_prefix == (1u << kL1))
+                first_prefix = static_cast<uint32_t>(code >> (b - kL1));
+        }
+        // canonical codes grow with length, so the long codes own the prefixes
+        // first_prefix .. 2^kL1 - 1
+        if ((1u << kL1) - first_prefix > static_cast<uint32_t>(kL2MaxPrefixes)) first_prefix = 1u << kL1;
+        tb.first_prefix = first_prefix;
+    }
+    __syncthreads();
+    uint32_t code = 0, rank = 0;
+    const uint32_t first_prefix = tb.first_prefix;
+    const bool have_l2 = first_prefix < (1u << kL1);
+    if (l) {
+        for (int s = 0; s < tid; ++s) rank += (tb.lens[s] == l);
+        code = tb.first[l] + rank;
+        tb.sorted[tb.offs[l] + rank] = static_cast<uint8_t>(tid);
+        if (l > kL1 && have_l2) atomicMax(&tb.pdepth[(code >> (l - kL1)) - first_prefix], l - kL1);
+    }
+    __syncthreads();
+    if (tid == 0 && have_l2) {
+        // every long prefix gets a block of 2^min(depth, cap) entries; lower the cap until all fit
+        const uint32_t n_prefix = (1u << kL1) - first_prefix;
+        uint32_t cap = kL2MaxBits;
+        for (;;) {
+            uint32_t total = 0;
+            for (uint32_t q = 0; q < n_prefix; ++q) total += 1u << (tb.pdepth[q] < cap ? tb.pdepth[q] : cap);
+            if (total <= static_cast<uint32_t>(kL2Cap) || cap == 0) break;
+            --cap;
+        }
+        uint32_t base = 0;
+        for (uint32_t q = 0; q < n_prefix; ++q) {
+            const uint32_t d = tb.pdepth[q] < cap ? tb.pdepth[q] : cap;
+            tb.pdepth[q] = d;
+            tb.pbase[q] = base;
+            base += 1u << d;
         }
     }
     __syncthreads();
     if (l) {
-        uint32_t rank = 0;
-        for (int s = 0; s < tid; ++s) rank += (tb.lens[s] == l);
-        const uint32_t code = tb.first[l] + rank;
-        tb.sorted[tb.offs[l] + rank] = static_cast<uint8_t>(tid);
+        const uint32_t e = make_entry<MODE>(tid, l, t.zero_point, t.scale);
         if (l <= kL1) {
             const uint32_t rev = __brev(code) >> (32 - l);        // first code bit -> bit 0
-            const uint32_t e = make_entry<MODE>(tid, l, t.zero_point, t.scale);
             for (uint32_t i = rev; i < (1u << kL1); i += (1u << l)) tb.lut[i] = e;
         } else {
-            const uint32_t prefix = code >> (l - kL1);
-            tb.lut[__brev(prefix) >> (32 - kL1)] = 0;             // long-code marker
+            const uint32_t extra = l - kL1;
+            const uint32_t prefix = code >> extra;
+            uint32_t depth = 0, base = 0;
+            if (have_l2) {
+                depth = tb.pdepth[prefix - first_prefix];
+                base = tb.pbase[prefix - first_prefix];
+            }
+            tb.lut[__brev(prefix) >> (32 - kL1)] = (depth << 8) | (base << 16);     // len 0: go to level 2
+            if (have_l2 && extra <= depth) {
+                const uint32_t suffix = code & ((1u << extra) - 1u);
+                const uint32_t rev = __brev(suffix) >> (32 - extra);
+                for (uint32_t i = rev; i < (1u << depth); i += (1u << extra)) tb.lut2[base + i] = e;
+            }
+            // longer codes keep the zero entry: canonical search
         }
     }
     __syncthreads();
 }
 
-// 64 stream bits starting at the dword that holds bit `p` (relative to byte
-// `base`), shifted so that bit p is bit 0: at least 33 valid bits.  The read
-// is clamped to the last 8 bytes of the (padded) stream.
-__device__ __forceinline__ uint64_t load_bits(const uint8_t *stream, uint32_t base, uint32_t p,
-                                              uint32_t last_off) {
-    uint32_t off = base + ((p >> 5) << 2);
-    off = off < last_off ? off : last_off;
-    const uint32_t *w = reinterpret_cast<const uint32_t *>(stream + off);
-    const uint64_t v = static_cast<uint64_t>(w[0]) | (static_cast<uint64_t>(w[1]) << 32);
-    return v >> (p & 31u);
-}
-
-// Second level: canonical search over the lengths above kL1.  `window` holds
-// the next 32 stream bits, first bit in bit 0.
+// Canonical search over the lengths above kL1.  `window` holds the next 32
+// stream bits, first bit in bit 0.
 template <int MODE>
-__device__ __noinline__ uint32_t decode_long(const Tables &tb, uint32_t window, uint32_t max_len,
-                                             int32_t z, float s) {
+__device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len,
+                                                  int32_t z, float s) {
     const uint32_t v = __brev(window);
     for (uint32_t l = kL1 + 1; l <= max_len; ++l) {
         const uint32_t d = (v >> (32 - l)) - tb.first[l];
@@ -147,88 +224,283 @@ __device__ __noinline__ uint32_t decode_long(const Tables &tb, uint32_t window, 
     return make_entry<MODE>(0, 1, z, s);     // not a code (corrupt stream): keep moving
 }
 
-// Per-lane reader of one segment.
-struct Reader {
+// Second-level lookup for a first-level miss e1; `window` holds the next >= 17
+// stream bits.  Returns an entry with len == 0 if the code is longer still.
+__device__ __forceinline__ uint32_t lookup_l2(const Tables &tb, uint32_t e1, uint32_t window) {
+    const uint32_t sub = __builtin_amdgcn_ubfe(window, kL1, (e1 >> 8) & 0xffu);
+    return tb.lut2[((e1 >> 16) + sub) & (kL2Cap - 1)];
+}
+
+// ---------------------------------------------------------------- scalar reader
+// Reads straight from global memory; used for segments whose size does not fit
+// the row path, for ragged tails, for codes too long for the tables and (for
+// now) by the GEMV.
+
+// 64 stream bits starting at the dword that holds absolute stream bit `pos`,
+// shifted so that bit pos is bit 0: at least 33 valid bits.  The read is
+// clamped to the last 8 bytes of the (padded) stream.
+__device__ __forceinline__ uint64_t load_bits(const uint8_t *stream, uint64_t pos, uint32_t last_off) {
+    uint32_t off = static_cast<uint32_t>(pos >> 5) << 2;
+    off = off < last_off ? off : last_off;
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(stream + off);
+    const uint64_t v = static_cast<uint64_t>(w[0]) | (static_cast<uint64_t>(w[1]) << 32);
+    return v >> (static_cast<uint32_t>(pos) & 31u);
+}
+
+struct ScalarReader {
     const uint8_t *stream;
-    uint32_t base;       // dword-aligned byte offset of the segment start
     uint32_t last_off;   // stream_bytes - 8
-    uint32_t p;          // bit position relative to base
+    uint64_t pos;        // absolute stream bit
     uint64_t buf;
 };
 
 template <int MODE>
-__device__ __forceinline__ uint32_t next_symbol(Reader &r, const Tables &tb, const DevTensor &t) {
+__device__ __forceinline__ uint32_t next_symbol(ScalarReader &r, const Tables &tb, const DevTensor &t) {
     uint32_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
-    if (__builtin_expect((e & 0xff00u) == 0, 0)) {
-        const uint64_t w = load_bits(r.stream, r.base, r.p, r.last_off);
-        e = decode_long<MODE>(tb, static_cast<uint32_t>(w), t.max_len, t.zero_point, t.scale);
-        r.p += (e >> 8) & 0xffu;
-        r.buf = load_bits(r.stream, r.base, r.p, r.last_off);
+    if (__builtin_expect((e & 0xffu) == 0, 0)) {
+        const uint32_t w = static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off));
+        e = lookup_l2(tb, e, w);
+        if ((e & 0xffu) == 0) e = decode_canonical<MODE>(tb, w, t.max_len, t.zero_point, t.scale);
+        r.pos += e & 0xffu;
+        r.buf = load_bits(r.stream, r.pos, r.last_off);
     } else {
-        const uint32_t len = (e >> 8) & 0xffu;
+        const uint32_t len = e & 0xffu;
         r.buf >>= len;
-        r.p += len;
+        r.pos += len;
     }
     return e;
 }
 
 template <int MODE> struct OutTraits;
-template <> struct OutTraits<kModeU8> { static constexpr int group = 16; static constexpr int ebits = 8; };
-template <> struct OutTraits<kModeU4> { static constexpr int group = 32; static constexpr int ebits = 4; };
-template <> struct OutTraits<kModeF32> { static constexpr int group = 4; static constexpr int ebits = 32; };
-template <> struct OutTraits<kModeBF16> { static constexpr int group = 8; static constexpr int ebits = 16; };
+template <> struct OutTraits<kModeU8> { static constexpr int ebits = 8; };
+template <> struct OutTraits<kModeU4> { static constexpr int ebits = 4; };
+template <> struct OutTraits<kModeF32> { static constexpr int ebits = 32; };
+template <> struct OutTraits<kModeBF16> { static constexpr int ebits = 16; };
 
-// Decode one segment and write it in the output type of MODE.
+// Symbols [i0, nsym) of segment k, element by element, starting at stream bit `pos`.
 template <int MODE>
-__device__ __forceinline__ void decode_segment(const DevTensor &t, const Tables &tb, uint32_t k) {
-    constexpr int G = OutTraits<MODE>::group;
-    const uint32_t C = t.chunk_symbols;
-    const uint64_t first_sym = static_cast<uint64_t>(k) * C;
-    const uint64_t left = t.n - first_sym;
-    const uint32_t nsym = left < C ? static_cast<uint32_t>(left) : C;
-    const uint64_t off_bits = t.offsets[k];
-    Reader r;
+__device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t i0, uint32_t nsym,
+                              uint64_t pos) {
+    ScalarReader r;
     r.stream = t.stream;
     r.last_off = t.stream_bytes - 8u;
-    r.base = static_cast<uint32_t>(off_bits >> 3) & ~3u;
-    r.p = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.base) << 3));
+    r.pos = pos;
     r.buf = 0;
-
-    // 16-byte stores need every segment to start on a 16-byte boundary
-    const bool vec_ok = ((static_cast<uint64_t>(C) * OutTraits<MODE>::ebits) & 127u) == 0;
+    const uint64_t first_sym = static_cast<uint64_t>(k) * t.chunk_symbols;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
-    uint32_t i = 0;
-    if (vec_ok) {
-        uint4 *dst = reinterpret_cast<uint4 *>(out8 + ((first_sym * OutTraits<MODE>::ebits) >> 3));
-        for (; i + G <= nsym; i += G) {
-            uint32_t v[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int j = 0; j < G; ++j) {
-                if (j % kBatch == 0) r.buf = load_bits(r.stream, r.base, r.p, r.last_off);
-                const uint32_t e = next_symbol<MODE>(r, tb, t);
-                if (MODE == kModeU8) v[j >> 2] |= (e & 0xffu) << ((j & 3) * 8);
-                if (MODE == kModeU4) v[j >> 3] |= (e & 0xfu) << ((j & 7) * 4);
-                if (MODE == kModeBF16) v[j >> 1] |= (j & 1) ? (e & 0xffff0000u) : (e >> 16);
-                if (MODE == kModeF32) v[j] = __float_as_uint(dequant(e & 0xffu, t.zero_point, t.scale));
-            }
-            *dst++ = make_uint4(v[0], v[1], v[2], v[3]);
-        }
-    }
-    // ragged tail, or segments that are not 16-byte aligned: element by element
     uint32_t pending = 0;     // low nibble waiting for its partner (packed 4-bit)
-    for (; i < nsym; ++i) {
-        r.buf = load_bits(r.stream, r.base, r.p, r.last_off);
+    for (uint32_t i = i0; i < nsym; ++i) {
+        if ((i - i0) % kTrio == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
         const uint32_t e = next_symbol<MODE>(r, tb, t);
         const uint64_t idx = first_sym + i;
-        if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(e);
+        const uint32_t sym = (e >> 8) & 0xffu;
+        if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
         if (MODE == kModeU4) {
-            if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((e & 0xfu) << 4));
-            else pending = e & 0xfu;
+            if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((sym & 0xfu) << 4));
+            else pending = sym & 0xfu;
         }
         if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(e >> 16);
-        if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(e & 0xffu, t.zero_point, t.scale);
+        if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, t.zero_point, t.scale);
     }
-    if (MODE == kModeU4 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
+    if (MODE == kModeU4 && nsym > i0 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
+}
+
+// ------------------------------------------------------------------ ring reader
+// Each lane keeps the next 48 bytes of its segment in a four-slot ring in LDS
+// (16-byte blocks, block j in slot j & 3, three of them resident) and the block
+// after those in registers.  Dwords 16 and 17 of the lane's ring row mirror
+// dwords 0 and 1, so a 96-bit read starting in the last ring dwords needs no wrap.
+struct RingReader {
+    const uint8_t *stream;
+    uint32_t *ring;        // this lane's ring row
+    uint32_t start16;      // byte offset of block 0 (16-byte aligned)
+    uint32_t last_blk;     // stream_bytes - 16
+    uint32_t p;            // bit position relative to block 0
+    uint32_t cur;          // block that held p at the last check
+    u32x4 nx;              // block cur + 3
+};
+
+__device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t start16, uint32_t last_blk, uint32_t blk) {
+    uint32_t off = start16 + (blk << 4);
+    off = off < last_blk ? off : last_blk;
+    return *(global_u4_ptr)(stream + off);
+}
+
+__device__ __forceinline__ void ring_init(RingReader &r, const DevTensor &t, uint64_t off_bits, uint32_t *ring_row) {
+    r.stream = t.stream;
+    r.ring = ring_row;
+    r.last_blk = t.stream_bytes - 16u;
+    r.start16 = static_cast<uint32_t>(off_bits >> 3) & ~15u;
+    r.p = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.start16) << 3));
+    r.cur = 0;
+    const u32x4 b0 = load_block(r.stream, r.start16, r.last_blk, 0);
+    const u32x4 b1 = load_block(r.stream, r.start16, r.last_blk, 1);
+    const u32x4 b2 = load_block(r.stream, r.start16, r.last_blk, 2);
+    r.nx = load_block(r.stream, r.start16, r.last_blk, 3);
+    // ring rows are only 4-byte aligned: dword stores
+    ring_row[0] = b0.x; ring_row[1] = b0.y; ring_row[2] = b0.z; ring_row[3] = b0.w;
+    ring_row[4] = b1.x; ring_row[5] = b1.y; ring_row[6] = b1.z; ring_row[7] = b1.w;
+    ring_row[8] = b2.x; ring_row[9] = b2.y; ring_row[10] = b2.z; ring_row[11] = b2.w;
+    ring_row[16] = b0.x; ring_row[17] = b0.y;
+}
+
+// Retire the blocks p has left behind.  A ring read is valid while p is less
+// than 192 bits past the end of block cur.  Between two checks kCheck symbols
+// are decoded and a symbol resolved by the two table levels is at most 17 bits
+// long, so every read in between starts at most (kCheck - 1) * 17 = 153 bits
+// (after the last symbol: 170) past the end of block cur.  A longer code (up
+// to 32 bits) runs its own check first; reads after it stay within
+// 32 + 9 * 17 = 185.
+__device__ __forceinline__ void ring_check(RingReader &r) {
+    const uint32_t nb = r.p >> 7;
+    while (nb != r.cur) {
+        const uint32_t slot = (r.cur + 3u) & 3u;
+        uint32_t *dst = r.ring + (slot << 2);
+        dst[0] = r.nx.x; dst[1] = r.nx.y; dst[2] = r.nx.z; dst[3] = r.nx.w;
+        if (slot == 0) { r.ring[16] = r.nx.x; r.ring[17] = r.nx.y; }
+        r.cur += 1;
+        r.nx = load_block(r.stream, r.start16, r.last_blk, r.cur + 3u);
+    }
+}
+
+// The next 64 stream bits, shifted left by two (62 of them survive): bits
+// 2..12 are the first-level table's byte offset of the code that starts at p.
+__device__ __forceinline__ uint64_t ring_read(const RingReader &r) {
+    const uint32_t d = (r.p >> 5) & 15u;
+    const uint32_t w0 = r.ring[d], w1 = r.ring[d + 1], w2 = r.ring[d + 2];
+    const uint32_t lo = __builtin_amdgcn_alignbit(w1, w0, r.p);     // uses p & 31
+    const uint32_t hi = __builtin_amdgcn_alignbit(w2, w1, r.p);
+    return ((static_cast<uint64_t>(hi) << 32) | lo) << 2;
+}
+
+__device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) {
+    return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
+}
+
+// One symbol from the window w, which holds at least 17 valid bits.  A fresh
+// window has 62; kGroup - 1 first-level symbols leave 62 - 44 = 18.  After a
+// longer symbol the window is read again, so the rest of the group starts from
+// 62 bits once more.
+template <int MODE>
+__device__ __forceinline__ uint32_t ring_symbol(RingReader &r, uint64_t &w, const Tables &tb, const DevTensor &t) {
+    uint32_t e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 2));
+    if (__builtin_expect((e & 0xffu) == 0, 0)) {
+        e = lookup_l2(tb, e, static_cast<uint32_t>(w >> 2));
+        if (__builtin_expect((e & 0xffu) == 0, 0)) {
+            // longer than the tables resolve: bring the ring up to date (see ring_check), then search
+            ring_check(r);
+            w = ring_read(r);
+            e = decode_canonical<MODE>(tb, static_cast<uint32_t>(w >> 2), t.max_len, t.zero_point, t.scale);
+        }
+        r.p += e & 0xffu;
+        w = ring_read(r);
+        e &= ~0xffu;                 // already consumed
+    }
+    w >>= (e & 63u);
+    r.p += e & 0xffu;
+    return e;
+}
+
+// The row path decodes `spb` symbols per step into a row of `dpb` dwords.
+template <int MODE> struct RowTraits;
+template <> struct RowTraits<kModeU8> { static constexpr int spb = 128, dpb = 32, spd = 4; };
+template <> struct RowTraits<kModeU4> { static constexpr int spb = 128, dpb = 16, spd = 8; };
+template <> struct RowTraits<kModeF32> { static constexpr int spb = 32, dpb = 32, spd = 1; };
+template <> struct RowTraits<kModeBF16> { static constexpr int spb = 64, dpb = 32, spd = 2; };
+
+// NSYM symbols (a whole number of output dwords) into dst[0 .. NSYM / spd).
+template <int MODE, int NSYM>
+__device__ __forceinline__ void decode_span(RingReader &r, const Tables &tb, const DevTensor &t, uint32_t *dst) {
+    constexpr int SPD = RowTraits<MODE>::spd;
+    static_assert(NSYM % SPD == 0, "span must fill whole dwords");
+    uint64_t w = 0;
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < NSYM; ++j) {
+        if (j % kCheck == 0) ring_check(r);
+        if (j % kGroup == 0) w = ring_read(r);
+        const uint32_t e = ring_symbol<MODE>(r, w, tb, t);
+        const uint32_t sym = (e >> 8) & 0xffu;
+        if (MODE == kModeU8) acc = (j % 4) ? (acc | (sym << ((j % 4) * 8))) : sym;
+        if (MODE == kModeU4) acc = (j % 8) ? (acc | ((sym & 0xfu) << ((j % 8) * 4))) : (sym & 0xfu);
+        // bytes 2,3 of the entry are the bf16 value: low half from the even symbol, high half from the odd one
+        if (MODE == kModeBF16) acc = (j % 2) ? __builtin_amdgcn_perm(e, acc, 0x07060100u) : (e >> 16);
+        if (MODE == kModeF32) acc = __float_as_uint(dequant(sym, t.zero_point, t.scale));
+        if (j % SPD == SPD - 1) dst[j / SPD] = acc;
+    }
+}
+
+// Decode the workgroup's segments block by block into the wave's LDS tile (one
+// row per lane) and write the tile out row-wise, so that every store
+// instruction covers whole rows of 4 * dpb bytes.
+template <int MODE>
+__device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem *wms, uint32_t first_chunk) {
+    constexpr int SPB = RowTraits<MODE>::spb;
+    constexpr int DPB = RowTraits<MODE>::dpb;
+    constexpr int SPD = RowTraits<MODE>::spd;
+    constexpr int SPAN = kCheck * (SPD > 2 ? SPD / 2 : 1);   // symbols per loop trip: whole dwords, whole check intervals
+    constexpr int TRIPS = SPB / SPAN;
+    constexpr int REST = SPB - TRIPS * SPAN;
+    constexpr uint32_t LPR = DPB / 4;                 // lanes that store one row
+    constexpr uint32_t RPI = 64 / LPR;                // rows per store instruction
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
+    WaveMem &wm = wms[wave];
+    const uint32_t wave_first = first_chunk + wave * 64u;
+    if (wave_first >= t.n_chunks) return;
+    const uint32_t C = t.chunk_symbols;
+    const uint32_t blocks_total = C / SPB;
+    const uint32_t k = wave_first + lane;
+    const bool active = k < t.n_chunks;
+    uint32_t nsym = 0;
+    RingReader r;
+    r.stream = t.stream;
+    r.last_blk = t.stream_bytes - 16u;
+    r.p = 0;
+    r.start16 = 0;
+    r.cur = 0;
+    r.nx = u32x4{0u, 0u, 0u, 0u};
+    r.ring = wm.ring + lane * kRingStride;
+    if (active) {
+        const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
+        nsym = left < C ? static_cast<uint32_t>(left) : C;
+        ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
+    }
+    const uint32_t my_blocks = nsym / SPB;
+    const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * OutTraits<MODE>::ebits) >> 3;
+    uint8_t *out8 = static_cast<uint8_t *>(t.out);
+    uint32_t *my_row = wm.tile + lane * kTileStride;
+
+    for (uint32_t bs = 0; bs < blocks_total; ++bs) {
+        if (bs < my_blocks) {
+            uint32_t *dst = my_row;
+#pragma unroll 1
+            for (int trip = 0; trip < TRIPS; ++trip) {
+                decode_span<MODE, SPAN>(r, tb, t, dst);
+                dst += SPAN / SPD;
+            }
+            if constexpr (REST > 0) decode_span<MODE, REST>(r, tb, t, dst);
+        }
+        wave_sync_lds();
+#pragma unroll
+        for (uint32_t it = 0; it < 64 / RPI; ++it) {
+            const uint32_t rr = it * RPI + lane / LPR;
+            const uint32_t piece = lane % LPR;
+            const uint32_t *src = wm.tile + rr * kTileStride + piece * 4u;
+            const u32x4 v = {src[0], src[1], src[2], src[3]};
+            const uint32_t kk = wave_first + rr;
+            if (kk < t.n_chunks) {
+                const uint64_t left = t.n - static_cast<uint64_t>(kk) * C;
+                const uint32_t blocks_kk = (left < C ? static_cast<uint32_t>(left) : C) / SPB;
+                if (bs < blocks_kk)
+                    *(global_u4_wptr)(out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * (DPB * 4u) + piece * 16u) = v;
+            }
+        }
+        wave_sync_lds();
+    }
+    // symbols of a shorter last segment that do not fill a block
+    if (active && my_blocks * SPB < nsym)
+        decode_scalar<MODE>(t, tb, k, my_blocks * SPB, nsym, (static_cast<uint64_t>(r.start16) << 3) + r.p);
 }
 
 // Decode one segment straight into dot products with x.  A segment covers one
@@ -240,12 +512,10 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     const uint64_t first_sym = static_cast<uint64_t>(k) * C;
     const uint64_t left = t.n - first_sym;
     const uint32_t nsym = left < C ? static_cast<uint32_t>(left) : C;
-    const uint64_t off_bits = t.offsets[k];
-    Reader r;
+    ScalarReader r;
     r.stream = t.stream;
     r.last_off = t.stream_bytes - 8u;
-    r.base = static_cast<uint32_t>(off_bits >> 3) & ~3u;
-    r.p = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.base) << 3));
+    r.pos = t.offsets[k];
     r.buf = 0;
 
     uint32_t row = static_cast<uint32_t>(first_sym / t.cols);
@@ -255,10 +525,10 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     float acc = 0.0f;
     float head = 0.0f, tail = 0.0f;
     for (uint32_t i = 0; i < nsym; ++i) {
-        if (i % kBatch == 0) r.buf = load_bits(r.stream, r.base, r.p, r.last_off);
+        if (i % kTrio == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
         const uint32_t e = next_symbol<MODE>(r, tb, t);
         const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
-        acc = fmaf(static_cast<float>(static_cast<int32_t>(e & 0xffu) - t.zero_point), xv, acc);
+        acc = fmaf(static_cast<float>(static_cast<int32_t>((e >> 8) & 0xffu) - t.zero_point), xv, acc);
         if (++col == t.cols) {
             if (first_fragment && start_col != 0) {
                 head = acc;                                  // row began in an earlier segment
@@ -284,26 +554,42 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 }
 
 template <int MODE>
-__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, Tables &tb) {
+__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, Tables &tb, WaveMem *wms) {
     build_tables<MODE>(t, tb);
-    const uint32_t k = first_chunk + threadIdx.x;
-    if (k >= t.n_chunks) return;
-    if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) gemv_segment<MODE>(t, tb, k);
-    else decode_segment<MODE>(t, tb, k);
+    if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
+        const uint32_t k = first_chunk + threadIdx.x;
+        if (k < t.n_chunks) gemv_segment<MODE>(t, tb, k);
+    } else {
+        if (t.chunk_symbols % RowTraits<MODE>::spb == 0) {
+            decode_rows<MODE>(t, tb, wms, first_chunk);
+        } else {                                             // segment size does not tile into blocks
+            const uint32_t k = first_chunk + threadIdx.x;
+            if (k < t.n_chunks) {
+                const uint64_t left = t.n - static_cast<uint64_t>(k) * t.chunk_symbols;
+                const uint32_t nsym = left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols;
+                decode_scalar<MODE>(t, tb, k, 0, nsym, t.offsets[k]);
+            }
+        }
+    }
 }
+
+// The GEMV kernels need the tables only; the others also the per-wave buffers.
+template <int MODE> struct SmemFor { Tables tb; WaveMem wm[kWaves]; };
+template <> struct SmemFor<kModeGemvF32> { Tables tb; WaveMem wm[1]; };
+template <> struct SmemFor<kModeGemvBF16> { Tables tb; WaveMem wm[1]; };
 
 template <int MODE>
 __global__ __launch_bounds__(kWG) void k_single(const DevTensor t) {
-    __shared__ Tables tb;
-    run_item<MODE>(t, blockIdx.x * kWG, tb);
+    __shared__ SmemFor<MODE> sm;
+    run_item<MODE>(t, blockIdx.x * kWG, sm.tb, sm.wm);
 }
 
 template <int MODE>
 __global__ __launch_bounds__(kWG) void k_batch(const DevTensor *__restrict__ tensors,
                                                const WorkItem *__restrict__ items) {
-    __shared__ Tables tb;
+    __shared__ SmemFor<MODE> sm;
     const WorkItem it = items[blockIdx.x];
-    run_item<MODE>(tensors[it.tensor], it.first, tb);
+    run_item<MODE>(tensors[it.tensor], it.first, sm.tb, sm.wm);
 }
 
 // Second stage of the GEMV: rows that straddle segments are summed in segment order.
@@ -325,13 +611,15 @@ __device__ __forceinline__ void fix_row(const DevTensor &t, uint32_t row) {
     else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
 }
 
+constexpr int kFixWG = 256;
+
 template <int MODE>
-__global__ __launch_bounds__(kWG) void k_fix_single(const DevTensor t) {
-    fix_row<MODE>(t, blockIdx.x * kWG + threadIdx.x);
+__global__ __launch_bounds__(kFixWG) void k_fix_single(const DevTensor t) {
+    fix_row<MODE>(t, blockIdx.x * kFixWG + threadIdx.x);
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kWG) void k_fix_batch(const DevTensor *__restrict__ tensors,
+__global__ __launch_bounds__(kFixWG) void k_fix_batch(const DevTensor *__restrict__ tensors,
                                                    const WorkItem *__restrict__ items) {
     const WorkItem it = items[blockIdx.x];
     fix_row<MODE>(tensors[it.tensor], it.first + threadIdx.x);
@@ -443,9 +731,9 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     dispatch_mode(mode, [&](auto m) { hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(kWG), 0, s, dt); });
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
-        const unsigned g2 = (dt.rows + kWG - 1) / kWG;
-        if (mode == kModeGemvF32) hipLaunchKernelGGL(k_fix_single<kModeGemvF32>, dim3(g2), dim3(kWG), 0, s, dt);
-        else hipLaunchKernelGGL(k_fix_single<kModeGemvBF16>, dim3(g2), dim3(kWG), 0, s, dt);
+        const unsigned g2 = (dt.rows + kFixWG - 1) / kFixWG;
+        if (mode == kModeGemvF32) hipLaunchKernelGGL(k_fix_single<kModeGemvF32>, dim3(g2), dim3(kFixWG), 0, s, dt);
+        else hipLaunchKernelGGL(k_fix_single<kModeGemvBF16>, dim3(g2), dim3(kFixWG), 0, s, dt);
         if (!hip_ok(hipGetLastError(), "launch row-sum kernel")) return ENTRO_ERR_DEVICE;
     }
     return ENTRO_OK;
@@ -466,7 +754,7 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
         const uint64_t nc = entro_num_chunks(ts[i].n, ts[i].chunk_symbols);
         items += (nc + kWG - 1) / kWG;
         if (op == ENTRO_OP_GEMV && ts[i].cols && (ts[i].chunk_symbols % ts[i].cols) != 0) {
-            fix += (static_cast<uint64_t>(ts[i].rows) + kWG - 1) / kWG;
+            fix += (static_cast<uint64_t>(ts[i].rows) + kFixWG - 1) / kFixWG;
             partial_floats += 2 * nc;
         }
     }
@@ -543,7 +831,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
-            for (uint32_t r = 0; r < dts[i].rows; r += kWG) fix[n_fix++] = WorkItem{i, r};
+            for (uint32_t r = 0; r < dts[i].rows; r += kFixWG) fix[n_fix++] = WorkItem{i, r};
         }
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -580,8 +868,8 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     });
     if (!hip_ok(hipGetLastError(), "launch batched decode kernel")) return ENTRO_ERR_DEVICE;
     if (plan->n_fix) {
-        if (mode == kModeGemvF32) hipLaunchKernelGGL(k_fix_batch<kModeGemvF32>, dim3(plan->n_fix), dim3(kWG), 0, s, dts, fix);
-        else hipLaunchKernelGGL(k_fix_batch<kModeGemvBF16>, dim3(plan->n_fix), dim3(kWG), 0, s, dts, fix);
+        if (mode == kModeGemvF32) hipLaunchKernelGGL(k_fix_batch<kModeGemvF32>, dim3(plan->n_fix), dim3(kFixWG), 0, s, dts, fix);
+        else hipLaunchKernelGGL(k_fix_batch<kModeGemvBF16>, dim3(plan->n_fix), dim3(kFixWG), 0, s, dts, fix);
         if (!hip_ok(hipGetLastError(), "launch batched row-sum kernel")) return ENTRO_ERR_DEVICE;
     }
     return ENTRO_OK;
