@@ -4,15 +4,15 @@
 // EntroLLM ("Segmentation for parallel Huffman decoding", Fig. 3) cuts the
 // encoded parameter space into segments with known boundaries and decodes
 // them independently; here a segment is a fixed number of symbols and one
-// GPU lane owns one segment, so a 704-lane workgroup decodes 704 consecutive
+// GPU lane owns one segment, so a 640-lane workgroup decodes 640 consecutive
 // segments of one tensor with one shared set of lookup tables in LDS.
 //
 // Data flow of the decode / dequant kernels, per lane:
-//   HBM --16-byte blocks--> four-slot ring in LDS --96-bit reads--> 62-bit window
-//   window --11 bits--> first-level table (LDS) --> symbol, length, bf16 value
-//   symbols --packed--> the lane's 128-byte row of the wave's LDS tile --> HBM,
-// the tile being written out row-wise so that every global store instruction
-// of a wave covers whole 128-byte lines.
+//   HBM --16-byte blocks--> four-slot ring in LDS --unaligned 64-bit reads--> bit window
+//   window --11 bits--> first-level table (LDS, 64-bit entries holding up to
+//   three decoded, already dequantised symbols) --one unaligned 64-bit write-->
+//   the lane's 128-byte row of the wave's LDS tile --row-wise--> HBM,
+// so that every global store instruction of a wave covers whole 128-byte lines.
 #include "entro.h"
 
 #include <hip/hip_runtime.h>
@@ -21,23 +21,23 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
-#include <utility>
 #include <vector>
 
 namespace {
 
-constexpr int kWG = 704;                 // lanes (= segments) per workgroup: 11 waves fill the 160 KB of LDS
+constexpr int kWG = 640;                 // lanes (= segments) per workgroup: 10 waves fill the 160 KB of LDS
 constexpr int kWaves = kWG / 64;
-constexpr int kL1 = 11;                  // bits resolved by the first-level table
+constexpr int kL1 = 11;                  // stream bits that index the first-level table
 constexpr uint32_t kL1Mask = (1u << kL1) - 1u;
-constexpr int kL2Cap = 1024;             // second-level entries (all long prefixes together)
+constexpr int kL2Cap = 512;              // second-level entries (all long prefixes together)
 constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 17 bits
 constexpr int kL2MaxPrefixes = 64;       // more long prefixes than this: second level unused
-constexpr int kGroup = 5;                // symbols per ring read: 62 valid bits >= 4 * 11 + 17
-constexpr int kCheck = 10;               // symbols between two refill checks (see ring_check)
-constexpr int kTrio = 3;                 // scalar reader: symbols per 64-bit load, 64 - 31 >= 3 * kL1
+constexpr int kGroup = 3;                // table probes per ring read: 54 valid bits >= 2 * 17 + 17
+constexpr int kTripGroups = 4;           // ring reads between two refill checks (see ring_check)
+constexpr int kScalarProbes = 3;         // scalar reader: probes per 64-bit load, 33 valid bits >= 3 * kL1
 constexpr int kRingStride = 19;          // dwords per lane: 4 x 16-byte slots, 2 mirror dwords, pad (odd)
-constexpr int kTileStride = 33;          // dwords per lane in the output tile: a 128-byte row plus one (odd)
+constexpr int kRowBytes = 128;           // output row per lane and block
+constexpr int kTileStride = 35;          // dwords per lane in the output tile: row, 8 bytes of slack, pad (odd)
 constexpr uint32_t kMaxChunkSymbols = 1u << 20;
 
 // What the kernels read about one tensor.  Lives in kernel arguments (single
@@ -69,18 +69,28 @@ struct WorkItem {
 
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5 };
 
+// Per mode: bytes one decoded symbol occupies in a table entry and in the LDS
+// tile, most symbols one entry carries, symbols per 128-byte tile row.
+template <int MODE> struct Elem { static constexpr int size = 1, max_syms = 6; };      // symbol values
+template <> struct Elem<kModeBF16> { static constexpr int size = 2, max_syms = 3; };   // dequantised bf16
+template <> struct Elem<kModeF32> { static constexpr int size = 4, max_syms = 1; };    // dequantised fp32
+
 // Lookup tables of one workgroup (LDS).
-// Symbol entry: len | symbol << 8 | payload << 16 (the length sits in the low
-// byte so that it can feed a shift directly; payload = bf16 of the dequantised
-// value in bf16 mode).
-// First level: indexed by the next kL1 stream bits.  len == 0 marks a prefix
-// whose codes are longer than kL1 bits; the entry then is
-// depth << 8 | base << 16: the prefix owns lut2[base .. base + 2^depth).
-// Second level: indexed by the following `depth` stream bits; len == 0 there
-// sends the lane to the canonical search (first / cnt / offs / sorted).
+// Symbol entry (64 bits): bits 0..47 up to max_syms decoded elements, first one
+// lowest; bits 48..55 the stream bits they take together; bits 56..63 the bytes
+// they occupy.  Writing the entry as it is to the output position stores the
+// elements; the two control bytes land behind them and are overwritten by the
+// next entry.
+// First level: indexed by the next kL1 stream bits, holds every run of whole
+// codes that fits into them.  A zero length marks a prefix whose first code is
+// longer than kL1 bits; bits 0..15 then are the base and bits 16..23 the depth
+// of the prefix's block in the second level.
+// Second level: one symbol per entry, indexed by the following `depth` stream
+// bits; a zero length there sends the lane to the canonical search
+// (first / cnt / offs / sorted).
 struct alignas(16) Tables {
-    uint32_t lut[1 << kL1];
-    uint32_t lut2[kL2Cap];
+    uint64_t lut[1 << kL1];
+    uint64_t lut2[kL2Cap];
     uint32_t cnt[ENTRO_MAX_CODE_LEN + 2];
     uint32_t first[ENTRO_MAX_CODE_LEN + 2];
     uint32_t offs[ENTRO_MAX_CODE_LEN + 2];
@@ -99,8 +109,11 @@ struct alignas(16) WaveMem {
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef const u32x4 __attribute__((address_space(1))) *global_u4_ptr;
 typedef u32x4 __attribute__((address_space(1))) *global_u4_wptr;
+typedef u32x2 __attribute__((address_space(1))) *global_u2_wptr;
+struct __attribute__((packed)) Packed64 { uint64_t v; };      // 64-bit LDS access at any byte address
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -113,11 +126,23 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
 }
 
 template <int MODE>
-__device__ __forceinline__ uint32_t make_entry(uint32_t sym, uint32_t len, int32_t z, float s) {
-    uint32_t e = len | (sym << 8);
-    if (MODE == kModeBF16) e |= bf16_bits(dequant(sym, z, s)) << 16;
-    return e;
+__device__ __forceinline__ uint64_t make_elem(uint32_t sym, int32_t z, float s) {
+    if (MODE == kModeBF16) return bf16_bits(dequant(sym, z, s));
+    if (MODE == kModeF32) return __float_as_uint(dequant(sym, z, s));
+    return sym;
 }
+
+__device__ __forceinline__ uint64_t pack_entry(uint64_t payload, uint32_t len, uint32_t bytes) {
+    return payload | (static_cast<uint64_t>(len) << 48) | (static_cast<uint64_t>(bytes) << 56);
+}
+
+template <int MODE>
+__device__ __forceinline__ uint64_t make_entry(uint32_t sym, uint32_t len, int32_t z, float s) {
+    return pack_entry(make_elem<MODE>(sym, z, s), len, Elem<MODE>::size);
+}
+
+__device__ __forceinline__ uint32_t entry_len(uint64_t e) { return static_cast<uint32_t>(e >> 48) & 0xffu; }
+__device__ __forceinline__ uint32_t entry_bytes(uint64_t e) { return static_cast<uint32_t>(e >> 56); }
 
 __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -125,16 +150,16 @@ __device__ __forceinline__ void wave_sync_lds() {
 }
 
 // Canonical code tables and both lookup levels, built from the 256 (or 16)
-// code lengths by the whole workgroup.
+// code lengths by the whole workgroup.  `lut1` is scratch for a single-symbol
+// table of 2^kL1 words (len | symbol << 8, zero for long prefixes).
 template <int MODE>
-__device__ void build_tables(const DevTensor &t, Tables &tb) {
+__device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
     const int tid = threadIdx.x;
     const uint32_t l = tid < 256 ? t.len[tid] : 0u;
     if (tid < 256) tb.lens[tid] = static_cast<uint8_t>(l);
     if (tid < ENTRO_MAX_CODE_LEN + 2) tb.cnt[tid] = 0;
     if (tid < kL2MaxPrefixes) tb.pdepth[tid] = 0;
-    const uint32_t filler = make_entry<MODE>(0, 1, t.zero_point, t.scale);
-    for (int i = tid; i < (1 << kL1); i += kWG) tb.lut[i] = filler;
+    for (int i = tid; i < (1 << kL1); i += kWG) lut1[i] = 1u;            // symbol 0, one bit: filler of incomplete codes
     for (int i = tid; i < kL2Cap; i += kWG) tb.lut2[i] = 0;
     __syncthreads();
     if (l) atomicAdd(&tb.cnt[l], 1u);
@@ -187,26 +212,53 @@ __device__ void build_tables(const DevTensor &t, Tables &tb) {
     }
     __syncthreads();
     if (l) {
-        const uint32_t e = make_entry<MODE>(tid, l, t.zero_point, t.scale);
         if (l <= kL1) {
             const uint32_t rev = __brev(code) >> (32 - l);        // first code bit -> bit 0
-            for (uint32_t i = rev; i < (1u << kL1); i += (1u << l)) tb.lut[i] = e;
+            const uint32_t e1 = l | (static_cast<uint32_t>(tid) << 8);
+            for (uint32_t i = rev; i < (1u << kL1); i += (1u << l)) lut1[i] = e1;
         } else {
             const uint32_t extra = l - kL1;
             const uint32_t prefix = code >> extra;
-            uint32_t depth = 0, base = 0;
+            lut1[__brev(prefix) >> (32 - kL1)] = 0;              // first code longer than kL1 bits
             if (have_l2) {
+                const uint32_t depth = tb.pdepth[prefix - first_prefix];
+                const uint32_t base = tb.pbase[prefix - first_prefix];
+                if (extra <= depth) {
+                    const uint64_t e = make_entry<MODE>(tid, l, t.zero_point, t.scale);
+                    const uint32_t suffix = code & ((1u << extra) - 1u);
+                    const uint32_t rev = __brev(suffix) >> (32 - extra);
+                    for (uint32_t i = rev; i < (1u << depth); i += (1u << extra)) tb.lut2[base + i] = e;
+                }
+                // longer codes keep the zero entry: canonical search
+            }
+        }
+    }
+    __syncthreads();
+    // first level: all whole codes that fit into the kL1 index bits
+    for (uint32_t i = tid; i < (1u << kL1); i += kWG) {
+        uint32_t pos = 0, count = 0;
+        uint64_t payload = 0;
+        while (count < static_cast<uint32_t>(Elem<MODE>::max_syms)) {
+            const uint32_t e1 = lut1[i >> pos];
+            const uint32_t len1 = e1 & 0xffu;
+            if (len1 == 0 || pos + len1 > static_cast<uint32_t>(kL1)) break;
+            payload |= make_elem<MODE>(e1 >> 8, t.zero_point, t.scale) << (count * Elem<MODE>::size * 8);
+            pos += len1;
+            ++count;
+        }
+        uint64_t e;
+        if (count) {
+            e = pack_entry(payload, pos, count * Elem<MODE>::size);
+        } else {                                                  // long prefix: where its second-level block is
+            uint32_t depth = 0, base = 0;
+            const uint32_t prefix = __brev(i) >> (32 - kL1);
+            if (have_l2 && prefix >= first_prefix) {
                 depth = tb.pdepth[prefix - first_prefix];
                 base = tb.pbase[prefix - first_prefix];
             }
-            tb.lut[__brev(prefix) >> (32 - kL1)] = (depth << 8) | (base << 16);     // len 0: go to level 2
-            if (have_l2 && extra <= depth) {
-                const uint32_t suffix = code & ((1u << extra) - 1u);
-                const uint32_t rev = __brev(suffix) >> (32 - extra);
-                for (uint32_t i = rev; i < (1u << depth); i += (1u << extra)) tb.lut2[base + i] = e;
-            }
-            // longer codes keep the zero entry: canonical search
+            e = base | (depth << 16);
         }
+        tb.lut[i] = e;
     }
     __syncthreads();
 }
@@ -214,7 +266,7 @@ __device__ void build_tables(const DevTensor &t, Tables &tb) {
 // Canonical search over the lengths above kL1.  `window` holds the next 32
 // stream bits, first bit in bit 0.
 template <int MODE>
-__device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len,
+__device__ __noinline__ uint64_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len,
                                                   int32_t z, float s) {
     const uint32_t v = __brev(window);
     for (uint32_t l = kL1 + 1; l <= max_len; ++l) {
@@ -225,16 +277,16 @@ __device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t win
 }
 
 // Second-level lookup for a first-level miss e1; `window` holds the next >= 17
-// stream bits.  Returns an entry with len == 0 if the code is longer still.
-__device__ __forceinline__ uint32_t lookup_l2(const Tables &tb, uint32_t e1, uint32_t window) {
-    const uint32_t sub = __builtin_amdgcn_ubfe(window, kL1, (e1 >> 8) & 0xffu);
-    return tb.lut2[((e1 >> 16) + sub) & (kL2Cap - 1)];
+// stream bits.  Returns an entry of zero length if the code is longer still.
+__device__ __forceinline__ uint64_t lookup_l2(const Tables &tb, uint64_t e1, uint32_t window) {
+    const uint32_t m = static_cast<uint32_t>(e1);
+    const uint32_t sub = __builtin_amdgcn_ubfe(window, kL1, (m >> 16) & 0xffu);
+    return tb.lut2[((m & 0xffffu) + sub) & (kL2Cap - 1)];
 }
 
 // ---------------------------------------------------------------- scalar reader
 // Reads straight from global memory; used for segments whose size does not fit
-// the row path, for ragged tails, for codes too long for the tables and (for
-// now) by the GEMV.
+// the row path, for shorter last segments and (for now) by the GEMV.
 
 // 64 stream bits starting at the dword that holds absolute stream bit `pos`,
 // shifted so that bit pos is bit 0: at least 33 valid bits.  The read is
@@ -254,17 +306,18 @@ struct ScalarReader {
     uint64_t buf;
 };
 
+// One table entry (one or more symbols) from the scalar reader.
 template <int MODE>
-__device__ __forceinline__ uint32_t next_symbol(ScalarReader &r, const Tables &tb, const DevTensor &t) {
-    uint32_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
-    if (__builtin_expect((e & 0xffu) == 0, 0)) {
+__device__ __forceinline__ uint64_t next_entry(ScalarReader &r, const Tables &tb, const DevTensor &t) {
+    uint64_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
+    if (__builtin_expect(entry_len(e) == 0, 0)) {
         const uint32_t w = static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off));
         e = lookup_l2(tb, e, w);
-        if ((e & 0xffu) == 0) e = decode_canonical<MODE>(tb, w, t.max_len, t.zero_point, t.scale);
-        r.pos += e & 0xffu;
+        if (entry_len(e) == 0) e = decode_canonical<MODE>(tb, w, t.max_len, t.zero_point, t.scale);
+        r.pos += entry_len(e);
         r.buf = load_bits(r.stream, r.pos, r.last_off);
     } else {
-        const uint32_t len = e & 0xffu;
+        const uint32_t len = entry_len(e);
         r.buf >>= len;
         r.pos += len;
     }
@@ -277,45 +330,51 @@ template <> struct OutTraits<kModeU4> { static constexpr int ebits = 4; };
 template <> struct OutTraits<kModeF32> { static constexpr int ebits = 32; };
 template <> struct OutTraits<kModeBF16> { static constexpr int ebits = 16; };
 
-// Symbols [i0, nsym) of segment k, element by element, starting at stream bit `pos`.
+// All nsym symbols of segment k, element by element.
 template <int MODE>
-__device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t i0, uint32_t nsym,
-                              uint64_t pos) {
+__device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t nsym) {
     ScalarReader r;
     r.stream = t.stream;
     r.last_off = t.stream_bytes - 8u;
-    r.pos = pos;
+    r.pos = t.offsets[k];
     r.buf = 0;
     const uint64_t first_sym = static_cast<uint64_t>(k) * t.chunk_symbols;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
     uint32_t pending = 0;     // low nibble waiting for its partner (packed 4-bit)
-    for (uint32_t i = i0; i < nsym; ++i) {
-        if ((i - i0) % kTrio == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint32_t e = next_symbol<MODE>(r, tb, t);
-        const uint64_t idx = first_sym + i;
-        const uint32_t sym = (e >> 8) & 0xffu;
-        if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
-        if (MODE == kModeU4) {
-            if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((sym & 0xfu) << 4));
-            else pending = sym & 0xfu;
+    uint32_t i = 0;
+    for (uint32_t probe = 0; i < nsym; ++probe) {
+        if (probe % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
+        const uint64_t e = next_entry<MODE>(r, tb, t);
+        const uint32_t count = entry_bytes(e) / Elem<MODE>::size;
+        for (uint32_t c = 0; c < count && i < nsym; ++c, ++i) {
+            const uint64_t idx = first_sym + i;
+            const uint32_t v = static_cast<uint32_t>(e >> (c * Elem<MODE>::size * 8));
+            if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(v);
+            if (MODE == kModeU4) {
+                if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((v & 0xfu) << 4));
+                else pending = v & 0xfu;
+            }
+            if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(v);
+            if (MODE == kModeF32) reinterpret_cast<uint32_t *>(t.out)[idx] = v;
         }
-        if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(e >> 16);
-        if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, t.zero_point, t.scale);
     }
-    if (MODE == kModeU4 && nsym > i0 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
+    if (MODE == kModeU4 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
 }
 
 // ------------------------------------------------------------------ ring reader
 // Each lane keeps the next 48 bytes of its segment in a four-slot ring in LDS
 // (16-byte blocks, block j in slot j & 3, three of them resident) and the block
-// after those in registers.  Dwords 16 and 17 of the lane's ring row mirror
-// dwords 0 and 1, so a 96-bit read starting in the last ring dwords needs no wrap.
+// after those in registers.  Bytes 64..71 of the lane's ring row mirror bytes
+// 0..7, so a 64-bit read starting anywhere in the ring needs no wrap.
+// The lane tracks q = p - 3, p being its bit position relative to block 0: a
+// window read at bit q carries three stale low bits, which makes bits 3..13 the
+// first-level table's byte offset of the code that starts at p.
 struct RingReader {
     const uint8_t *stream;
-    uint32_t *ring;        // this lane's ring row
+    uint8_t *ring;         // this lane's ring row
     uint32_t start16;      // byte offset of block 0 (16-byte aligned)
     uint32_t last_blk;     // stream_bytes - 16
-    uint32_t p;            // bit position relative to block 0
+    uint32_t q;            // p - 3 (wraps below zero for p < 3, which the mirror absorbs)
     uint32_t cur;          // block that held p at the last check
     u32x4 nx;              // block cur + 3
 };
@@ -328,121 +387,89 @@ __device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t star
 
 __device__ __forceinline__ void ring_init(RingReader &r, const DevTensor &t, uint64_t off_bits, uint32_t *ring_row) {
     r.stream = t.stream;
-    r.ring = ring_row;
+    r.ring = reinterpret_cast<uint8_t *>(ring_row);
     r.last_blk = t.stream_bytes - 16u;
     r.start16 = static_cast<uint32_t>(off_bits >> 3) & ~15u;
-    r.p = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.start16) << 3));
+    r.q = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.start16) << 3)) - 3u;
     r.cur = 0;
     const u32x4 b0 = load_block(r.stream, r.start16, r.last_blk, 0);
     const u32x4 b1 = load_block(r.stream, r.start16, r.last_blk, 1);
     const u32x4 b2 = load_block(r.stream, r.start16, r.last_blk, 2);
     r.nx = load_block(r.stream, r.start16, r.last_blk, 3);
-    // ring rows are only 4-byte aligned: dword stores
     ring_row[0] = b0.x; ring_row[1] = b0.y; ring_row[2] = b0.z; ring_row[3] = b0.w;
     ring_row[4] = b1.x; ring_row[5] = b1.y; ring_row[6] = b1.z; ring_row[7] = b1.w;
     ring_row[8] = b2.x; ring_row[9] = b2.y; ring_row[10] = b2.z; ring_row[11] = b2.w;
     ring_row[16] = b0.x; ring_row[17] = b0.y;
 }
 
-// Retire the blocks p has left behind.  A ring read is valid while p is less
-// than 192 bits past the end of block cur.  Between two checks kCheck symbols
-// are decoded and a symbol resolved by the two table levels is at most 17 bits
-// long, so every read in between starts at most (kCheck - 1) * 17 = 153 bits
-// (after the last symbol: 170) past the end of block cur.  A longer code (up
-// to 32 bits) runs its own check first; reads after it stay within
-// 32 + 9 * 17 = 185.
+// Retire the blocks p has left behind.  A ring read at p touches the 9 bytes
+// from the one holding bit p - 3 on, so it is valid while p is at most 184
+// bits past the end of block cur.  Between two checks kTripGroups ring reads
+// happen, each followed by kGroup probes of at most 17 bits (both table
+// levels), so the last read starts at most (kTripGroups - 1) * kGroup * 17 =
+// 153 bits past the end of block cur.  A longer code (up to 32 bits) runs its
+// own check first and reads again afterwards; later reads stay within
+// 32 + 9 * 17 = 185 - 1.
 __device__ __forceinline__ void ring_check(RingReader &r) {
-    const uint32_t nb = r.p >> 7;
+    const uint32_t nb = (r.q + 3u) >> 7;
+    uint32_t *ring32 = reinterpret_cast<uint32_t *>(r.ring);
     while (nb != r.cur) {
         const uint32_t slot = (r.cur + 3u) & 3u;
-        uint32_t *dst = r.ring + (slot << 2);
+        uint32_t *dst = ring32 + (slot << 2);
         dst[0] = r.nx.x; dst[1] = r.nx.y; dst[2] = r.nx.z; dst[3] = r.nx.w;
-        if (slot == 0) { r.ring[16] = r.nx.x; r.ring[17] = r.nx.y; }
+        if (slot == 0) { ring32[16] = r.nx.x; ring32[17] = r.nx.y; }
         r.cur += 1;
         r.nx = load_block(r.stream, r.start16, r.last_blk, r.cur + 3u);
     }
 }
 
-// The next 64 stream bits, shifted left by two (62 of them survive): bits
-// 2..12 are the first-level table's byte offset of the code that starts at p.
+// The stream from bit q = p - 3 on: at least 54 valid bits above the three stale ones.
 __device__ __forceinline__ uint64_t ring_read(const RingReader &r) {
-    const uint32_t d = (r.p >> 5) & 15u;
-    const uint32_t w0 = r.ring[d], w1 = r.ring[d + 1], w2 = r.ring[d + 2];
-    const uint32_t lo = __builtin_amdgcn_alignbit(w1, w0, r.p);     // uses p & 31
-    const uint32_t hi = __builtin_amdgcn_alignbit(w2, w1, r.p);
-    return ((static_cast<uint64_t>(hi) << 32) | lo) << 2;
+    const uint64_t v = reinterpret_cast<const Packed64 *>(r.ring + ((r.q >> 3) & 63u))->v;
+    return v >> (r.q & 7u);
 }
 
-__device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) {
-    return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
+__device__ __forceinline__ uint64_t lut_at(const Tables &tb, uint32_t byte_off) {
+    return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
 }
 
-// One symbol from the window w, which holds at least 17 valid bits.  A fresh
-// window has 62; kGroup - 1 first-level symbols leave 62 - 44 = 18.  After a
-// longer symbol the window is read again, so the rest of the group starts from
-// 62 bits once more.
+// One table probe: decode the codes at the front of the window w, write their
+// elements at `out` and advance.  w must hold at least 17 valid bits: a fresh
+// window has 54 and each of the kGroup - 1 probes before took at most 17.
 template <int MODE>
-__device__ __forceinline__ uint32_t ring_symbol(RingReader &r, uint64_t &w, const Tables &tb, const DevTensor &t) {
-    uint32_t e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 2));
-    if (__builtin_expect((e & 0xffu) == 0, 0)) {
-        e = lookup_l2(tb, e, static_cast<uint32_t>(w >> 2));
-        if (__builtin_expect((e & 0xffu) == 0, 0)) {
-            // longer than the tables resolve: bring the ring up to date (see ring_check), then search
+__device__ __forceinline__ void ring_probe(RingReader &r, uint64_t &w, uint8_t *&out, const Tables &tb,
+                                           const DevTensor &t) {
+    uint64_t e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 3));
+    if (__builtin_expect(entry_len(e) == 0, 0)) {
+        e = lookup_l2(tb, e, static_cast<uint32_t>(w >> 3));
+        if (__builtin_expect(entry_len(e) == 0, 0)) {
+            // longer than the tables resolve: bring the ring up to date (see ring_check), search,
+            // and start the rest of the group from a fresh window
             ring_check(r);
             w = ring_read(r);
-            e = decode_canonical<MODE>(tb, static_cast<uint32_t>(w >> 2), t.max_len, t.zero_point, t.scale);
+            e = decode_canonical<MODE>(tb, static_cast<uint32_t>(w >> 3), t.max_len, t.zero_point, t.scale);
+            r.q += entry_len(e);
+            w = ring_read(r);
+            e &= ~(0xffull << 48);           // already consumed
         }
-        r.p += e & 0xffu;
-        w = ring_read(r);
-        e &= ~0xffu;                 // already consumed
     }
-    w >>= (e & 63u);
-    r.p += e & 0xffu;
-    return e;
-}
-
-// The row path decodes `spb` symbols per step into a row of `dpb` dwords.
-template <int MODE> struct RowTraits;
-template <> struct RowTraits<kModeU8> { static constexpr int spb = 128, dpb = 32, spd = 4; };
-template <> struct RowTraits<kModeU4> { static constexpr int spb = 128, dpb = 16, spd = 8; };
-template <> struct RowTraits<kModeF32> { static constexpr int spb = 32, dpb = 32, spd = 1; };
-template <> struct RowTraits<kModeBF16> { static constexpr int spb = 64, dpb = 32, spd = 2; };
-
-// NSYM symbols (a whole number of output dwords) into dst[0 .. NSYM / spd).
-template <int MODE, int NSYM>
-__device__ __forceinline__ void decode_span(RingReader &r, const Tables &tb, const DevTensor &t, uint32_t *dst) {
-    constexpr int SPD = RowTraits<MODE>::spd;
-    static_assert(NSYM % SPD == 0, "span must fill whole dwords");
-    uint64_t w = 0;
-    uint32_t acc = 0;
-#pragma unroll
-    for (int j = 0; j < NSYM; ++j) {
-        if (j % kCheck == 0) ring_check(r);
-        if (j % kGroup == 0) w = ring_read(r);
-        const uint32_t e = ring_symbol<MODE>(r, w, tb, t);
-        const uint32_t sym = (e >> 8) & 0xffu;
-        if (MODE == kModeU8) acc = (j % 4) ? (acc | (sym << ((j % 4) * 8))) : sym;
-        if (MODE == kModeU4) acc = (j % 8) ? (acc | ((sym & 0xfu) << ((j % 8) * 4))) : (sym & 0xfu);
-        // bytes 2,3 of the entry are the bf16 value: low half from the even symbol, high half from the odd one
-        if (MODE == kModeBF16) acc = (j % 2) ? __builtin_amdgcn_perm(e, acc, 0x07060100u) : (e >> 16);
-        if (MODE == kModeF32) acc = __float_as_uint(dequant(sym, t.zero_point, t.scale));
-        if (j % SPD == SPD - 1) dst[j / SPD] = acc;
-    }
+    reinterpret_cast<Packed64 *>(out)->v = e;
+    const uint32_t ctl = static_cast<uint32_t>(e >> 48);
+    w >>= (ctl & 63u);
+    r.q += ctl & 0xffu;
+    out += ctl >> 8;
 }
 
 // Decode the workgroup's segments block by block into the wave's LDS tile (one
-// row per lane) and write the tile out row-wise, so that every store
-// instruction covers whole rows of 4 * dpb bytes.
+// 128-byte row per lane) and write the tile out row-wise, so that every store
+// instruction covers whole rows.
 template <int MODE>
 __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem *wms, uint32_t first_chunk) {
-    constexpr int SPB = RowTraits<MODE>::spb;
-    constexpr int DPB = RowTraits<MODE>::dpb;
-    constexpr int SPD = RowTraits<MODE>::spd;
-    constexpr int SPAN = kCheck * (SPD > 2 ? SPD / 2 : 1);   // symbols per loop trip: whole dwords, whole check intervals
-    constexpr int TRIPS = SPB / SPAN;
-    constexpr int REST = SPB - TRIPS * SPAN;
-    constexpr uint32_t LPR = DPB / 4;                 // lanes that store one row
-    constexpr uint32_t RPI = 64 / LPR;                // rows per store instruction
+    constexpr int ESZ = Elem<MODE>::size;
+    constexpr int SPB = kRowBytes / ESZ;                  // symbols per block
+    constexpr int OUT_ROW = SPB * OutTraits<MODE>::ebits / 8;      // bytes a block becomes in memory (64 for packed 4-bit)
+    constexpr uint32_t LPR = 8;                           // lanes that store one row
+    constexpr uint32_t RPI = 64 / LPR;                    // rows per store instruction
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     WaveMem &wm = wms[wave];
@@ -451,35 +478,41 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const uint32_t C = t.chunk_symbols;
     const uint32_t blocks_total = C / SPB;
     const uint32_t k = wave_first + lane;
-    const bool active = k < t.n_chunks;
     uint32_t nsym = 0;
+    if (k < t.n_chunks) {
+        const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
+        nsym = left < C ? static_cast<uint32_t>(left) : C;
+    }
+    // a shorter last segment goes through the scalar path as a whole
+    const bool fast = nsym == C;
     RingReader r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
-    r.p = 0;
+    r.q = 0u - 3u;
     r.start16 = 0;
     r.cur = 0;
     r.nx = u32x4{0u, 0u, 0u, 0u};
-    r.ring = wm.ring + lane * kRingStride;
-    if (active) {
-        const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
-        nsym = left < C ? static_cast<uint32_t>(left) : C;
-        ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
-    }
-    const uint32_t my_blocks = nsym / SPB;
+    r.ring = reinterpret_cast<uint8_t *>(wm.ring + lane * kRingStride);
+    if (fast) ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * OutTraits<MODE>::ebits) >> 3;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
-    uint32_t *my_row = wm.tile + lane * kTileStride;
+    uint8_t *const my_row = reinterpret_cast<uint8_t *>(wm.tile + lane * kTileStride);
+    uint8_t *const row_end = my_row + kRowBytes;
+    uint8_t *out = my_row;
 
     for (uint32_t bs = 0; bs < blocks_total; ++bs) {
-        if (bs < my_blocks) {
-            uint32_t *dst = my_row;
-#pragma unroll 1
-            for (int trip = 0; trip < TRIPS; ++trip) {
-                decode_span<MODE, SPAN>(r, tb, t, dst);
-                dst += SPAN / SPD;
+        // every lane fills its row; a probe may run up to 5 bytes over, which the next block inherits
+        while (__builtin_amdgcn_ballot_w64(fast && out < row_end)) {
+            ring_check(r);
+#pragma unroll
+            for (int g = 0; g < kTripGroups; ++g) {
+                if (fast && out < row_end) {
+                    uint64_t w = ring_read(r);
+#pragma unroll
+                    for (int i = 0; i < kGroup; ++i)
+                        if (out < row_end) ring_probe<MODE>(r, w, out, tb, t);
+                }
             }
-            if constexpr (REST > 0) decode_span<MODE, REST>(r, tb, t, dst);
         }
         wave_sync_lds();
 #pragma unroll
@@ -489,18 +522,30 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             const uint32_t *src = wm.tile + rr * kTileStride + piece * 4u;
             const u32x4 v = {src[0], src[1], src[2], src[3]};
             const uint32_t kk = wave_first + rr;
-            if (kk < t.n_chunks) {
-                const uint64_t left = t.n - static_cast<uint64_t>(kk) * C;
-                const uint32_t blocks_kk = (left < C ? static_cast<uint32_t>(left) : C) / SPB;
-                if (bs < blocks_kk)
-                    *(global_u4_wptr)(out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * (DPB * 4u) + piece * 16u) = v;
+            bool full = false;
+            if (kk < t.n_chunks) full = t.n - static_cast<uint64_t>(kk) * C >= C;
+            if (full) {
+                uint8_t *dst = out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * OUT_ROW;
+                if constexpr (MODE == kModeU4) {
+                    // 16 symbols, one per byte -> 8 bytes, even symbol in the low nibble
+                    u32x2 pk;
+                    uint32_t a = (v.x | (v.x >> 4)) & 0x00ff00ffu, b = (v.y | (v.y >> 4)) & 0x00ff00ffu;
+                    pk.x = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
+                    a = (v.z | (v.z >> 4)) & 0x00ff00ffu; b = (v.w | (v.w >> 4)) & 0x00ff00ffu;
+                    pk.y = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
+                    *(global_u2_wptr)(dst + piece * 8u) = pk;
+                } else {
+                    *(global_u4_wptr)(dst + piece * 16u) = v;
+                }
             }
         }
         wave_sync_lds();
+        // what ran over the row end opens the next row
+        const uint64_t spill = reinterpret_cast<const Packed64 *>(row_end)->v;
+        reinterpret_cast<Packed64 *>(my_row)->v = spill;
+        out = my_row + (out > row_end ? static_cast<uint32_t>(out - row_end) : 0u);
     }
-    // symbols of a shorter last segment that do not fill a block
-    if (active && my_blocks * SPB < nsym)
-        decode_scalar<MODE>(t, tb, k, my_blocks * SPB, nsym, (static_cast<uint64_t>(r.start16) << 3) + r.p);
+    if (!fast && nsym) decode_scalar<MODE>(t, tb, k, nsym);
 }
 
 // Decode one segment straight into dot products with x.  A segment covers one
@@ -524,23 +569,28 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     bool first_fragment = true;
     float acc = 0.0f;
     float head = 0.0f, tail = 0.0f;
-    for (uint32_t i = 0; i < nsym; ++i) {
-        if (i % kTrio == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint32_t e = next_symbol<MODE>(r, tb, t);
-        const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
-        acc = fmaf(static_cast<float>(static_cast<int32_t>((e >> 8) & 0xffu) - t.zero_point), xv, acc);
-        if (++col == t.cols) {
-            if (first_fragment && start_col != 0) {
-                head = acc;                                  // row began in an earlier segment
-            } else {
-                const float y = acc * t.scale;
-                if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[row] = y;
-                else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
+    uint32_t i = 0;
+    for (uint32_t probe = 0; i < nsym; ++probe) {
+        if (probe % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
+        const uint64_t e = next_entry<MODE>(r, tb, t);
+        const uint32_t count = entry_bytes(e);
+        for (uint32_t c = 0; c < count && i < nsym; ++c, ++i) {
+            const uint32_t sym = static_cast<uint32_t>(e >> (c * 8)) & 0xffu;
+            const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
+            acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - t.zero_point), xv, acc);
+            if (++col == t.cols) {
+                if (first_fragment && start_col != 0) {
+                    head = acc;                              // row began in an earlier segment
+                } else {
+                    const float y = acc * t.scale;
+                    if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[row] = y;
+                    else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
+                }
+                first_fragment = false;
+                acc = 0.0f;
+                col = 0;
+                ++row;
             }
-            first_fragment = false;
-            acc = 0.0f;
-            col = 0;
-            ++row;
         }
     }
     if (col != 0) {                                          // row continues in the next segment
@@ -555,28 +605,29 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 
 template <int MODE>
 __device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, Tables &tb, WaveMem *wms) {
-    build_tables<MODE>(t, tb);
+    // the single-symbol scratch table lives in the first wave's buffers, which are not in use yet
+    build_tables<MODE>(t, tb, reinterpret_cast<uint32_t *>(wms));
     if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
         const uint32_t k = first_chunk + threadIdx.x;
         if (k < t.n_chunks) gemv_segment<MODE>(t, tb, k);
     } else {
-        if (t.chunk_symbols % RowTraits<MODE>::spb == 0) {
+        if (t.chunk_symbols % (kRowBytes / Elem<MODE>::size) == 0) {
             decode_rows<MODE>(t, tb, wms, first_chunk);
         } else {                                             // segment size does not tile into blocks
             const uint32_t k = first_chunk + threadIdx.x;
             if (k < t.n_chunks) {
                 const uint64_t left = t.n - static_cast<uint64_t>(k) * t.chunk_symbols;
-                const uint32_t nsym = left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols;
-                decode_scalar<MODE>(t, tb, k, 0, nsym, t.offsets[k]);
+                decode_scalar<MODE>(t, tb, k, left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols);
             }
         }
     }
 }
 
-// The GEMV kernels need the tables only; the others also the per-wave buffers.
+// The GEMV kernels need the tables and the scratch table only.
 template <int MODE> struct SmemFor { Tables tb; WaveMem wm[kWaves]; };
 template <> struct SmemFor<kModeGemvF32> { Tables tb; WaveMem wm[1]; };
 template <> struct SmemFor<kModeGemvBF16> { Tables tb; WaveMem wm[1]; };
+static_assert(sizeof(WaveMem) >= sizeof(uint32_t) << kL1, "scratch table must fit into one wave's buffers");
 
 template <int MODE>
 __global__ __launch_bounds__(kWG) void k_single(const DevTensor t) {
