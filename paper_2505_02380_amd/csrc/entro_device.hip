@@ -8,11 +8,13 @@
 // segments of one tensor with one shared set of lookup tables in LDS.
 //
 // Data flow of the decode / dequant kernels, per lane:
-//   HBM --16-byte blocks--> four-slot ring in LDS --unaligned 64-bit reads--> bit window
+//   HBM --16-byte blocks--> four-slot ring in LDS --three dwords--> 61-bit window
 //   window --11 bits--> first-level table (LDS, 64-bit entries holding up to
-//   three decoded, already dequantised symbols) --one unaligned 64-bit write-->
+//   three decoded, already dequantised symbols) --three element writes-->
 //   the lane's 128-byte row of the wave's LDS tile --row-wise--> HBM,
 // so that every global store instruction of a wave covers whole 128-byte lines.
+// Every LDS access is naturally aligned: gfx950 executes unaligned ones, but
+// they stall the LDS pipeline for most of the kernel's time.
 #include "entro.h"
 
 #include <hip/hip_runtime.h>
@@ -71,16 +73,15 @@ enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 
 
 // Per mode: bytes one decoded symbol occupies in a table entry and in the LDS
 // tile, most symbols one entry carries, symbols per 128-byte tile row.
-template <int MODE> struct Elem { static constexpr int size = 1, max_syms = 6; };      // symbol values
+template <int MODE> struct Elem { static constexpr int size = 1, max_syms = 3; };      // symbol values
 template <> struct Elem<kModeBF16> { static constexpr int size = 2, max_syms = 3; };   // dequantised bf16
 template <> struct Elem<kModeF32> { static constexpr int size = 4, max_syms = 1; };    // dequantised fp32
 
 // Lookup tables of one workgroup (LDS).
 // Symbol entry (64 bits): bits 0..47 up to max_syms decoded elements, first one
 // lowest; bits 48..55 the stream bits they take together; bits 56..63 the bytes
-// they occupy.  Writing the entry as it is to the output position stores the
-// elements; the two control bytes land behind them and are overwritten by the
-// next entry.
+// they occupy.  A probe writes all max_syms element slots; the slots past the
+// entry's own elements are overwritten by the next probe.
 // First level: indexed by the next kL1 stream bits, holds every run of whole
 // codes that fits into them.  A zero length marks a prefix whose first code is
 // longer than kL1 bits; bits 0..15 then are the base and bits 16..23 the depth
@@ -113,7 +114,11 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef const u32x4 __attribute__((address_space(1))) *global_u4_ptr;
 typedef u32x4 __attribute__((address_space(1))) *global_u4_wptr;
 typedef u32x2 __attribute__((address_space(1))) *global_u2_wptr;
-struct __attribute__((packed)) Packed64 { uint64_t v; };      // 64-bit LDS access at any byte address
+// volatile LDS element pointers: keeps the compiler from fusing neighbouring element
+// accesses into one wider, unaligned LDS access
+typedef volatile uint8_t __attribute__((address_space(3))) *lds_v8;
+typedef volatile uint16_t __attribute__((address_space(3))) *lds_v16;
+typedef volatile uint32_t __attribute__((address_space(3))) *lds_v32;
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -364,14 +369,15 @@ __device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, 
 // ------------------------------------------------------------------ ring reader
 // Each lane keeps the next 48 bytes of its segment in a four-slot ring in LDS
 // (16-byte blocks, block j in slot j & 3, three of them resident) and the block
-// after those in registers.  Bytes 64..71 of the lane's ring row mirror bytes
-// 0..7, so a 64-bit read starting anywhere in the ring needs no wrap.
+// after those in registers.  Dwords 16 and 17 of the lane's ring row mirror
+// dwords 0 and 1, so a three-dword read starting in the last ring dwords needs
+// no wrap.
 // The lane tracks q = p - 3, p being its bit position relative to block 0: a
 // window read at bit q carries three stale low bits, which makes bits 3..13 the
 // first-level table's byte offset of the code that starts at p.
 struct RingReader {
     const uint8_t *stream;
-    uint8_t *ring;         // this lane's ring row
+    uint32_t *ring;        // this lane's ring row
     uint32_t start16;      // byte offset of block 0 (16-byte aligned)
     uint32_t last_blk;     // stream_bytes - 16
     uint32_t q;            // p - 3 (wraps below zero for p < 3, which the mirror absorbs)
@@ -387,7 +393,7 @@ __device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t star
 
 __device__ __forceinline__ void ring_init(RingReader &r, const DevTensor &t, uint64_t off_bits, uint32_t *ring_row) {
     r.stream = t.stream;
-    r.ring = reinterpret_cast<uint8_t *>(ring_row);
+    r.ring = ring_row;
     r.last_blk = t.stream_bytes - 16u;
     r.start16 = static_cast<uint32_t>(off_bits >> 3) & ~15u;
     r.q = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.start16) << 3)) - 3u;
@@ -402,43 +408,55 @@ __device__ __forceinline__ void ring_init(RingReader &r, const DevTensor &t, uin
     ring_row[16] = b0.x; ring_row[17] = b0.y;
 }
 
-// Retire the blocks p has left behind.  A ring read at p touches the 9 bytes
-// from the one holding bit p - 3 on, so it is valid while p is at most 184
-// bits past the end of block cur.  Between two checks kTripGroups ring reads
-// happen, each followed by kGroup probes of at most 17 bits (both table
+// Retire the blocks p has left behind.  A ring read at q = p - 3 takes the
+// dword holding bit q and the two after it, so it is valid while q is less
+// than 192 bits past the end of block cur.  Between two checks kTripGroups ring
+// reads happen, each followed by kGroup probes of at most 17 bits (both table
 // levels), so the last read starts at most (kTripGroups - 1) * kGroup * 17 =
 // 153 bits past the end of block cur.  A longer code (up to 32 bits) runs its
 // own check first and reads again afterwards; later reads stay within
-// 32 + 9 * 17 = 185 - 1.
+// 32 + 9 * 17 = 185.
 __device__ __forceinline__ void ring_check(RingReader &r) {
     const uint32_t nb = (r.q + 3u) >> 7;
-    uint32_t *ring32 = reinterpret_cast<uint32_t *>(r.ring);
     while (nb != r.cur) {
         const uint32_t slot = (r.cur + 3u) & 3u;
-        uint32_t *dst = ring32 + (slot << 2);
+        uint32_t *dst = r.ring + (slot << 2);
         dst[0] = r.nx.x; dst[1] = r.nx.y; dst[2] = r.nx.z; dst[3] = r.nx.w;
-        if (slot == 0) { ring32[16] = r.nx.x; ring32[17] = r.nx.y; }
+        if (slot == 0) { r.ring[16] = r.nx.x; r.ring[17] = r.nx.y; }
         r.cur += 1;
         r.nx = load_block(r.stream, r.start16, r.last_blk, r.cur + 3u);
     }
 }
 
-// The stream from bit q = p - 3 on: at least 54 valid bits above the three stale ones.
+// The stream from bit q = p - 3 on: 61 valid bits above the three stale ones.
 __device__ __forceinline__ uint64_t ring_read(const RingReader &r) {
-    const uint64_t v = reinterpret_cast<const Packed64 *>(r.ring + ((r.q >> 3) & 63u))->v;
-    return v >> (r.q & 7u);
+    const uint32_t d = (r.q >> 5) & 15u;
+    const uint32_t w0 = r.ring[d], w1 = r.ring[d + 1], w2 = r.ring[d + 2];
+    const uint32_t lo = __builtin_amdgcn_alignbit(w1, w0, r.q);     // uses q & 31
+    const uint32_t hi = __builtin_amdgcn_alignbit(w2, w1, r.q);
+    return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
 __device__ __forceinline__ uint64_t lut_at(const Tables &tb, uint32_t byte_off) {
     return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
 }
 
+// The few per-tensor scalars the hot loop needs, copied out of the descriptor
+// once so that they stay in registers (the descriptor sits in global memory
+// and would otherwise be re-read after every store).
+struct HotParams {
+    uint32_t max_len;
+    int32_t zero_point;
+    float scale;
+};
+
 // One table probe: decode the codes at the front of the window w, write their
-// elements at `out` and advance.  w must hold at least 17 valid bits: a fresh
-// window has 54 and each of the kGroup - 1 probes before took at most 17.
+// elements at byte `out` of the lane's tile row and advance.  w must hold at
+// least 17 valid bits: a fresh window has 61 and each of the kGroup - 1 probes
+// before took at most 17.
 template <int MODE>
-__device__ __forceinline__ void ring_probe(RingReader &r, uint64_t &w, uint8_t *&out, const Tables &tb,
-                                           const DevTensor &t) {
+__device__ __forceinline__ void ring_probe(RingReader &r, uint64_t &w, uint8_t *row, uint32_t &out,
+                                           const Tables &tb, const HotParams &hp) {
     uint64_t e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 3));
     if (__builtin_expect(entry_len(e) == 0, 0)) {
         e = lookup_l2(tb, e, static_cast<uint32_t>(w >> 3));
@@ -447,14 +465,24 @@ __device__ __forceinline__ void ring_probe(RingReader &r, uint64_t &w, uint8_t *
             // and start the rest of the group from a fresh window
             ring_check(r);
             w = ring_read(r);
-            e = decode_canonical<MODE>(tb, static_cast<uint32_t>(w >> 3), t.max_len, t.zero_point, t.scale);
+            e = decode_canonical<MODE>(tb, static_cast<uint32_t>(w >> 3), hp.max_len, hp.zero_point, hp.scale);
             r.q += entry_len(e);
             w = ring_read(r);
             e &= ~(0xffull << 48);           // already consumed
         }
     }
-    reinterpret_cast<Packed64 *>(out)->v = e;
-    const uint32_t ctl = static_cast<uint32_t>(e >> 48);
+    // all three element slots, each with its own naturally aligned write
+    const uint32_t lo = static_cast<uint32_t>(e), hi = static_cast<uint32_t>(e >> 32);
+    if constexpr (Elem<MODE>::size == 2) {
+        lds_v16 o = (lds_v16)(row + out);
+        o[0] = static_cast<uint16_t>(lo); o[1] = static_cast<uint16_t>(lo >> 16); o[2] = static_cast<uint16_t>(hi);
+    } else if constexpr (Elem<MODE>::size == 1) {
+        lds_v8 o = (lds_v8)(row + out);
+        o[0] = static_cast<uint8_t>(lo); o[1] = static_cast<uint8_t>(lo >> 8); o[2] = static_cast<uint8_t>(lo >> 16);
+    } else {
+        *(lds_v32)(row + out) = lo;
+    }
+    const uint32_t ctl = hi >> 16;
     w >>= (ctl & 63u);
     r.q += ctl & 0xffu;
     out += ctl >> 8;
@@ -492,25 +520,27 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     r.start16 = 0;
     r.cur = 0;
     r.nx = u32x4{0u, 0u, 0u, 0u};
-    r.ring = reinterpret_cast<uint8_t *>(wm.ring + lane * kRingStride);
+    r.ring = wm.ring + lane * kRingStride;
     if (fast) ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * OutTraits<MODE>::ebits) >> 3;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
+    const HotParams hp = {t.max_len, t.zero_point, t.scale};
+    const uint32_t n_chunks = t.n_chunks;
+    const uint64_t n_total = t.n;
     uint8_t *const my_row = reinterpret_cast<uint8_t *>(wm.tile + lane * kTileStride);
-    uint8_t *const row_end = my_row + kRowBytes;
-    uint8_t *out = my_row;
+    uint32_t out = 0;                                     // write position in my_row, bytes
 
     for (uint32_t bs = 0; bs < blocks_total; ++bs) {
-        // every lane fills its row; a probe may run up to 5 bytes over, which the next block inherits
-        while (__builtin_amdgcn_ballot_w64(fast && out < row_end)) {
+        // every lane fills its row; a probe may run up to two elements over, which the next block inherits
+        while (__builtin_amdgcn_ballot_w64(fast && out < kRowBytes)) {
             ring_check(r);
 #pragma unroll
             for (int g = 0; g < kTripGroups; ++g) {
-                if (fast && out < row_end) {
+                if (fast && out < kRowBytes) {
                     uint64_t w = ring_read(r);
 #pragma unroll
                     for (int i = 0; i < kGroup; ++i)
-                        if (out < row_end) ring_probe<MODE>(r, w, out, tb, t);
+                        if (out < kRowBytes) ring_probe<MODE>(r, w, my_row, out, tb, hp);
                 }
             }
         }
@@ -523,7 +553,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             const u32x4 v = {src[0], src[1], src[2], src[3]};
             const uint32_t kk = wave_first + rr;
             bool full = false;
-            if (kk < t.n_chunks) full = t.n - static_cast<uint64_t>(kk) * C >= C;
+            if (kk < n_chunks) full = n_total - static_cast<uint64_t>(kk) * C >= C;
             if (full) {
                 uint8_t *dst = out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * OUT_ROW;
                 if constexpr (MODE == kModeU4) {
@@ -541,9 +571,16 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         }
         wave_sync_lds();
         // what ran over the row end opens the next row
-        const uint64_t spill = reinterpret_cast<const Packed64 *>(row_end)->v;
-        reinterpret_cast<Packed64 *>(my_row)->v = spill;
-        out = my_row + (out > row_end ? static_cast<uint32_t>(out - row_end) : 0u);
+        if constexpr (ESZ == 2) {
+            lds_v16 row16 = (lds_v16)my_row;
+            const uint16_t s0 = row16[kRowBytes / 2], s1 = row16[kRowBytes / 2 + 1];
+            row16[0] = s0; row16[1] = s1;
+        } else if constexpr (ESZ == 1) {
+            lds_v8 row8 = (lds_v8)my_row;
+            const uint8_t s0 = row8[kRowBytes], s1 = row8[kRowBytes + 1];
+            row8[0] = s0; row8[1] = s1;
+        }
+        out = out > kRowBytes ? out - kRowBytes : 0u;
     }
     if (!fast && nsym) decode_scalar<MODE>(t, tb, k, nsym);
 }
