@@ -4,17 +4,20 @@
 // EntroLLM ("Segmentation for parallel Huffman decoding", Fig. 3) cuts the
 // encoded parameter space into segments with known boundaries and decodes
 // them independently; here a segment is a fixed number of symbols and one
-// GPU lane owns one segment, so a 640-lane workgroup decodes 640 consecutive
+// GPU lane owns one segment, so a workgroup of W lanes decodes W consecutive
 // segments of one tensor with one shared set of lookup tables in LDS.
 //
 // Data flow of the decode / dequant kernels, per lane:
 //   HBM --16-byte blocks--> four-slot ring in LDS --three dwords--> 61-bit window
 //   window --11 bits--> first-level table (LDS, 64-bit entries holding up to
-//   three decoded, already dequantised symbols) --three element writes-->
-//   the lane's 128-byte row of the wave's LDS tile --row-wise--> HBM,
+//   four decoded symbols) --byte writes--> the lane's row of the wave's LDS tile
+//   tile rows --dequantise / pack, row-wise--> HBM,
 // so that every global store instruction of a wave covers whole 128-byte lines.
 // Every LDS access is naturally aligned: gfx950 executes unaligned ones, but
-// they stall the LDS pipeline for most of the kernel's time.
+// they stall the LDS pipeline for most of the kernel's time.  The symbol loop
+// has no branch per table probe; a probe that meets a code too long for the
+// first-level table simply makes no progress, and the lane resolves that code
+// once per group of probes.
 #include "entro.h"
 
 #include <hip/hip_runtime.h>
@@ -27,19 +30,17 @@
 
 namespace {
 
-constexpr int kWG = 640;                 // lanes (= segments) per workgroup: 10 waves fill the 160 KB of LDS
-constexpr int kWaves = kWG / 64;
 constexpr int kL1 = 11;                  // stream bits that index the first-level table
 constexpr uint32_t kL1Mask = (1u << kL1) - 1u;
+constexpr int kMaxSyms = 4;              // symbols one first-level entry can carry
 constexpr int kL2Cap = 512;              // second-level entries (all long prefixes together)
 constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 17 bits
 constexpr int kL2MaxPrefixes = 64;       // more long prefixes than this: second level unused
-constexpr int kGroup = 3;                // table probes per ring read: 54 valid bits >= 2 * 17 + 17
+constexpr int kGroup = 3;                // table probes per ring read: 61 valid bits >= 3 * 11 + 17
 constexpr int kTripGroups = 4;           // ring reads between two refill checks (see ring_check)
 constexpr int kScalarProbes = 3;         // scalar reader: probes per 64-bit load, 33 valid bits >= 3 * kL1
 constexpr int kRingStride = 19;          // dwords per lane: 4 x 16-byte slots, 2 mirror dwords, pad (odd)
-constexpr int kRowBytes = 128;           // output row per lane and block
-constexpr int kTileStride = 35;          // dwords per lane in the output tile: row, 8 bytes of slack, pad (odd)
+constexpr int kRowSlack = 8;             // tile bytes behind a row: 3 symbols run over, 4 more are written blind
 constexpr uint32_t kMaxChunkSymbols = 1u << 20;
 
 // What the kernels read about one tensor.  Lives in kernel arguments (single
@@ -71,23 +72,33 @@ struct WorkItem {
 
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5 };
 
-// Per mode: bytes one decoded symbol occupies in a table entry and in the LDS
-// tile, most symbols one entry carries, symbols per 128-byte tile row.
-template <int MODE> struct Elem { static constexpr int size = 1, max_syms = 3; };      // symbol values
-template <> struct Elem<kModeBF16> { static constexpr int size = 2, max_syms = 3; };   // dequantised bf16
-template <> struct Elem<kModeF32> { static constexpr int size = 4, max_syms = 1; };    // dequantised fp32
+// Per output mode: symbols a lane decodes per block (= bytes of its tile row),
+// waves per workgroup (what fits into the 160 KB of LDS) and bytes a block
+// becomes in memory.  The host glue sizes its launches with the same numbers.
+template <int MODE> struct Cfg;
+template <> struct Cfg<kModeU8> { static constexpr int spb = 128, waves = 10, out_row = 128; };
+template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 10, out_row = 64; };
+template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 14, out_row = 256; };
+template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 14, out_row = 128; };
+template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 4, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 4, out_row = 0; };
+constexpr int kWgDecode = 64 * Cfg<kModeU8>::waves;
+constexpr int kWgDequant = 64 * Cfg<kModeBF16>::waves;
+constexpr int kWgGemv = 64 * Cfg<kModeGemvF32>::waves;
+static_assert(Cfg<kModeU8>::waves == Cfg<kModeU4>::waves && Cfg<kModeF32>::waves == Cfg<kModeBF16>::waves,
+              "one workgroup size per operation");
 
 // Lookup tables of one workgroup (LDS).
-// Symbol entry (64 bits): bits 0..47 up to max_syms decoded elements, first one
-// lowest; bits 48..55 the stream bits they take together; bits 56..63 the bytes
-// they occupy.  A probe writes all max_syms element slots; the slots past the
-// entry's own elements are overwritten by the next probe.
+// Symbol entry (64 bits): bits 0..31 up to four decoded symbols, first one
+// lowest; bits 48..55 the stream bits they take together; bits 56..63 their
+// number.  A probe writes all four bytes; those past the entry's own symbols are
+// overwritten by the next probe.
 // First level: indexed by the next kL1 stream bits, holds every run of whole
-// codes that fits into them.  A zero length marks a prefix whose first code is
+// codes that fits into them.  A zero count marks a prefix whose first code is
 // longer than kL1 bits; bits 0..15 then are the base and bits 16..23 the depth
 // of the prefix's block in the second level.
 // Second level: one symbol per entry, indexed by the following `depth` stream
-// bits; a zero length there sends the lane to the canonical search
+// bits; a zero count there sends the lane to the canonical search
 // (first / cnt / offs / sorted).
 struct alignas(16) Tables {
     uint64_t lut[1 << kL1];
@@ -104,21 +115,24 @@ struct alignas(16) Tables {
 };
 
 // Per-wave LDS: the lanes' stream windows and their output rows.
+template <int SPB>
 struct alignas(16) WaveMem {
+    static constexpr int tile_stride = (SPB + kRowSlack) / 4 + 1;       // dwords per lane, odd
+    static_assert(tile_stride % 2 == 1, "odd stride keeps the lanes' rows on different banks");
     uint32_t ring[64 * kRingStride];
-    uint32_t tile[64 * kTileStride];
+    uint32_t tile[64 * tile_stride];
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef const u32x4 __attribute__((address_space(1))) *global_u4_ptr;
 typedef u32x4 __attribute__((address_space(1))) *global_u4_wptr;
 typedef u32x2 __attribute__((address_space(1))) *global_u2_wptr;
-// volatile LDS element pointers: keeps the compiler from fusing neighbouring element
-// accesses into one wider, unaligned LDS access
+// volatile LDS byte pointer: keeps the compiler from fusing neighbouring byte
+// writes into one wider, unaligned LDS access
 typedef volatile uint8_t __attribute__((address_space(3))) *lds_v8;
-typedef volatile uint16_t __attribute__((address_space(3))) *lds_v16;
-typedef volatile uint32_t __attribute__((address_space(3))) *lds_v32;
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -130,24 +144,11 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
     return static_cast<float>(static_cast<int32_t>(sym) - z) * s;
 }
 
-template <int MODE>
-__device__ __forceinline__ uint64_t make_elem(uint32_t sym, int32_t z, float s) {
-    if (MODE == kModeBF16) return bf16_bits(dequant(sym, z, s));
-    if (MODE == kModeF32) return __float_as_uint(dequant(sym, z, s));
-    return sym;
+__device__ __forceinline__ uint64_t pack_entry(uint32_t syms, uint32_t len, uint32_t count) {
+    return syms | (static_cast<uint64_t>(len) << 48) | (static_cast<uint64_t>(count) << 56);
 }
-
-__device__ __forceinline__ uint64_t pack_entry(uint64_t payload, uint32_t len, uint32_t bytes) {
-    return payload | (static_cast<uint64_t>(len) << 48) | (static_cast<uint64_t>(bytes) << 56);
-}
-
-template <int MODE>
-__device__ __forceinline__ uint64_t make_entry(uint32_t sym, uint32_t len, int32_t z, float s) {
-    return pack_entry(make_elem<MODE>(sym, z, s), len, Elem<MODE>::size);
-}
-
 __device__ __forceinline__ uint32_t entry_len(uint64_t e) { return static_cast<uint32_t>(e >> 48) & 0xffu; }
-__device__ __forceinline__ uint32_t entry_bytes(uint64_t e) { return static_cast<uint32_t>(e >> 56); }
+__device__ __forceinline__ uint32_t entry_count(uint64_t e) { return static_cast<uint32_t>(e >> 56); }
 
 __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -155,17 +156,17 @@ __device__ __forceinline__ void wave_sync_lds() {
 }
 
 // Canonical code tables and both lookup levels, built from the 256 (or 16)
-// code lengths by the whole workgroup.  `lut1` is scratch for a single-symbol
-// table of 2^kL1 words (len | symbol << 8, zero for long prefixes).
-template <int MODE>
+// code lengths by the whole workgroup of WG lanes.  `lut1` is scratch for a
+// single-symbol table of 2^kL1 words (len | symbol << 8, zero for long prefixes).
+template <int WG>
 __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
     const int tid = threadIdx.x;
     const uint32_t l = tid < 256 ? t.len[tid] : 0u;
     if (tid < 256) tb.lens[tid] = static_cast<uint8_t>(l);
     if (tid < ENTRO_MAX_CODE_LEN + 2) tb.cnt[tid] = 0;
     if (tid < kL2MaxPrefixes) tb.pdepth[tid] = 0;
-    for (int i = tid; i < (1 << kL1); i += kWG) lut1[i] = 1u;            // symbol 0, one bit: filler of incomplete codes
-    for (int i = tid; i < kL2Cap; i += kWG) tb.lut2[i] = 0;
+    for (int i = tid; i < (1 << kL1); i += WG) lut1[i] = 1u;             // symbol 0, one bit: filler of incomplete codes
+    for (int i = tid; i < kL2Cap; i += WG) tb.lut2[i] = 0;
     __syncthreads();
     if (l) atomicAdd(&tb.cnt[l], 1u);
     __syncthreads();
@@ -229,7 +230,7 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
                 const uint32_t depth = tb.pdepth[prefix - first_prefix];
                 const uint32_t base = tb.pbase[prefix - first_prefix];
                 if (extra <= depth) {
-                    const uint64_t e = make_entry<MODE>(tid, l, t.zero_point, t.scale);
+                    const uint64_t e = pack_entry(tid, l, 1);
                     const uint32_t suffix = code & ((1u << extra) - 1u);
                     const uint32_t rev = __brev(suffix) >> (32 - extra);
                     for (uint32_t i = rev; i < (1u << depth); i += (1u << extra)) tb.lut2[base + i] = e;
@@ -240,20 +241,19 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
     }
     __syncthreads();
     // first level: all whole codes that fit into the kL1 index bits
-    for (uint32_t i = tid; i < (1u << kL1); i += kWG) {
-        uint32_t pos = 0, count = 0;
-        uint64_t payload = 0;
-        while (count < static_cast<uint32_t>(Elem<MODE>::max_syms)) {
+    for (uint32_t i = tid; i < (1u << kL1); i += WG) {
+        uint32_t pos = 0, count = 0, syms = 0;
+        while (count < static_cast<uint32_t>(kMaxSyms)) {
             const uint32_t e1 = lut1[i >> pos];
             const uint32_t len1 = e1 & 0xffu;
             if (len1 == 0 || pos + len1 > static_cast<uint32_t>(kL1)) break;
-            payload |= make_elem<MODE>(e1 >> 8, t.zero_point, t.scale) << (count * Elem<MODE>::size * 8);
+            syms |= (e1 >> 8) << (count * 8);
             pos += len1;
             ++count;
         }
         uint64_t e;
         if (count) {
-            e = pack_entry(payload, pos, count * Elem<MODE>::size);
+            e = pack_entry(syms, pos, count);
         } else {                                                  // long prefix: where its second-level block is
             uint32_t depth = 0, base = 0;
             const uint32_t prefix = __brev(i) >> (32 - kL1);
@@ -269,20 +269,18 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
 }
 
 // Canonical search over the lengths above kL1.  `window` holds the next 32
-// stream bits, first bit in bit 0.
-template <int MODE>
-__device__ __noinline__ uint64_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len,
-                                                  int32_t z, float s) {
+// stream bits, first bit in bit 0.  Returns a one-symbol entry.
+__device__ __noinline__ uint64_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len) {
     const uint32_t v = __brev(window);
     for (uint32_t l = kL1 + 1; l <= max_len; ++l) {
         const uint32_t d = (v >> (32 - l)) - tb.first[l];
-        if (d < tb.cnt[l]) return make_entry<MODE>(tb.sorted[tb.offs[l] + d], l, z, s);
+        if (d < tb.cnt[l]) return pack_entry(tb.sorted[tb.offs[l] + d], l, 1);
     }
-    return make_entry<MODE>(0, 1, z, s);     // not a code (corrupt stream): keep moving
+    return pack_entry(0, 1, 1);     // not a code (corrupt stream): keep moving
 }
 
 // Second-level lookup for a first-level miss e1; `window` holds the next >= 17
-// stream bits.  Returns an entry of zero length if the code is longer still.
+// stream bits.  Returns an entry of zero count if the code is longer still.
 __device__ __forceinline__ uint64_t lookup_l2(const Tables &tb, uint64_t e1, uint32_t window) {
     const uint32_t m = static_cast<uint32_t>(e1);
     const uint32_t sub = __builtin_amdgcn_ubfe(window, kL1, (m >> 16) & 0xffu);
@@ -312,13 +310,12 @@ struct ScalarReader {
 };
 
 // One table entry (one or more symbols) from the scalar reader.
-template <int MODE>
-__device__ __forceinline__ uint64_t next_entry(ScalarReader &r, const Tables &tb, const DevTensor &t) {
+__device__ __forceinline__ uint64_t next_entry(ScalarReader &r, const Tables &tb, uint32_t max_len) {
     uint64_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
-    if (__builtin_expect(entry_len(e) == 0, 0)) {
+    if (__builtin_expect(entry_count(e) == 0, 0)) {
         const uint32_t w = static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off));
         e = lookup_l2(tb, e, w);
-        if (entry_len(e) == 0) e = decode_canonical<MODE>(tb, w, t.max_len, t.zero_point, t.scale);
+        if (entry_count(e) == 0) e = decode_canonical(tb, w, max_len);
         r.pos += entry_len(e);
         r.buf = load_bits(r.stream, r.pos, r.last_off);
     } else {
@@ -344,23 +341,26 @@ __device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, 
     r.pos = t.offsets[k];
     r.buf = 0;
     const uint64_t first_sym = static_cast<uint64_t>(k) * t.chunk_symbols;
+    const uint32_t max_len = t.max_len;
+    const int32_t z = t.zero_point;
+    const float s = t.scale;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
     uint32_t pending = 0;     // low nibble waiting for its partner (packed 4-bit)
     uint32_t i = 0;
     for (uint32_t probe = 0; i < nsym; ++probe) {
         if (probe % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint64_t e = next_entry<MODE>(r, tb, t);
-        const uint32_t count = entry_bytes(e) / Elem<MODE>::size;
+        const uint64_t e = next_entry(r, tb, max_len);
+        const uint32_t count = entry_count(e);
         for (uint32_t c = 0; c < count && i < nsym; ++c, ++i) {
             const uint64_t idx = first_sym + i;
-            const uint32_t v = static_cast<uint32_t>(e >> (c * Elem<MODE>::size * 8));
-            if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(v);
+            const uint32_t sym = (static_cast<uint32_t>(e) >> (c * 8)) & 0xffu;
+            if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
             if (MODE == kModeU4) {
-                if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((v & 0xfu) << 4));
-                else pending = v & 0xfu;
+                if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((sym & 0xfu) << 4));
+                else pending = sym & 0xfu;
             }
-            if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(v);
-            if (MODE == kModeF32) reinterpret_cast<uint32_t *>(t.out)[idx] = v;
+            if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(bf16_bits(dequant(sym, z, s)));
+            if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, z, s);
         }
     }
     if (MODE == kModeU4 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
@@ -411,11 +411,11 @@ __device__ __forceinline__ void ring_init(RingReader &r, const DevTensor &t, uin
 // Retire the blocks p has left behind.  A ring read at q = p - 3 takes the
 // dword holding bit q and the two after it, so it is valid while q is less
 // than 192 bits past the end of block cur.  Between two checks kTripGroups ring
-// reads happen, each followed by kGroup probes of at most 17 bits (both table
-// levels), so the last read starts at most (kTripGroups - 1) * kGroup * 17 =
-// 153 bits past the end of block cur.  A longer code (up to 32 bits) runs its
-// own check first and reads again afterwards; later reads stay within
-// 32 + 9 * 17 = 185.
+// reads happen; a group consumes at most kGroup * kL1 bits through the first
+// level plus one second-level code of at most 17 bits, i.e. 50, so the last
+// read starts at most 3 * 50 = 150 bits past the end of block cur.  A longer
+// code (up to 32 bits) runs its own check first; reads after it stay within
+// 32 + 3 * 50 = 182.
 __device__ __forceinline__ void ring_check(RingReader &r) {
     const uint32_t nb = (r.q + 3u) >> 7;
     while (nb != r.cur) {
@@ -441,66 +441,58 @@ __device__ __forceinline__ uint64_t lut_at(const Tables &tb, uint32_t byte_off) 
     return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
 }
 
-// The few per-tensor scalars the hot loop needs, copied out of the descriptor
-// once so that they stay in registers (the descriptor sits in global memory
-// and would otherwise be re-read after every store).
-struct HotParams {
-    uint32_t max_len;
-    int32_t zero_point;
-    float scale;
-};
-
-// One table probe: decode the codes at the front of the window w, write their
-// elements at byte `out` of the lane's tile row and advance.  w must hold at
-// least 17 valid bits: a fresh window has 61 and each of the kGroup - 1 probes
-// before took at most 17.
-template <int MODE>
-__device__ __forceinline__ void ring_probe(RingReader &r, uint64_t &w, uint8_t *row, uint32_t &out,
-                                           const Tables &tb, const HotParams &hp) {
-    uint64_t e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 3));
-    if (__builtin_expect(entry_len(e) == 0, 0)) {
-        e = lookup_l2(tb, e, static_cast<uint32_t>(w >> 3));
-        if (__builtin_expect(entry_len(e) == 0, 0)) {
-            // longer than the tables resolve: bring the ring up to date (see ring_check), search,
-            // and start the rest of the group from a fresh window
+// One group: a fresh window and kGroup first-level probes without a branch.
+// Each probe writes its four symbol bytes at `out` of the lane's tile row and
+// advances by what the entry says; a lane whose row is full, or whose window
+// starts with a code longer than kL1 bits, advances by nothing (and the probes
+// after it see the same bits).  The long code is then resolved once, behind the
+// probes, through the second level or the canonical search.
+template <int SPB>
+__device__ __forceinline__ void ring_group(RingReader &r, uint8_t *row, uint32_t &out, const Tables &tb,
+                                           uint32_t max_len) {
+    uint64_t w = ring_read(r);
+    uint64_t e = 0;
+#pragma unroll
+    for (int i = 0; i < kGroup; ++i) {
+        e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 3));
+        const uint32_t syms = static_cast<uint32_t>(e);
+        lds_v8 o = (lds_v8)(row + out);
+        o[0] = static_cast<uint8_t>(syms); o[1] = static_cast<uint8_t>(syms >> 8);
+        o[2] = static_cast<uint8_t>(syms >> 16); o[3] = static_cast<uint8_t>(syms >> 24);
+        const uint32_t ctl = out < static_cast<uint32_t>(SPB) ? static_cast<uint32_t>(e >> 48) : 0u;   // len | count << 8
+        w >>= (ctl & 63u);
+        r.q += ctl & 0xffu;
+        out += ctl >> 8;
+    }
+    if (__builtin_expect(out < static_cast<uint32_t>(SPB) && entry_count(e) == 0, 0)) {
+        // w still starts with the long code and holds at least 61 - 2 * 11 valid bits
+        uint64_t e2 = lookup_l2(tb, e, static_cast<uint32_t>(w >> 3));
+        if (__builtin_expect(entry_count(e2) == 0, 0)) {
             ring_check(r);
             w = ring_read(r);
-            e = decode_canonical<MODE>(tb, static_cast<uint32_t>(w >> 3), hp.max_len, hp.zero_point, hp.scale);
-            r.q += entry_len(e);
-            w = ring_read(r);
-            e &= ~(0xffull << 48);           // already consumed
+            e2 = decode_canonical(tb, static_cast<uint32_t>(w >> 3), max_len);
         }
+        *(lds_v8)(row + out) = static_cast<uint8_t>(e2);
+        r.q += entry_len(e2);
+        out += 1;
     }
-    // all three element slots, each with its own naturally aligned write
-    const uint32_t lo = static_cast<uint32_t>(e), hi = static_cast<uint32_t>(e >> 32);
-    if constexpr (Elem<MODE>::size == 2) {
-        lds_v16 o = (lds_v16)(row + out);
-        o[0] = static_cast<uint16_t>(lo); o[1] = static_cast<uint16_t>(lo >> 16); o[2] = static_cast<uint16_t>(hi);
-    } else if constexpr (Elem<MODE>::size == 1) {
-        lds_v8 o = (lds_v8)(row + out);
-        o[0] = static_cast<uint8_t>(lo); o[1] = static_cast<uint8_t>(lo >> 8); o[2] = static_cast<uint8_t>(lo >> 16);
-    } else {
-        *(lds_v32)(row + out) = lo;
-    }
-    const uint32_t ctl = hi >> 16;
-    w >>= (ctl & 63u);
-    r.q += ctl & 0xffu;
-    out += ctl >> 8;
 }
 
 // Decode the workgroup's segments block by block into the wave's LDS tile (one
-// 128-byte row per lane) and write the tile out row-wise, so that every store
-// instruction covers whole rows.
+// row of symbol bytes per lane), then write the tile out row-wise in the output
+// type, so that every store instruction covers whole rows.
 template <int MODE>
-__device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem *wms, uint32_t first_chunk) {
-    constexpr int ESZ = Elem<MODE>::size;
-    constexpr int SPB = kRowBytes / ESZ;                  // symbols per block
-    constexpr int OUT_ROW = SPB * OutTraits<MODE>::ebits / 8;      // bytes a block becomes in memory (64 for packed 4-bit)
+__device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::spb> *wms,
+                                            uint32_t first_chunk) {
+    constexpr int SPB = Cfg<MODE>::spb;
+    constexpr int OUT_ROW = Cfg<MODE>::out_row;
+    constexpr int TS = WaveMem<SPB>::tile_stride;
     constexpr uint32_t LPR = 8;                           // lanes that store one row
     constexpr uint32_t RPI = 64 / LPR;                    // rows per store instruction
+    constexpr uint32_t PIECE = SPB / LPR;                 // symbols one lane converts and stores: 8 or 16
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
-    WaveMem &wm = wms[wave];
+    WaveMem<SPB> &wm = wms[wave];
     const uint32_t wave_first = first_chunk + wave * 64u;
     if (wave_first >= t.n_chunks) return;
     const uint32_t C = t.chunk_symbols;
@@ -524,63 +516,80 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     if (fast) ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * OutTraits<MODE>::ebits) >> 3;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
-    const HotParams hp = {t.max_len, t.zero_point, t.scale};
+    const uint32_t max_len = t.max_len;
+    const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
+    const float scale = t.scale;
     const uint32_t n_chunks = t.n_chunks;
     const uint64_t n_total = t.n;
-    uint8_t *const my_row = reinterpret_cast<uint8_t *>(wm.tile + lane * kTileStride);
-    uint32_t out = 0;                                     // write position in my_row, bytes
+    uint8_t *const my_row = reinterpret_cast<uint8_t *>(wm.tile + lane * TS);
+    // a lane that does not decode keeps its position at the row end: its probes are no-ops
+    uint32_t out = fast ? 0u : static_cast<uint32_t>(SPB);
 
     for (uint32_t bs = 0; bs < blocks_total; ++bs) {
-        // every lane fills its row; a probe may run up to two elements over, which the next block inherits
-        while (__builtin_amdgcn_ballot_w64(fast && out < kRowBytes)) {
+        // every lane fills its row; the last probe may run up to three symbols over, which the next block inherits
+        while (__builtin_amdgcn_ballot_w64(out < static_cast<uint32_t>(SPB))) {
             ring_check(r);
 #pragma unroll
-            for (int g = 0; g < kTripGroups; ++g) {
-                if (fast && out < kRowBytes) {
-                    uint64_t w = ring_read(r);
-#pragma unroll
-                    for (int i = 0; i < kGroup; ++i)
-                        if (out < kRowBytes) ring_probe<MODE>(r, w, my_row, out, tb, hp);
-                }
-            }
+            for (int g = 0; g < kTripGroups; ++g)
+                if (out < static_cast<uint32_t>(SPB)) ring_group<SPB>(r, my_row, out, tb, max_len);
         }
         wave_sync_lds();
 #pragma unroll
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
             const uint32_t rr = it * RPI + lane / LPR;
             const uint32_t piece = lane % LPR;
-            const uint32_t *src = wm.tile + rr * kTileStride + piece * 4u;
-            const u32x4 v = {src[0], src[1], src[2], src[3]};
+            const uint32_t *src = wm.tile + rr * TS + piece * (PIECE / 4);
             const uint32_t kk = wave_first + rr;
             bool full = false;
             if (kk < n_chunks) full = n_total - static_cast<uint64_t>(kk) * C >= C;
-            if (full) {
-                uint8_t *dst = out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * OUT_ROW;
-                if constexpr (MODE == kModeU4) {
-                    // 16 symbols, one per byte -> 8 bytes, even symbol in the low nibble
-                    u32x2 pk;
-                    uint32_t a = (v.x | (v.x >> 4)) & 0x00ff00ffu, b = (v.y | (v.y >> 4)) & 0x00ff00ffu;
-                    pk.x = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
-                    a = (v.z | (v.z >> 4)) & 0x00ff00ffu; b = (v.w | (v.w >> 4)) & 0x00ff00ffu;
-                    pk.y = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
-                    *(global_u2_wptr)(dst + piece * 8u) = pk;
+            uint8_t *dst = out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * OUT_ROW;
+            if constexpr (MODE == kModeU8) {
+                const u32x4 v = {src[0], src[1], src[2], src[3]};
+                if (full) *(global_u4_wptr)(dst + piece * 16u) = v;
+            } else if constexpr (MODE == kModeU4) {
+                // 16 symbols, one per byte -> 8 bytes, even symbol in the low nibble
+                const u32x4 v = {src[0], src[1], src[2], src[3]};
+                u32x2 pk;
+                uint32_t a = (v.x | (v.x >> 4)) & 0x00ff00ffu, b = (v.y | (v.y >> 4)) & 0x00ff00ffu;
+                pk.x = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
+                a = (v.z | (v.z >> 4)) & 0x00ff00ffu; b = (v.w | (v.w >> 4)) & 0x00ff00ffu;
+                pk.y = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
+                if (full) *(global_u2_wptr)(dst + piece * 8u) = pk;
+            } else {
+                // 8 symbols -> w = (q - z) * s: exact difference, one fp32 multiply
+                const uint32_t d0 = src[0], d1 = src[1];
+                float f[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f[j] = (static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf) * scale;
+                    f[4 + j] = (static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf) * scale;
+                }
+                if constexpr (MODE == kModeF32) {
+                    const u32x4 v0 = {__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
+                    const u32x4 v1 = {__float_as_uint(f[4]), __float_as_uint(f[5]), __float_as_uint(f[6]), __float_as_uint(f[7])};
+                    if (full) {
+                        *(global_u4_wptr)(dst + piece * 32u) = v0;
+                        *(global_u4_wptr)(dst + piece * 32u + 16u) = v1;
+                    }
                 } else {
-                    *(global_u4_wptr)(dst + piece * 16u) = v;
+                    u32x4 v;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const f32x2 pr = {f[2 * j], f[2 * j + 1]};
+                        const bf16x2 b = __builtin_convertvector(pr, bf16x2);   // round to nearest even
+                        v[j] = __builtin_bit_cast(uint32_t, b);
+                    }
+                    if (full) *(global_u4_wptr)(dst + piece * 16u) = v;
                 }
             }
         }
         wave_sync_lds();
         // what ran over the row end opens the next row
-        if constexpr (ESZ == 2) {
-            lds_v16 row16 = (lds_v16)my_row;
-            const uint16_t s0 = row16[kRowBytes / 2], s1 = row16[kRowBytes / 2 + 1];
-            row16[0] = s0; row16[1] = s1;
-        } else if constexpr (ESZ == 1) {
-            lds_v8 row8 = (lds_v8)my_row;
-            const uint8_t s0 = row8[kRowBytes], s1 = row8[kRowBytes + 1];
-            row8[0] = s0; row8[1] = s1;
+        if (fast) {
+            const uint32_t spill = *reinterpret_cast<const uint32_t *>(my_row + SPB);
+            *reinterpret_cast<uint32_t *>(my_row) = spill;
+            out -= static_cast<uint32_t>(SPB);
         }
-        out = out > kRowBytes ? out - kRowBytes : 0u;
     }
     if (!fast && nsym) decode_scalar<MODE>(t, tb, k, nsym);
 }
@@ -599,9 +608,12 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     r.last_off = t.stream_bytes - 8u;
     r.pos = t.offsets[k];
     r.buf = 0;
+    const uint32_t max_len = t.max_len;
+    const int32_t z = t.zero_point;
+    const uint32_t cols = t.cols;
 
-    uint32_t row = static_cast<uint32_t>(first_sym / t.cols);
-    uint32_t col = static_cast<uint32_t>(first_sym - static_cast<uint64_t>(row) * t.cols);
+    uint32_t row = static_cast<uint32_t>(first_sym / cols);
+    uint32_t col = static_cast<uint32_t>(first_sym - static_cast<uint64_t>(row) * cols);
     const uint32_t start_col = col;
     bool first_fragment = true;
     float acc = 0.0f;
@@ -609,13 +621,13 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     uint32_t i = 0;
     for (uint32_t probe = 0; i < nsym; ++probe) {
         if (probe % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint64_t e = next_entry<MODE>(r, tb, t);
-        const uint32_t count = entry_bytes(e);
+        const uint64_t e = next_entry(r, tb, max_len);
+        const uint32_t count = entry_count(e);
         for (uint32_t c = 0; c < count && i < nsym; ++c, ++i) {
-            const uint32_t sym = static_cast<uint32_t>(e >> (c * 8)) & 0xffu;
+            const uint32_t sym = (static_cast<uint32_t>(e) >> (c * 8)) & 0xffu;
             const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
-            acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - t.zero_point), xv, acc);
-            if (++col == t.cols) {
+            acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - z), xv, acc);
+            if (++col == cols) {
                 if (first_fragment && start_col != 0) {
                     head = acc;                              // row began in an earlier segment
                 } else {
@@ -640,44 +652,43 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     }
 }
 
+// The GEMV kernels need the tables and the scratch table only.
+template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::spb> wm[Cfg<MODE>::waves]; };
+static_assert(sizeof(WaveMem<64>) >= sizeof(uint32_t) << kL1, "scratch table must fit into one wave's buffers");
+
 template <int MODE>
-__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, Tables &tb, WaveMem *wms) {
+__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, SmemFor<MODE> &sm) {
+    constexpr int WG = 64 * Cfg<MODE>::waves;
     // the single-symbol scratch table lives in the first wave's buffers, which are not in use yet
-    build_tables<MODE>(t, tb, reinterpret_cast<uint32_t *>(wms));
+    build_tables<WG>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
     if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
         const uint32_t k = first_chunk + threadIdx.x;
-        if (k < t.n_chunks) gemv_segment<MODE>(t, tb, k);
+        if (k < t.n_chunks) gemv_segment<MODE>(t, sm.tb, k);
     } else {
-        if (t.chunk_symbols % (kRowBytes / Elem<MODE>::size) == 0) {
-            decode_rows<MODE>(t, tb, wms, first_chunk);
+        if (t.chunk_symbols % Cfg<MODE>::spb == 0) {
+            decode_rows<MODE>(t, sm.tb, sm.wm, first_chunk);
         } else {                                             // segment size does not tile into blocks
             const uint32_t k = first_chunk + threadIdx.x;
             if (k < t.n_chunks) {
                 const uint64_t left = t.n - static_cast<uint64_t>(k) * t.chunk_symbols;
-                decode_scalar<MODE>(t, tb, k, left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols);
+                decode_scalar<MODE>(t, sm.tb, k, left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols);
             }
         }
     }
 }
 
-// The GEMV kernels need the tables and the scratch table only.
-template <int MODE> struct SmemFor { Tables tb; WaveMem wm[kWaves]; };
-template <> struct SmemFor<kModeGemvF32> { Tables tb; WaveMem wm[1]; };
-template <> struct SmemFor<kModeGemvBF16> { Tables tb; WaveMem wm[1]; };
-static_assert(sizeof(WaveMem) >= sizeof(uint32_t) << kL1, "scratch table must fit into one wave's buffers");
-
 template <int MODE>
-__global__ __launch_bounds__(kWG) void k_single(const DevTensor t) {
+__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t) {
     __shared__ SmemFor<MODE> sm;
-    run_item<MODE>(t, blockIdx.x * kWG, sm.tb, sm.wm);
+    run_item<MODE>(t, blockIdx.x * (64 * Cfg<MODE>::waves), sm);
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kWG) void k_batch(const DevTensor *__restrict__ tensors,
-                                               const WorkItem *__restrict__ items) {
+__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor *__restrict__ tensors,
+                                                                 const WorkItem *__restrict__ items) {
     __shared__ SmemFor<MODE> sm;
     const WorkItem it = items[blockIdx.x];
-    run_item<MODE>(tensors[it.tensor], it.first, sm.tb, sm.wm);
+    run_item<MODE>(tensors[it.tensor], it.first, sm);
 }
 
 // Second stage of the GEMV: rows that straddle segments are summed in segment order.
@@ -756,9 +767,11 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     if (t->stream_bytes < 32 || (t->stream_bytes & 15u) || t->stream_bytes >= (uint64_t{1} << 32))
         return ENTRO_ERR_SIZE;
     const uint64_t n_chunks = entro_num_chunks(t->n, t->chunk_symbols);
-    if (n_chunks >= (uint64_t{1} << 32) - kWG) return ENTRO_ERR_SIZE;
+    if (n_chunks >= (uint64_t{1} << 32) - 1024) return ENTRO_ERR_SIZE;
     if (!aligned16(t->stream) || !aligned16(t->offsets) || !aligned16(t->out)) return ENTRO_ERR_ALIGN;
     if (op != ENTRO_OP_DECODE && t->qp.bits != bits) return ENTRO_ERR_BITS;
+    // the kernels subtract the zero-point in fp32, which must represent it exactly
+    if (op != ENTRO_OP_DECODE && (t->qp.zero_point > (1 << 24) || t->qp.zero_point < -(1 << 24))) return ENTRO_ERR_RANGE;
     if (op == ENTRO_OP_GEMV) {
         if (!t->x) return ENTRO_ERR_NULL;
         if (!aligned16(t->x)) return ENTRO_ERR_ALIGN;
@@ -783,6 +796,11 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     dt->need_fix = (op == ENTRO_OP_GEMV && (t->chunk_symbols % t->cols) != 0) ? 1u : 0u;
     std::memcpy(dt->len, t->cb->len, 256);
     return ENTRO_OK;
+}
+
+// Lanes per workgroup of the main kernel of an operation.
+unsigned wg_of(entro_op op) {
+    return op == ENTRO_OP_DECODE ? kWgDecode : op == ENTRO_OP_DEQUANT ? kWgDequant : kWgGemv;
 }
 
 int mode_of(entro_op op, entro_dtype d) {
@@ -814,9 +832,10 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     if (st != ENTRO_OK) return st;
     dt.partials = partials;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const unsigned grid = (dt.n_chunks + kWG - 1) / kWG;
+    const unsigned wg = wg_of(op);
+    const unsigned grid = (dt.n_chunks + wg - 1) / wg;
     const int mode = mode_of(op, d);
-    dispatch_mode(mode, [&](auto m) { hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(kWG), 0, s, dt); });
+    dispatch_mode(mode, [&](auto m) { hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(wg), 0, s, dt); });
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
         const unsigned g2 = (dt.rows + kFixWG - 1) / kFixWG;
@@ -840,7 +859,7 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
     for (uint32_t i = 0; i < count; ++i) {
         if (ts[i].chunk_symbols == 0 || ts[i].n == 0) return false;
         const uint64_t nc = entro_num_chunks(ts[i].n, ts[i].chunk_symbols);
-        items += (nc + kWG - 1) / kWG;
+        items += (nc + wg_of(op) - 1) / wg_of(op);
         if (op == ENTRO_OP_GEMV && ts[i].cols && (ts[i].chunk_symbols % ts[i].cols) != 0) {
             fix += (static_cast<uint64_t>(ts[i].rows) + kFixWG - 1) / kFixWG;
             partial_floats += 2 * nc;
@@ -915,7 +934,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, &dts[i]);
         if (st != ENTRO_OK) return st;
-        for (uint32_t c = 0; c < dts[i].n_chunks; c += kWG) items[n_items++] = WorkItem{i, c};
+        for (uint32_t c = 0; c < dts[i].n_chunks; c += wg_of(op)) items[n_items++] = WorkItem{i, c};
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
@@ -952,7 +971,7 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const WorkItem *fix = reinterpret_cast<const WorkItem *>(ws + plan->off_fix);
     const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out));
     dispatch_mode(mode, [&](auto m) {
-        hipLaunchKernelGGL(k_batch<decltype(m)::value>, dim3(plan->n_items), dim3(kWG), 0, s, dts, items);
+        hipLaunchKernelGGL(k_batch<decltype(m)::value>, dim3(plan->n_items), dim3(wg_of(static_cast<entro_op>(plan->op))), 0, s, dts, items);
     });
     if (!hip_ok(hipGetLastError(), "launch batched decode kernel")) return ENTRO_ERR_DEVICE;
     if (plan->n_fix) {
