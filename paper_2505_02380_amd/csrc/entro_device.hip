@@ -478,18 +478,24 @@ __device__ __forceinline__ void ring_group(RingReader &r, uint8_t *row, uint32_t
     }
 }
 
+template <int MODE>
+__device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &tb, uint32_t k);
+
 // Decode the workgroup's segments block by block into the wave's LDS tile (one
-// row of symbol bytes per lane), then write the tile out row-wise in the output
-// type, so that every store instruction covers whole rows.
+// row of symbol bytes per lane), then consume the tile row-wise: write it out in
+// the output type, so that every store instruction covers whole rows, or (GEMV)
+// multiply it into the activation vector.
 template <int MODE>
 __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::spb> *wms,
                                             uint32_t first_chunk) {
+    constexpr bool GEMV = MODE == kModeGemvF32 || MODE == kModeGemvBF16;
     constexpr int SPB = Cfg<MODE>::spb;
     constexpr int OUT_ROW = Cfg<MODE>::out_row;
     constexpr int TS = WaveMem<SPB>::tile_stride;
-    constexpr uint32_t LPR = 8;                           // lanes that store one row
-    constexpr uint32_t RPI = 64 / LPR;                    // rows per store instruction
-    constexpr uint32_t PIECE = SPB / LPR;                 // symbols one lane converts and stores: 8 or 16
+    constexpr uint32_t LPR = 8;                           // lanes that consume one row
+    constexpr uint32_t RPI = 64 / LPR;                    // rows per pass
+    constexpr uint32_t PIECE = SPB / LPR;                 // symbols one lane converts: 8 or 16
+    constexpr uint32_t EBITS = GEMV ? 0 : OutTraits<GEMV ? kModeU8 : MODE>::ebits;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     WaveMem<SPB> &wm = wms[wave];
@@ -514,7 +520,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     r.nx = u32x4{0u, 0u, 0u, 0u};
     r.ring = wm.ring + lane * kRingStride;
     if (fast) ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
-    const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * OutTraits<MODE>::ebits) >> 3;
+    const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
     const uint32_t max_len = t.max_len;
     const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
@@ -524,6 +530,23 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     uint8_t *const my_row = reinterpret_cast<uint8_t *>(wm.tile + lane * TS);
     // a lane that does not decode keeps its position at the row end: its probes are no-ops
     uint32_t out = fast ? 0u : static_cast<uint32_t>(SPB);
+
+    // GEMV: the lane sums, for the eight rows it serves, its eight-symbol piece of every block.
+    // A segment is at most as long as a matrix row here, so it touches one row (acc_a) or the
+    // end of one and the start of the next (acc_b).
+    const uint32_t cols = t.cols;
+    const uint16_t *xvec = t.x;
+    float acc_a[64 / RPI], acc_b[64 / RPI];
+    uint32_t col0[64 / RPI];
+    if constexpr (GEMV) {
+#pragma unroll
+        for (uint32_t it = 0; it < 64 / RPI; ++it) {
+            const uint32_t kk = wave_first + it * RPI + lane / LPR;
+            acc_a[it] = 0.0f;
+            acc_b[it] = 0.0f;
+            col0[it] = static_cast<uint32_t>((static_cast<uint64_t>(kk) * C) % cols);
+        }
+    }
 
     for (uint32_t bs = 0; bs < blocks_total; ++bs) {
         // every lane fills its row; the last probe may run up to three symbols over, which the next block inherits
@@ -543,7 +566,26 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             bool full = false;
             if (kk < n_chunks) full = n_total - static_cast<uint64_t>(kk) * C >= C;
             uint8_t *dst = out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * OUT_ROW;
-            if constexpr (MODE == kModeU8) {
+            if constexpr (GEMV) {
+                const uint32_t d0 = src[0], d1 = src[1];
+                if (full) {
+                    uint32_t col = col0[it] + bs * SPB + piece * PIECE;
+                    const bool second = col >= cols;                  // past the row end: next row, from column 0
+                    col -= second ? cols : 0u;
+                    const u32x4 xv = *(global_u4_ptr)(xvec + col);    // eight bf16 activations
+                    float part = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t xa = j < 2 ? xv[0] : xv[1], xb = j < 2 ? xv[2] : xv[3];
+                        const float x0 = __uint_as_float((j & 1) ? (xa & 0xffff0000u) : (xa << 16));
+                        const float x1 = __uint_as_float((j & 1) ? (xb & 0xffff0000u) : (xb << 16));
+                        part = fmaf(static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf, x0, part);
+                        part = fmaf(static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf, x1, part);
+                    }
+                    acc_a[it] += second ? 0.0f : part;
+                    acc_b[it] += second ? part : 0.0f;
+                }
+            } else if constexpr (MODE == kModeU8) {
                 const u32x4 v = {src[0], src[1], src[2], src[3]};
                 if (full) *(global_u4_wptr)(dst + piece * 16u) = v;
             } else if constexpr (MODE == kModeU4) {
@@ -591,7 +633,34 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             out -= static_cast<uint32_t>(SPB);
         }
     }
-    if (!fast && nsym) decode_scalar<MODE>(t, tb, k, nsym);
+    if constexpr (GEMV) {
+        // the eight lanes of a row add up their pieces; the first of them publishes the result
+#pragma unroll
+        for (uint32_t it = 0; it < 64 / RPI; ++it) {
+            float a = acc_a[it], b = acc_b[it];
+#pragma unroll
+            for (int m = 1; m < 8; m <<= 1) {
+                a += __shfl_xor(a, m, 64);
+                b += __shfl_xor(b, m, 64);
+            }
+            const uint32_t kk = wave_first + it * RPI + lane / LPR;
+            bool full = false;
+            if (kk < n_chunks) full = n_total - static_cast<uint64_t>(kk) * C >= C;
+            if (full && (lane % LPR) == 0) {
+                if (t.need_fix) {                                   // row fragments: summed by the second stage
+                    t.partials[2 * static_cast<uint64_t>(kk)] = a;
+                    t.partials[2 * static_cast<uint64_t>(kk) + 1] = b;
+                } else {                                            // segment == row
+                    const float y = a * scale;
+                    if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[kk] = y;
+                    else reinterpret_cast<uint16_t *>(t.out)[kk] = static_cast<uint16_t>(bf16_bits(y));
+                }
+            }
+        }
+        if (!fast && nsym) gemv_segment<MODE>(t, tb, k);
+    } else {
+        if (!fast && nsym) decode_scalar<(GEMV ? kModeU8 : MODE)>(t, tb, k, nsym);
+    }
 }
 
 // Decode one segment straight into dot products with x.  A segment covers one
@@ -662,8 +731,14 @@ __device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chun
     // the single-symbol scratch table lives in the first wave's buffers, which are not in use yet
     build_tables<WG>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
     if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
-        const uint32_t k = first_chunk + threadIdx.x;
-        if (k < t.n_chunks) gemv_segment<MODE>(t, sm.tb, k);
+        // row path: a segment tiles into blocks, pieces of eight never straddle a matrix row,
+        // and a segment touches at most two rows
+        if (t.chunk_symbols % Cfg<MODE>::spb == 0 && t.cols % 8 == 0 && t.cols >= t.chunk_symbols) {
+            decode_rows<MODE>(t, sm.tb, sm.wm, first_chunk);
+        } else {
+            const uint32_t k = first_chunk + threadIdx.x;
+            if (k < t.n_chunks) gemv_segment<MODE>(t, sm.tb, k);
+        }
     } else {
         if (t.chunk_symbols % Cfg<MODE>::spb == 0) {
             decode_rows<MODE>(t, sm.tb, sm.wm, first_chunk);
