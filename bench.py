@@ -20,6 +20,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_batch_bf16_mistral7b_pmc_hbm_bytes.txt")
+
+
+def measured_traffic():
+    """HBM bytes per launch of the headline kernel as the rocprofv3 byte counters gave them
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size); None when no summary is there."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def log(msg):
@@ -153,7 +167,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_batch<bf16>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": round(kern_ms, 4),
-                     "traffic": None},
+                     "traffic": measured_traffic() if args.layers == 32 else None},
     }
 
     # ------------------------------------------------------------ extra legs: u8 and GEMV

@@ -621,7 +621,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                         const bf16x2 b = __builtin_convertvector(pr, bf16x2);   // round to nearest even
                         v[j] = __builtin_bit_cast(uint32_t, b);
                     }
-                    if (full) *(global_u4_wptr)(dst + piece * 16u) = v;
+                    if (full) __builtin_nontemporal_store(v, (global_u4_wptr)(dst + piece * 16u));
                 }
             }
         }
