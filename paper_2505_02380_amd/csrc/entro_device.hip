@@ -30,18 +30,20 @@
 
 namespace {
 
-constexpr int kL1 = 11;                  // stream bits that index the first-level table
+constexpr int kL1 = 14;                  // stream bits that index the first-level table
 constexpr uint32_t kL1Mask = (1u << kL1) - 1u;
-constexpr int kMaxSyms = 4;              // symbols one first-level entry can carry
 constexpr int kL2Cap = 512;              // second-level entries (all long prefixes together)
-constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 17 bits
+constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 20 bits
 constexpr int kL2MaxPrefixes = 64;       // more long prefixes than this: second level unused
-constexpr int kGroup = 3;                // table probes per ring read: 61 valid bits >= 3 * 11 + 17
-constexpr int kTripGroups = 4;           // ring reads between two refill checks (see ring_check)
-constexpr int kScalarProbes = 3;         // scalar reader: probes per 64-bit load, 33 valid bits >= 3 * kL1
-constexpr int kRingStride = 19;          // dwords per lane: 4 x 16-byte slots, 2 mirror dwords, pad (odd)
-constexpr int kRowSlack = 8;             // tile bytes behind a row: 3 symbols run over, 4 more are written blind
+constexpr int kGroup = 4;                // symbols per ring read: 63 valid bits >= 4 * 14
+constexpr int kTripGroups = 4;           // ring reads between two checks of the ring's fill
+constexpr int kScalarProbes = 2;         // scalar reader: symbols per 64-bit load, 33 valid bits >= 2 * kL1
+constexpr int kRingBits = 1024;          // a lane's ring: two 64-byte lines (eight 16-byte blocks)
+constexpr int kRingDwords = kRingBits / 32 + 2;   // and two mirror dwords
+constexpr int kGroupBits = kGroup * kL1;           // most stream bits a group takes through the first level
+constexpr int kTripBits = (kTripGroups - 1) * kGroupBits + 64;   // a trip's last ring read ends this far past its start
 constexpr uint32_t kMaxChunkSymbols = 1u << 20;
+static_assert(kGroup * kL1 <= 63 && kGroup == 4, "a group packs four symbol bytes into one dword");
 
 // What the kernels read about one tensor.  Lives in kernel arguments (single
 // tensor calls) or in the workspace table (batched calls).
@@ -72,16 +74,17 @@ struct WorkItem {
 
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5 };
 
-// Per output mode: symbols a lane decodes per block (= bytes of its tile row),
-// waves per workgroup (what fits into the 160 KB of LDS) and bytes a block
-// becomes in memory.  The host glue sizes its launches with the same numbers.
+// Per output mode: symbols of a lane that one flush takes (= bytes of its tile
+// row), waves per workgroup (what fits into the 160 KB of LDS), symbols one lane
+// converts per flush pass (a 16-byte store for all but fp32) and bytes that a
+// row becomes in memory.  The host glue sizes its launches with the same numbers.
 template <int MODE> struct Cfg;
-template <> struct Cfg<kModeU8> { static constexpr int spb = 128, waves = 10, out_row = 128; };
-template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 10, out_row = 64; };
-template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 14, out_row = 256; };
-template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 14, out_row = 128; };
-template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 4, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 4, out_row = 0; };
+template <> struct Cfg<kModeU8> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 128; };
+template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 64; };
+template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 256; };
+template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 128; };
+template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 4, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 4, piece = 8, out_row = 0; };
 constexpr int kWgDecode = 64 * Cfg<kModeU8>::waves;
 constexpr int kWgDequant = 64 * Cfg<kModeBF16>::waves;
 constexpr int kWgGemv = 64 * Cfg<kModeGemvF32>::waves;
@@ -89,37 +92,40 @@ static_assert(Cfg<kModeU8>::waves == Cfg<kModeU4>::waves && Cfg<kModeF32>::waves
               "one workgroup size per operation");
 
 // Lookup tables of one workgroup (LDS).
-// Symbol entry (64 bits): bits 0..31 up to four decoded symbols, first one
-// lowest; bits 48..55 the stream bits they take together; bits 56..63 their
-// number.  A probe writes all four bytes; those past the entry's own symbols are
-// overwritten by the next probe.
-// First level: indexed by the next kL1 stream bits, holds every run of whole
-// codes that fits into them.  A zero count marks a prefix whose first code is
-// longer than kL1 bits; bits 0..15 then are the base and bits 16..23 the depth
-// of the prefix's block in the second level.
-// Second level: one symbol per entry, indexed by the following `depth` stream
-// bits; a zero count there sends the lane to the canonical search
+// Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
+// entry serves as a 64-bit shift amount as it stands.
+// First level: indexed by the next kL1 stream bits.  A zero length marks a prefix
+// whose code is longer than kL1 bits (a lane that looks one up does not move);
+// bits 6..8 then are the depth of the prefix's block in the second level (7: it
+// has none) and bits 9..14 the block's start in units of eight entries.
+// Second level: per long prefix a block indexed by the following `depth` stream
+// bits; zero there sends the lane to the canonical search
 // (first / cnt / offs / sorted).
 struct alignas(16) Tables {
-    uint64_t lut[1 << kL1];
-    uint64_t lut2[kL2Cap];
+    uint16_t lut[1 << kL1];
+    uint16_t lut2[kL2Cap];
     uint32_t cnt[ENTRO_MAX_CODE_LEN + 2];
     uint32_t first[ENTRO_MAX_CODE_LEN + 2];
     uint32_t offs[ENTRO_MAX_CODE_LEN + 2];
     uint32_t pdepth[kL2MaxPrefixes];     // per long prefix: bits its second-level block resolves
-    uint32_t pbase[kL2MaxPrefixes];
+    uint32_t pbase[kL2MaxPrefixes];      // and where the block starts (a multiple of 8)
     uint32_t first_prefix;               // smallest kL1-bit prefix of a long code; 2^kL1 if level 2 is unused
-    uint32_t pad[3];
+    uint32_t long_start;                 // the same, but kept when level 2 is unused
+    uint32_t pad[2];
     uint8_t sorted[256];
-    uint8_t lens[256];
 };
 
-// Per-wave LDS: the lanes' stream windows and their output rows.
+// Per-wave LDS: the lanes' stream rings and their output rows.
+// The ring is stored dword-major (dword d of lane l at d * 64 + l): whatever
+// dword each lane reads, lane l stays on bank l % 32.  A tile row holds the SPB
+// symbol bytes a lane decodes between two flushes; all lanes write the same
+// dword of their rows at the same time, and the odd dword stride puts those on
+// different banks, as it does for the row-wise reads of the flush.
 template <int SPB>
 struct alignas(16) WaveMem {
-    static constexpr int tile_stride = (SPB + kRowSlack) / 4 + 1;       // dwords per lane, odd
+    static constexpr int tile_stride = SPB / 4 + 1;
     static_assert(tile_stride % 2 == 1, "odd stride keeps the lanes' rows on different banks");
-    uint32_t ring[64 * kRingStride];
+    uint32_t ring[kRingDwords * 64];
     uint32_t tile[64 * tile_stride];
 };
 
@@ -130,9 +136,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef const u32x4 __attribute__((address_space(1))) *global_u4_ptr;
 typedef u32x4 __attribute__((address_space(1))) *global_u4_wptr;
 typedef u32x2 __attribute__((address_space(1))) *global_u2_wptr;
-// volatile LDS byte pointer: keeps the compiler from fusing neighbouring byte
-// writes into one wider, unaligned LDS access
-typedef volatile uint8_t __attribute__((address_space(3))) *lds_v8;
+// LDS pointers with the address space spelled out: the accesses compile to plain
+// ds_ instructions with 32-bit addresses
+typedef volatile uint32_t __attribute__((address_space(3))) *lds_v32;
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -144,11 +150,9 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
     return static_cast<float>(static_cast<int32_t>(sym) - z) * s;
 }
 
-__device__ __forceinline__ uint64_t pack_entry(uint32_t syms, uint32_t len, uint32_t count) {
-    return syms | (static_cast<uint64_t>(len) << 48) | (static_cast<uint64_t>(count) << 56);
-}
-__device__ __forceinline__ uint32_t entry_len(uint64_t e) { return static_cast<uint32_t>(e >> 48) & 0xffu; }
-__device__ __forceinline__ uint32_t entry_count(uint64_t e) { return static_cast<uint32_t>(e >> 56); }
+__device__ __forceinline__ uint32_t pack_entry(uint32_t sym, uint32_t len) { return len | (sym << 8); }
+__device__ __forceinline__ uint32_t entry_len(uint32_t e) { return e & 0x3fu; }
+__device__ __forceinline__ uint32_t entry_sym(uint32_t e) { return e >> 8; }
 
 __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -156,43 +160,66 @@ __device__ __forceinline__ void wave_sync_lds() {
 }
 
 // Canonical code tables and both lookup levels, built from the 256 (or 16)
-// code lengths by the whole workgroup of WG lanes.  `lut1` is scratch for a
-// single-symbol table of 2^kL1 words (len | symbol << 8, zero for long prefixes).
+// code lengths by the whole workgroup of WG >= 256 lanes (four waves hold the
+// symbols).  `wcnt` is scratch of 4 * 33 words.
 template <int WG>
-__device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
-    const int tid = threadIdx.x;
+__device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
+    static_assert(WG >= 256, "one lane per symbol");
+    const uint32_t tid = threadIdx.x;
+    const uint32_t wave = tid >> 6;
     const uint32_t l = tid < 256 ? t.len[tid] : 0u;
-    if (tid < 256) tb.lens[tid] = static_cast<uint8_t>(l);
-    if (tid < ENTRO_MAX_CODE_LEN + 2) tb.cnt[tid] = 0;
     if (tid < kL2MaxPrefixes) tb.pdepth[tid] = 0;
-    for (int i = tid; i < (1 << kL1); i += WG) lut1[i] = 1u;             // symbol 0, one bit: filler of incomplete codes
-    for (int i = tid; i < kL2Cap; i += WG) tb.lut2[i] = 0;
+    for (uint32_t i = tid; i < kL2Cap; i += WG) tb.lut2[i] = 0;
+    // symbols of each length per wave, and every symbol's place among those of its length in its wave
+    uint32_t rank = 0;
+    if (tid < 256) {
+        for (uint32_t b = 1; b <= ENTRO_MAX_CODE_LEN; ++b) {
+            const uint64_t m = __builtin_amdgcn_ballot_w64(l == b);
+            if (l == b) rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
+            if ((tid & 63u) == 0) wcnt[wave * (ENTRO_MAX_CODE_LEN + 1) + b] = static_cast<uint32_t>(__builtin_popcountll(m));
+        }
+    }
     __syncthreads();
-    if (l) atomicAdd(&tb.cnt[l], 1u);
+    if (tid >= 1 && tid <= ENTRO_MAX_CODE_LEN + 1) {
+        // lane b: symbols shorter than b, and the first code of length b = sum over j < b of cnt[j] * 2^(b - j)
+        const uint32_t b = tid;
+        uint64_t code = 0;
+        uint32_t off = 0, mine = 0;
+        for (uint32_t j = 1; j <= b && j <= ENTRO_MAX_CODE_LEN; ++j) {
+            const uint32_t c = wcnt[j] + wcnt[(ENTRO_MAX_CODE_LEN + 1) + j] + wcnt[2 * (ENTRO_MAX_CODE_LEN + 1) + j] +
+                               wcnt[3 * (ENTRO_MAX_CODE_LEN + 1) + j];
+            if (j < b) {
+                code += static_cast<uint64_t>(c) << (b - j);
+                off += c;
+            } else {
+                mine = c;
+            }
+        }
+        tb.cnt[b] = b <= ENTRO_MAX_CODE_LEN ? mine : 0u;
+        tb.first[b] = static_cast<uint32_t>(code);
+        tb.offs[b] = off;
+    }
+    if (tid == 0) { tb.cnt[0] = 0; tb.first[0] = 0; tb.offs[0] = 0; }
     __syncthreads();
     if (tid == 0) {
-        uint64_t code = 0;
-        uint32_t off = 0;
-        uint32_t first_prefix = 1u << kL1;                        // no long code seen yet
-        for (int b = 1; b <= ENTRO_MAX_CODE_LEN; ++b) {
-            code = (code + (b > 1 ? tb.cnt[b - 1] : 0u)) << 1;
-            tb.first[b] = static_cast<uint32_t>(code);
-            tb.offs[b] = off;
-            off += tb.cnt[b];
-            if (b > kL1 && tb.cnt[b] && first_prefix == (1u << kL1))
-                first_prefix = static_cast<uint32_t>(code >> (b - kL1));
-        }
-        // canonical codes grow with length, so the long codes own the prefixes
-        // first_prefix .. 2^kL1 - 1
+        // canonical codes grow with length, so the long codes own the kL1-bit prefixes from the
+        // first long code's on
+        uint32_t first_prefix = 1u << kL1;
+        for (uint32_t b = kL1 + 1; b <= ENTRO_MAX_CODE_LEN; ++b)
+            if (tb.cnt[b]) {
+                first_prefix = tb.first[b] >> (b - kL1);
+                break;
+            }
+        tb.long_start = first_prefix;
         if ((1u << kL1) - first_prefix > static_cast<uint32_t>(kL2MaxPrefixes)) first_prefix = 1u << kL1;
         tb.first_prefix = first_prefix;
     }
     __syncthreads();
-    uint32_t code = 0, rank = 0;
+    uint32_t code = 0;
     const uint32_t first_prefix = tb.first_prefix;
     const bool have_l2 = first_prefix < (1u << kL1);
     if (l) {
-        for (int s = 0; s < tid; ++s) rank += (tb.lens[s] == l);
+        for (uint32_t w = 0; w < wave; ++w) rank += wcnt[w * (ENTRO_MAX_CODE_LEN + 1) + l];
         code = tb.first[l] + rank;
         tb.sorted[tb.offs[l] + rank] = static_cast<uint8_t>(tid);
         if (l > kL1 && have_l2) atomicMax(&tb.pdepth[(code >> (l - kL1)) - first_prefix], l - kL1);
@@ -204,7 +231,10 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
         uint32_t cap = kL2MaxBits;
         for (;;) {
             uint32_t total = 0;
-            for (uint32_t q = 0; q < n_prefix; ++q) total += 1u << (tb.pdepth[q] < cap ? tb.pdepth[q] : cap);
+            for (uint32_t q = 0; q < n_prefix; ++q) {
+                const uint32_t d = tb.pdepth[q] < cap ? tb.pdepth[q] : cap;
+                total += d < 3 ? 8u : 1u << d;
+            }
             if (total <= static_cast<uint32_t>(kL2Cap) || cap == 0) break;
             --cap;
         }
@@ -213,83 +243,87 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *lut1) {
             const uint32_t d = tb.pdepth[q] < cap ? tb.pdepth[q] : cap;
             tb.pdepth[q] = d;
             tb.pbase[q] = base;
-            base += 1u << d;
+            base += d < 3 ? 8u : 1u << d;
         }
     }
     __syncthreads();
-    if (l) {
-        if (l <= kL1) {
-            const uint32_t rev = __brev(code) >> (32 - l);        // first code bit -> bit 0
-            const uint32_t e1 = l | (static_cast<uint32_t>(tid) << 8);
-            for (uint32_t i = rev; i < (1u << kL1); i += (1u << l)) lut1[i] = e1;
-        } else {
-            const uint32_t extra = l - kL1;
-            const uint32_t prefix = code >> extra;
-            lut1[__brev(prefix) >> (32 - kL1)] = 0;              // first code longer than kL1 bits
-            if (have_l2) {
-                const uint32_t depth = tb.pdepth[prefix - first_prefix];
-                const uint32_t base = tb.pbase[prefix - first_prefix];
-                if (extra <= depth) {
-                    const uint64_t e = pack_entry(tid, l, 1);
-                    const uint32_t suffix = code & ((1u << extra) - 1u);
-                    const uint32_t rev = __brev(suffix) >> (32 - extra);
-                    for (uint32_t i = rev; i < (1u << depth); i += (1u << extra)) tb.lut2[base + i] = e;
-                }
-                // longer codes keep the zero entry: canonical search
-            }
+    // second level: every long symbol fills the slots of its block that start with its code
+    if (l > kL1 && have_l2) {
+        const uint32_t extra = l - kL1;
+        const uint32_t prefix = code >> extra;
+        const uint32_t depth = tb.pdepth[prefix - first_prefix];
+        const uint32_t base = tb.pbase[prefix - first_prefix];
+        if (extra <= depth) {
+            const uint16_t e = static_cast<uint16_t>(pack_entry(tid, l));
+            const uint32_t suffix = code & ((1u << extra) - 1u);
+            const uint32_t rev = __brev(suffix) >> (32 - extra);
+            for (uint32_t i = rev; i < (1u << depth); i += (1u << extra)) tb.lut2[base + i] = e;
         }
+        // longer codes keep the zero entry: canonical search
     }
-    __syncthreads();
-    // first level: all whole codes that fit into the kL1 index bits
+    // first level: every lane resolves its share of the index values by a canonical search whose
+    // limits sit in scalar registers
+    const uint32_t long_start = tb.long_start;
+    uint32_t fb[kL1 + 1], cb[kL1 + 1], ob[kL1 + 1];
+#pragma unroll
+    for (int b = 1; b <= kL1; ++b) {
+        fb[b] = __builtin_amdgcn_readfirstlane(tb.first[b]);
+        cb[b] = __builtin_amdgcn_readfirstlane(tb.cnt[b]);
+        ob[b] = __builtin_amdgcn_readfirstlane(tb.offs[b]);
+    }
     for (uint32_t i = tid; i < (1u << kL1); i += WG) {
-        uint32_t pos = 0, count = 0, syms = 0;
-        while (count < static_cast<uint32_t>(kMaxSyms)) {
-            const uint32_t e1 = lut1[i >> pos];
-            const uint32_t len1 = e1 & 0xffu;
-            if (len1 == 0 || pos + len1 > static_cast<uint32_t>(kL1)) break;
-            syms |= (e1 >> 8) << (count * 8);
-            pos += len1;
-            ++count;
+        const uint32_t v = __brev(i) >> (32 - kL1);               // the index bits in code order
+        uint32_t len = 0, idx = 0;
+#pragma unroll
+        for (int b = 1; b <= kL1; ++b) {
+            const uint32_t d = (v >> (kL1 - b)) - fb[b];
+            const bool hit = d < cb[b];                           // at most one length matches
+            len = hit ? static_cast<uint32_t>(b) : len;
+            idx = hit ? ob[b] + d : idx;
         }
-        uint64_t e;
-        if (count) {
-            e = pack_entry(syms, pos, count);
-        } else {                                                  // long prefix: where its second-level block is
-            uint32_t depth = 0, base = 0;
-            const uint32_t prefix = __brev(i) >> (32 - kL1);
-            if (have_l2 && prefix >= first_prefix) {
-                depth = tb.pdepth[prefix - first_prefix];
-                base = tb.pbase[prefix - first_prefix];
-            }
-            e = base | (depth << 16);
+        // no match: the start of a longer code (the entry says where its second-level block is),
+        // or, where a lone symbol leaves half of the code space unused, of none: symbol 0, one bit
+        uint32_t e = pack_entry(0, 1);
+        if (v >= long_start) {
+            e = 7u << 6;
+            if (v >= first_prefix) e = (tb.pdepth[v - first_prefix] << 6) | ((tb.pbase[v - first_prefix] >> 3) << 9);
         }
-        tb.lut[i] = e;
+        if (len) e = pack_entry(tb.sorted[idx], len);
+        tb.lut[i] = static_cast<uint16_t>(e);
     }
     __syncthreads();
 }
 
 // Canonical search over the lengths above kL1.  `window` holds the next 32
-// stream bits, first bit in bit 0.  Returns a one-symbol entry.
-__device__ __noinline__ uint64_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len) {
+// stream bits, first bit in bit 0.
+__device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len) {
     const uint32_t v = __brev(window);
     for (uint32_t l = kL1 + 1; l <= max_len; ++l) {
         const uint32_t d = (v >> (32 - l)) - tb.first[l];
-        if (d < tb.cnt[l]) return pack_entry(tb.sorted[tb.offs[l] + d], l, 1);
+        if (d < tb.cnt[l]) return pack_entry(tb.sorted[tb.offs[l] + d], l);
     }
-    return pack_entry(0, 1, 1);     // not a code (corrupt stream): keep moving
+    return pack_entry(0, 1);        // not a code (corrupt stream): keep moving
 }
 
-// Second-level lookup for a first-level miss e1; `window` holds the next >= 17
-// stream bits.  Returns an entry of zero count if the code is longer still.
-__device__ __forceinline__ uint64_t lookup_l2(const Tables &tb, uint64_t e1, uint32_t window) {
-    const uint32_t m = static_cast<uint32_t>(e1);
-    const uint32_t sub = __builtin_amdgcn_ubfe(window, kL1, (m >> 16) & 0xffu);
-    return tb.lut2[((m & 0xffffu) + sub) & (kL2Cap - 1)];
+// The code at the start of `window`, which the first level answered with the
+// miss entry `miss`: second level (needs kL1 + kL2MaxBits valid bits).  Zero if
+// the code is longer still.
+__device__ __forceinline__ uint32_t lookup_l2(const Tables &tb, uint32_t miss, uint32_t window) {
+    const uint32_t depth = (miss >> 6) & 7u;
+    if (depth > static_cast<uint32_t>(kL2MaxBits)) return 0;
+    return tb.lut2[(((miss >> 9) << 3) + __builtin_amdgcn_ubfe(window, kL1, depth)) & (kL2Cap - 1)];
+}
+
+// The same with the canonical search behind it; `window` holds the next 32 stream bits.
+__device__ __forceinline__ uint32_t decode_long(const Tables &tb, uint32_t miss, uint32_t window, uint32_t max_len) {
+    uint32_t e = lookup_l2(tb, miss, window);
+    if (__builtin_expect(e == 0, 0)) e = decode_canonical(tb, window, max_len);
+    return e;
 }
 
 // ---------------------------------------------------------------- scalar reader
-// Reads straight from global memory; used for segments whose size does not fit
-// the row path, for shorter last segments and (for now) by the GEMV.
+// Reads straight from global memory, one symbol per lookup; used for segments
+// whose size does not fit the row path and for shorter last segments.
 
 // 64 stream bits starting at the dword that holds absolute stream bit `pos`,
 // shifted so that bit pos is bit 0: at least 33 valid bits.  The read is
@@ -309,19 +343,16 @@ struct ScalarReader {
     uint64_t buf;
 };
 
-// One table entry (one or more symbols) from the scalar reader.
-__device__ __forceinline__ uint64_t next_entry(ScalarReader &r, const Tables &tb, uint32_t max_len) {
-    uint64_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
-    if (__builtin_expect(entry_count(e) == 0, 0)) {
-        const uint32_t w = static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off));
-        e = lookup_l2(tb, e, w);
-        if (entry_count(e) == 0) e = decode_canonical(tb, w, max_len);
+// The next symbol's entry from the scalar reader; r.buf must hold kL1 valid bits.
+__device__ __forceinline__ uint32_t next_entry(ScalarReader &r, const Tables &tb, uint32_t max_len) {
+    uint32_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
+    if (__builtin_expect(entry_len(e) == 0, 0)) {
+        e = decode_long(tb, e, static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off)), max_len);
         r.pos += entry_len(e);
         r.buf = load_bits(r.stream, r.pos, r.last_off);
     } else {
-        const uint32_t len = entry_len(e);
-        r.buf >>= len;
-        r.pos += len;
+        r.buf >>= entry_len(e);
+        r.pos += entry_len(e);
     }
     return e;
 }
@@ -346,145 +377,182 @@ __device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, 
     const float s = t.scale;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
     uint32_t pending = 0;     // low nibble waiting for its partner (packed 4-bit)
-    uint32_t i = 0;
-    for (uint32_t probe = 0; i < nsym; ++probe) {
-        if (probe % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint64_t e = next_entry(r, tb, max_len);
-        const uint32_t count = entry_count(e);
-        for (uint32_t c = 0; c < count && i < nsym; ++c, ++i) {
-            const uint64_t idx = first_sym + i;
-            const uint32_t sym = (static_cast<uint32_t>(e) >> (c * 8)) & 0xffu;
-            if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
-            if (MODE == kModeU4) {
-                if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((sym & 0xfu) << 4));
-                else pending = sym & 0xfu;
-            }
-            if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(bf16_bits(dequant(sym, z, s)));
-            if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, z, s);
+    for (uint32_t i = 0; i < nsym; ++i) {
+        if (i % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
+        const uint32_t sym = entry_sym(next_entry(r, tb, max_len));
+        const uint64_t idx = first_sym + i;
+        if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
+        if (MODE == kModeU4) {
+            if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((sym & 0xfu) << 4));
+            else pending = sym & 0xfu;
         }
+        if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(bf16_bits(dequant(sym, z, s)));
+        if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, z, s);
     }
     if (MODE == kModeU4 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
 }
 
 // ------------------------------------------------------------------ ring reader
-// Each lane keeps the next 48 bytes of its segment in a four-slot ring in LDS
-// (16-byte blocks, block j in slot j & 3, three of them resident) and the block
-// after those in registers.  Dwords 16 and 17 of the lane's ring row mirror
-// dwords 0 and 1, so a three-dword read starting in the last ring dwords needs
-// no wrap.
-// The lane tracks q = p - 3, p being its bit position relative to block 0: a
-// window read at bit q carries three stale low bits, which makes bits 3..13 the
-// first-level table's byte offset of the code that starts at p.
+// Each lane keeps up to 128 bytes of its segment in a ring in LDS (eight 16-byte
+// blocks, block j in slot j & 7) and the 64-byte line that follows the ring's
+// contents in registers: a lane asks memory for a whole line at a time.  Dwords
+// 32 and 33 of the lane's ring mirror dwords 0 and 1, so a three-dword read
+// starting in the last ring dwords needs no wrap.
+// Positions are bits relative to line 0, the 64-byte line in which the segment
+// starts.  The lane tracks q = p - 1, p being its position: a window read at bit
+// q carries one stale low bit, which makes bits 1..14 the first-level table's
+// byte offset of the code that starts at p.
+// Registers move into the ring only between blocks of output (ring_topup), half
+// a line at a time, at the point where the wave's previous stores have long been
+// written: a wait for the line then does not wait for stores.  A lane whose codes
+// are so long that the ring runs dry in between loads its ring afresh.
 struct RingReader {
     const uint8_t *stream;
-    uint32_t *ring;        // this lane's ring row
-    uint32_t start16;      // byte offset of block 0 (16-byte aligned)
+    lds_v32 ring;          // this lane's dword 0; dword d is ring[d * 64]
+    uint32_t start64;      // byte offset of line 0
     uint32_t last_blk;     // stream_bytes - 16
-    uint32_t q;            // p - 3 (wraps below zero for p < 3, which the mirror absorbs)
-    uint32_t cur;          // block that held p at the last check
-    u32x4 nx;              // block cur + 3
+    uint32_t q;            // p - 1
+    uint32_t end;          // the ring holds the stream up to here; a multiple of 256, at most 1024 past p's block
+    u32x4 nx[4];           // the line at `end` (its first half is in the ring already if end is not a multiple of 512)
 };
 
-__device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t start16, uint32_t last_blk, uint32_t blk) {
-    uint32_t off = start16 + (blk << 4);
+__device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t off, uint32_t last_blk) {
     off = off < last_blk ? off : last_blk;
     return *(global_u4_ptr)(stream + off);
 }
 
-__device__ __forceinline__ void ring_init(RingReader &r, const DevTensor &t, uint64_t off_bits, uint32_t *ring_row) {
-    r.stream = t.stream;
-    r.ring = ring_row;
-    r.last_blk = t.stream_bytes - 16u;
-    r.start16 = static_cast<uint32_t>(off_bits >> 3) & ~15u;
-    r.q = static_cast<uint32_t>(off_bits - (static_cast<uint64_t>(r.start16) << 3)) - 3u;
-    r.cur = 0;
-    const u32x4 b0 = load_block(r.stream, r.start16, r.last_blk, 0);
-    const u32x4 b1 = load_block(r.stream, r.start16, r.last_blk, 1);
-    const u32x4 b2 = load_block(r.stream, r.start16, r.last_blk, 2);
-    r.nx = load_block(r.stream, r.start16, r.last_blk, 3);
-    ring_row[0] = b0.x; ring_row[1] = b0.y; ring_row[2] = b0.z; ring_row[3] = b0.w;
-    ring_row[4] = b1.x; ring_row[5] = b1.y; ring_row[6] = b1.z; ring_row[7] = b1.w;
-    ring_row[8] = b2.x; ring_row[9] = b2.y; ring_row[10] = b2.z; ring_row[11] = b2.w;
-    ring_row[16] = b0.x; ring_row[17] = b0.y;
+// Line `line` into the registers; quarters past the end of the stream repeat its
+// last block (nothing decodes them).
+__device__ __forceinline__ void load_line(RingReader &r, uint32_t line) {
+    const uint32_t base = r.start64 + (line << 6);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.nx[i] = load_block(r.stream, base + 16u * i, r.last_blk);
 }
 
-// Retire the blocks p has left behind.  A ring read at q = p - 3 takes the
-// dword holding bit q and the two after it, so it is valid while q is less
-// than 192 bits past the end of block cur.  Between two checks kTripGroups ring
-// reads happen; a group consumes at most kGroup * kL1 bits through the first
-// level plus one second-level code of at most 17 bits, i.e. 50, so the last
-// read starts at most 3 * 50 = 150 bits past the end of block cur.  A longer
-// code (up to 32 bits) runs its own check first; reads after it stay within
-// 32 + 3 * 50 = 182.
-__device__ __forceinline__ void ring_check(RingReader &r) {
-    const uint32_t nb = (r.q + 3u) >> 7;
-    while (nb != r.cur) {
-        const uint32_t slot = (r.cur + 3u) & 3u;
-        uint32_t *dst = r.ring + (slot << 2);
-        dst[0] = r.nx.x; dst[1] = r.nx.y; dst[2] = r.nx.z; dst[3] = r.nx.w;
-        if (slot == 0) { r.ring[16] = r.nx.x; r.ring[17] = r.nx.y; }
-        r.cur += 1;
-        r.nx = load_block(r.stream, r.start16, r.last_blk, r.cur + 3u);
+// Block `blk` (16 bytes, counted from line 0) into its slot.
+__device__ __forceinline__ void ring_store(RingReader &r, uint32_t blk, const u32x4 v) {
+    const uint32_t slot = blk & 7u;
+    lds_v32 dst = r.ring + slot * 256u;
+    dst[0] = v.x; dst[64] = v.y; dst[128] = v.z; dst[192] = v.w;
+    if (slot == 0) { r.ring[32 * 64] = v.x; r.ring[33 * 64] = v.y; }
+}
+
+// Fill the ring with the two lines from absolute stream bit `pos` on and ask for the third.
+__device__ __forceinline__ void ring_load(RingReader &r, uint64_t pos) {
+    r.start64 = static_cast<uint32_t>(pos >> 3) & ~63u;
+    r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - 1u;
+    r.end = kRingBits;
+#pragma unroll
+    for (uint32_t b = 0; b < 8; ++b) ring_store(r, b, load_block(r.stream, r.start64 + 16u * b, r.last_blk));
+    load_line(r, 2);
+}
+
+// A ring read at q takes the dword that holds bit q and the two after it: it
+// stays inside the ring's contents while q + 64 < end.
+__device__ __forceinline__ bool ring_short(const RingReader &r, uint32_t ahead) { return r.q + ahead + 64u >= r.end; }
+
+__device__ __forceinline__ void ring_reload(RingReader &r) {
+    ring_load(r, (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u);
+}
+
+// Move what the registers hold into the blocks p has left behind: half a line
+// when two slots are free, and the other half, followed by the request for the
+// next line, when two more are.
+__device__ __forceinline__ void ring_topup(RingReader &r) {
+    const uint32_t pblk = ((r.q + 1u) >> 7) << 7;                    // start of the block that holds p
+    if ((r.end & 256u) == 0 && r.end - pblk <= kRingBits - 256u) {
+        ring_store(r, r.end >> 7, r.nx[0]);
+        ring_store(r, (r.end >> 7) + 1u, r.nx[1]);
+        r.end += 256u;
+    }
+    if ((r.end & 256u) != 0 && r.end - pblk <= kRingBits - 256u) {
+        ring_store(r, r.end >> 7, r.nx[2]);
+        ring_store(r, (r.end >> 7) + 1u, r.nx[3]);
+        r.end += 256u;
+        load_line(r, r.end >> 9);
     }
 }
 
-// The stream from bit q = p - 3 on: 61 valid bits above the three stale ones.
+// The stream from bit q = p - 1 on: 63 valid bits above the stale one.
 __device__ __forceinline__ uint64_t ring_read(const RingReader &r) {
-    const uint32_t d = (r.q >> 5) & 15u;
-    const uint32_t w0 = r.ring[d], w1 = r.ring[d + 1], w2 = r.ring[d + 2];
+    lds_v32 src = r.ring + ((r.q >> 5) & 31u) * 64u;
+    const uint32_t w0 = src[0], w1 = src[64], w2 = src[128];
     const uint32_t lo = __builtin_amdgcn_alignbit(w1, w0, r.q);     // uses q & 31
     const uint32_t hi = __builtin_amdgcn_alignbit(w2, w1, r.q);
     return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
-__device__ __forceinline__ uint64_t lut_at(const Tables &tb, uint32_t byte_off) {
-    return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
+__device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) {
+    return *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
 }
 
-// One group: a fresh window and kGroup first-level probes without a branch.
-// Each probe writes its four symbol bytes at `out` of the lane's tile row and
-// advances by what the entry says; a lane whose row is full, or whose window
-// starts with a code longer than kL1 bits, advances by nothing (and the probes
-// after it see the same bits).  The long code is then resolved once, behind the
-// probes, through the second level or the canonical search.
-template <int SPB>
-__device__ __forceinline__ void ring_group(RingReader &r, uint8_t *row, uint32_t &out, const Tables &tb,
-                                           uint32_t max_len) {
-    uint64_t w = ring_read(r);
-    uint64_t e = 0;
-#pragma unroll
-    for (int i = 0; i < kGroup; ++i) {
-        e = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 3));
-        const uint32_t syms = static_cast<uint32_t>(e);
-        lds_v8 o = (lds_v8)(row + out);
-        o[0] = static_cast<uint8_t>(syms); o[1] = static_cast<uint8_t>(syms >> 8);
-        o[2] = static_cast<uint8_t>(syms >> 16); o[3] = static_cast<uint8_t>(syms >> 24);
-        const uint32_t ctl = out < static_cast<uint32_t>(SPB) ? static_cast<uint32_t>(e >> 48) : 0u;   // len | count << 8
-        w >>= (ctl & 63u);
-        r.q += ctl & 0xffu;
-        out += ctl >> 8;
+// The rest of a group for the lanes that met a code longer than kL1 bits.  e0..e3
+// are the group's entries (from the long code on they all are its miss entry),
+// w is the window as it stopped in front of the long code, `packed` the symbols in
+// front of it (and junk behind).  The long code comes out of the second level
+// with the bits still in the window (at least 63 - 3 * 14 of them; it needs 20)
+// or, failing that, out of the canonical search; the symbols behind it are
+// looked up one by one, each with a window of its own.
+__device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &tb, uint32_t max_len, uint32_t e0,
+                                                  uint32_t e1, uint32_t e2, uint32_t e3, uint64_t w, uint32_t packed) {
+    const uint32_t l0 = entry_len(e0), l1 = entry_len(e1), l2 = entry_len(e2);
+    const uint32_t at = l0 == 0 ? 0u : l1 == 0 ? 1u : l2 == 0 ? 2u : 3u;     // place of the long code
+    r.q += l0 + l1 + l2;                                                   // its entries add nothing
+    uint32_t e = lookup_l2(tb, e3, static_cast<uint32_t>(w >> 1));
+    if (__builtin_expect(e == 0, 0)) {
+        if (ring_short(r, 0)) ring_reload(r);
+        e = decode_canonical(tb, static_cast<uint32_t>(ring_read(r) >> 1), max_len);
     }
-    if (__builtin_expect(out < static_cast<uint32_t>(SPB) && entry_count(e) == 0, 0)) {
-        // w still starts with the long code and holds at least 61 - 2 * 11 valid bits
-        uint64_t e2 = lookup_l2(tb, e, static_cast<uint32_t>(w >> 3));
-        if (__builtin_expect(entry_count(e2) == 0, 0)) {
-            ring_check(r);
-            w = ring_read(r);
-            e2 = decode_canonical(tb, static_cast<uint32_t>(w >> 3), max_len);
+    packed = __builtin_amdgcn_ubfe(packed, 0, 8u * at) | (entry_sym(e) << (8u * at));
+    r.q += entry_len(e);
+#pragma unroll 1
+    for (uint32_t i = 1; i < static_cast<uint32_t>(kGroup); ++i) {
+        if (i > at) {
+            if (ring_short(r, 0)) ring_reload(r);
+            const uint64_t wi = ring_read(r);
+            e = lut_at(tb, static_cast<uint32_t>(wi) & (kL1Mask << 1));
+            if (__builtin_expect(entry_len(e) == 0, 0)) e = decode_long(tb, e, static_cast<uint32_t>(wi >> 1), max_len);
+            packed |= entry_sym(e) << (8u * i);
+            r.q += entry_len(e);
         }
-        *(lds_v8)(row + out) = static_cast<uint8_t>(e2);
-        r.q += entry_len(e2);
-        out += 1;
     }
+    // the groups that follow in this trip count on the usual margin
+    if (ring_short(r, kTripBits - 64)) ring_reload(r);
+    return packed;
+}
+
+// One group: a fresh window and kGroup table lookups without a branch; every
+// entry is the shift amount that moves the window to the next code.  A lane that
+// meets a code longer than kL1 bits stops moving (its later lookups see the same
+// bits and give the same entry of length zero), and the rest of the group is
+// decoded for it with more care.  Returns the group's four symbols, first one lowest.
+__device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, uint32_t max_len) {
+    uint64_t w = ring_read(r);
+    const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    w >>= (e0 & 63u);
+    const uint32_t e1 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    w >>= (e1 & 63u);
+    const uint32_t e2 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    w >>= (e2 & 63u);
+    const uint32_t e3 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    // byte 1 of each entry, in order
+    uint32_t packed = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u) | __builtin_amdgcn_perm(e3, e2, 0x05010c0cu);
+    if (__builtin_expect(entry_len(e3) == 0, 0)) {
+        packed = careful_group(r, tb, max_len, e0, e1, e2, e3, w, packed);
+    } else {
+        r.q += (e0 + e1 + e2 + e3) & 0xffu;                           // lengths add up in the low byte (<= 56)
+    }
+    return packed;
 }
 
 template <int MODE>
 __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &tb, uint32_t k);
 
-// Decode the workgroup's segments block by block into the wave's LDS tile (one
-// row of symbol bytes per lane), then consume the tile row-wise: write it out in
-// the output type, so that every store instruction covers whole rows, or (GEMV)
-// multiply it into the activation vector.
+// Decode the workgroup's segments SPB symbols per lane at a time into the wave's
+// LDS tile (one row of symbol bytes per lane; all lanes move in step, four
+// symbols per group), then consume the tile row-wise: write it out in the output
+// type, so that every store instruction covers whole rows, or (GEMV) multiply it
+// into the activation vector.
 template <int MODE>
 __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::spb> *wms,
                                             uint32_t first_chunk) {
@@ -492,10 +560,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     constexpr int SPB = Cfg<MODE>::spb;
     constexpr int OUT_ROW = Cfg<MODE>::out_row;
     constexpr int TS = WaveMem<SPB>::tile_stride;
-    constexpr uint32_t LPR = 8;                           // lanes that consume one row
+    constexpr uint32_t PIECE = Cfg<MODE>::piece;          // symbols one lane converts per pass
+    constexpr uint32_t LPR = SPB / PIECE;                 // lanes that consume one row
     constexpr uint32_t RPI = 64 / LPR;                    // rows per pass
-    constexpr uint32_t PIECE = SPB / LPR;                 // symbols one lane converts: 8 or 16
     constexpr uint32_t EBITS = GEMV ? 0 : OutTraits<GEMV ? kModeU8 : MODE>::ebits;
+    constexpr int TRIPS = SPB / (kGroup * kTripGroups);
+    static_assert(SPB % (kGroup * kTripGroups) == 0, "a row is a whole number of trips");
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     WaveMem<SPB> &wm = wms[wave];
@@ -514,12 +584,9 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     RingReader r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
-    r.q = 0u - 3u;
-    r.start16 = 0;
-    r.cur = 0;
-    r.nx = u32x4{0u, 0u, 0u, 0u};
-    r.ring = wm.ring + lane * kRingStride;
-    if (fast) ring_init(r, t, t.offsets[k], wm.ring + lane * kRingStride);
+    r.ring = (lds_v32)(wm.ring + lane);
+    // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
+    ring_load(r, fast ? t.offsets[k] : 0);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
     uint8_t *out8 = static_cast<uint8_t *>(t.out);
     const uint32_t max_len = t.max_len;
@@ -527,9 +594,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const float scale = t.scale;
     const uint32_t n_chunks = t.n_chunks;
     const uint64_t n_total = t.n;
-    uint8_t *const my_row = reinterpret_cast<uint8_t *>(wm.tile + lane * TS);
-    // a lane that does not decode keeps its position at the row end: its probes are no-ops
-    uint32_t out = fast ? 0u : static_cast<uint32_t>(SPB);
+    lds_v32 my_row = (lds_v32)(wm.tile + lane * TS);
 
     // GEMV: the lane sums, for the eight rows it serves, its eight-symbol piece of every block.
     // A segment is at most as long as a matrix row here, so it touches one row (acc_a) or the
@@ -549,13 +614,13 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     }
 
     for (uint32_t bs = 0; bs < blocks_total; ++bs) {
-        // every lane fills its row; the last probe may run up to three symbols over, which the next block inherits
-        while (__builtin_amdgcn_ballot_w64(out < static_cast<uint32_t>(SPB))) {
-            ring_check(r);
+#pragma unroll 1
+        for (int trip = 0; trip < TRIPS; ++trip) {
+            if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
 #pragma unroll
-            for (int g = 0; g < kTripGroups; ++g)
-                if (out < static_cast<uint32_t>(SPB)) ring_group<SPB>(r, my_row, out, tb, max_len);
+            for (int g = 0; g < kTripGroups; ++g) my_row[trip * kTripGroups + g] = ring_group(r, tb, max_len);
         }
+        ring_topup(r);
         wave_sync_lds();
 #pragma unroll
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
@@ -626,12 +691,6 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             }
         }
         wave_sync_lds();
-        // what ran over the row end opens the next row
-        if (fast) {
-            const uint32_t spill = *reinterpret_cast<const uint32_t *>(my_row + SPB);
-            *reinterpret_cast<uint32_t *>(my_row) = spill;
-            out -= static_cast<uint32_t>(SPB);
-        }
     }
     if constexpr (GEMV) {
         // the eight lanes of a row add up their pieces; the first of them publishes the result
@@ -639,7 +698,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
             float a = acc_a[it], b = acc_b[it];
 #pragma unroll
-            for (int m = 1; m < 8; m <<= 1) {
+            for (uint32_t m = 1; m < LPR; m <<= 1) {
                 a += __shfl_xor(a, m, 64);
                 b += __shfl_xor(b, m, 64);
             }
@@ -687,28 +746,23 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     bool first_fragment = true;
     float acc = 0.0f;
     float head = 0.0f, tail = 0.0f;
-    uint32_t i = 0;
-    for (uint32_t probe = 0; i < nsym; ++probe) {
-        if (probe % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint64_t e = next_entry(r, tb, max_len);
-        const uint32_t count = entry_count(e);
-        for (uint32_t c = 0; c < count && i < nsym; ++c, ++i) {
-            const uint32_t sym = (static_cast<uint32_t>(e) >> (c * 8)) & 0xffu;
-            const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
-            acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - z), xv, acc);
-            if (++col == cols) {
-                if (first_fragment && start_col != 0) {
-                    head = acc;                              // row began in an earlier segment
-                } else {
-                    const float y = acc * t.scale;
-                    if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[row] = y;
-                    else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
-                }
-                first_fragment = false;
-                acc = 0.0f;
-                col = 0;
-                ++row;
+    for (uint32_t i = 0; i < nsym; ++i) {
+        if (i % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
+        const uint32_t sym = entry_sym(next_entry(r, tb, max_len));
+        const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
+        acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - z), xv, acc);
+        if (++col == cols) {
+            if (first_fragment && start_col != 0) {
+                head = acc;                              // row began in an earlier segment
+            } else {
+                const float y = acc * t.scale;
+                if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[row] = y;
+                else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
             }
+            first_fragment = false;
+            acc = 0.0f;
+            col = 0;
+            ++row;
         }
     }
     if (col != 0) {                                          // row continues in the next segment
@@ -723,12 +777,11 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 
 // The GEMV kernels need the tables and the scratch table only.
 template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::spb> wm[Cfg<MODE>::waves]; };
-static_assert(sizeof(WaveMem<64>) >= sizeof(uint32_t) << kL1, "scratch table must fit into one wave's buffers");
 
 template <int MODE>
 __device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, SmemFor<MODE> &sm) {
     constexpr int WG = 64 * Cfg<MODE>::waves;
-    // the single-symbol scratch table lives in the first wave's buffers, which are not in use yet
+    // the per-wave symbol counts live in the first wave's buffers, which are not in use yet
     build_tables<WG>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
     if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
         // row path: a segment tiles into blocks, pieces of eight never straddle a matrix row,
