@@ -8,16 +8,18 @@
 // segments of one tensor with one shared set of lookup tables in LDS.
 //
 // Data flow of the decode / dequant kernels, per lane:
-//   HBM --16-byte blocks--> four-slot ring in LDS --three dwords--> 61-bit window
-//   window --11 bits--> first-level table (LDS, 64-bit entries holding up to
-//   four decoded symbols) --byte writes--> the lane's row of the wave's LDS tile
+//   HBM --64-byte lines--> registers --between output blocks--> 128-byte ring in LDS
+//   ring --three dwords--> 63-bit window --14 bits--> first-level table (LDS,
+//   16-bit entries: length | symbol) --shift by the entry--> next code ...
+//   four symbols --one aligned dword--> the lane's row of the wave's LDS tile
 //   tile rows --dequantise / pack, row-wise--> HBM,
-// so that every global store instruction of a wave covers whole 128-byte lines.
-// Every LDS access is naturally aligned: gfx950 executes unaligned ones, but
-// they stall the LDS pipeline for most of the kernel's time.  The symbol loop
-// has no branch per table probe; a probe that meets a code too long for the
-// first-level table simply makes no progress, and the lane resolves that code
-// once per group of probes.
+// so that every global store instruction of a wave covers whole rows.  All 64
+// lanes of a wave decode in step, four symbols per window: no lane waits for
+// another, nothing is written to LDS at an odd address, and a flush happens
+// after a fixed number of groups.  The symbol loop has no branch per lookup; a
+// lane that meets a code too long for the first-level table stops moving for the
+// rest of its group, and the wave then finishes that group for it with the
+// second-level table or a canonical search.
 #include "entro.h"
 
 #include <hip/hip_runtime.h>
@@ -79,17 +81,12 @@ enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 
 // converts per flush pass (a 16-byte store for all but fp32) and bytes that a
 // row becomes in memory.  The host glue sizes its launches with the same numbers.
 template <int MODE> struct Cfg;
-template <> struct Cfg<kModeU8> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 128; };
+template <> struct Cfg<kModeU8> { static constexpr int spb = 64, waves = 9, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 256; };
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 128; };
 template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 4, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 4, piece = 8, out_row = 0; };
-constexpr int kWgDecode = 64 * Cfg<kModeU8>::waves;
-constexpr int kWgDequant = 64 * Cfg<kModeBF16>::waves;
-constexpr int kWgGemv = 64 * Cfg<kModeGemvF32>::waves;
-static_assert(Cfg<kModeU8>::waves == Cfg<kModeU4>::waves && Cfg<kModeF32>::waves == Cfg<kModeBF16>::waves,
-              "one workgroup size per operation");
 
 // Lookup tables of one workgroup (LDS).
 // Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
@@ -451,8 +448,15 @@ __device__ __forceinline__ void ring_load(RingReader &r, uint64_t pos) {
 // stays inside the ring's contents while q + 64 < end.
 __device__ __forceinline__ bool ring_short(const RingReader &r, uint32_t ahead) { return r.q + ahead + 64u >= r.end; }
 
+// Rare: written as a loop to stay small where it is inlined.
 __device__ __forceinline__ void ring_reload(RingReader &r) {
-    ring_load(r, (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u);
+    const uint64_t pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
+    r.start64 = static_cast<uint32_t>(pos >> 3) & ~63u;
+    r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - 1u;
+    r.end = kRingBits;
+#pragma unroll 1
+    for (uint32_t b = 0; b < 8; ++b) ring_store(r, b, load_block(r.stream, r.start64 + 16u * b, r.last_blk));
+    load_line(r, 2);
 }
 
 // Move what the registers hold into the blocks p has left behind: half a line
@@ -524,8 +528,9 @@ __device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &t
 // One group: a fresh window and kGroup table lookups without a branch; every
 // entry is the shift amount that moves the window to the next code.  A lane that
 // meets a code longer than kL1 bits stops moving (its later lookups see the same
-// bits and give the same entry of length zero), and the rest of the group is
-// decoded for it with more care.  Returns the group's four symbols, first one lowest.
+// bits and give the same entry of length zero); if the wave has such a lane, the
+// rest of its group is decoded with more care.  Returns the group's four symbols,
+// first one lowest.
 __device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, uint32_t max_len) {
     uint64_t w = ring_read(r);
     const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
@@ -537,11 +542,15 @@ __device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, 
     const uint32_t e3 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
     // byte 1 of each entry, in order
     uint32_t packed = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u) | __builtin_amdgcn_perm(e3, e2, 0x05010c0cu);
-    if (__builtin_expect(entry_len(e3) == 0, 0)) {
-        packed = careful_group(r, tb, max_len, e0, e1, e2, e3, w, packed);
-    } else {
-        r.q += (e0 + e1 + e2 + e3) & 0xffu;                           // lengths add up in the low byte (<= 56)
+    uint32_t q_next = r.q + ((e0 + e1 + e2 + e3) & 0xffu);            // lengths add up in the low byte (<= 56)
+    const bool miss = entry_len(e3) == 0;
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(miss) != 0, 0)) {
+        if (miss) {
+            packed = careful_group(r, tb, max_len, e0, e1, e2, e3, w, packed);
+            q_next = r.q;
+        }
     }
+    r.q = q_next;
     return packed;
 }
 
@@ -588,12 +597,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
     ring_load(r, fast ? t.offsets[k] : 0);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
-    uint8_t *out8 = static_cast<uint8_t *>(t.out);
+    const uint32_t n_full = static_cast<uint32_t>(t.n / C);          // segments of full length
+    // where the first row this lane serves in a flush pass begins; the passes are RPI rows apart
+    uint8_t *const row0 = static_cast<uint8_t *>(t.out) + (wave_first + lane / LPR) * bytes_per_chunk;
     const uint32_t max_len = t.max_len;
     const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
     const float scale = t.scale;
-    const uint32_t n_chunks = t.n_chunks;
-    const uint64_t n_total = t.n;
     lds_v32 my_row = (lds_v32)(wm.tile + lane * TS);
 
     // GEMV: the lane sums, for the eight rows it serves, its eight-symbol piece of every block.
@@ -628,9 +637,8 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             const uint32_t piece = lane % LPR;
             const uint32_t *src = wm.tile + rr * TS + piece * (PIECE / 4);
             const uint32_t kk = wave_first + rr;
-            bool full = false;
-            if (kk < n_chunks) full = n_total - static_cast<uint64_t>(kk) * C >= C;
-            uint8_t *dst = out8 + kk * bytes_per_chunk + static_cast<uint64_t>(bs) * OUT_ROW;
+            const bool full = kk < n_full;
+            uint8_t *dst = row0 + static_cast<uint64_t>(it) * (RPI * bytes_per_chunk) + static_cast<uint64_t>(bs) * OUT_ROW;
             if constexpr (GEMV) {
                 const uint32_t d0 = src[0], d1 = src[1];
                 if (full) {
@@ -703,8 +711,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                 b += __shfl_xor(b, m, 64);
             }
             const uint32_t kk = wave_first + it * RPI + lane / LPR;
-            bool full = false;
-            if (kk < n_chunks) full = n_total - static_cast<uint64_t>(kk) * C >= C;
+            const bool full = kk < n_full;
             if (full && (lane % LPR) == 0) {
                 if (t.need_fix) {                                   // row fragments: summed by the second stage
                     t.partials[2 * static_cast<uint64_t>(kk)] = a;
@@ -779,10 +786,13 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::spb> wm[Cfg<MODE>::waves]; };
 
 template <int MODE>
-__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, SmemFor<MODE> &sm) {
+__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, SmemFor<MODE> &sm, bool build) {
     constexpr int WG = 64 * Cfg<MODE>::waves;
-    // the per-wave symbol counts live in the first wave's buffers, which are not in use yet
-    build_tables<WG>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+    if (build) {
+        __syncthreads();                                     // nobody reads the previous tensor's tables any more
+        // the per-wave symbol counts live in the first wave's buffers, which are not in use now
+        build_tables<WG>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+    }
     if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
         // row path: a segment tiles into blocks, pieces of eight never straddle a matrix row,
         // and a segment touches at most two rows
@@ -808,15 +818,24 @@ __device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chun
 template <int MODE>
 __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t) {
     __shared__ SmemFor<MODE> sm;
-    run_item<MODE>(t, blockIdx.x * (64 * Cfg<MODE>::waves), sm);
+    run_item<MODE>(t, blockIdx.x * (64 * Cfg<MODE>::waves), sm, true);
 }
 
+// Workgroup b takes the work items [b * n / G, (b + 1) * n / G) of a launch of G
+// workgroups, about one workgroup per compute unit: neighbouring items mostly
+// belong to one tensor, whose tables the workgroup then builds once.
 template <int MODE>
 __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor *__restrict__ tensors,
-                                                                 const WorkItem *__restrict__ items) {
+                                                                 const WorkItem *__restrict__ items, uint32_t n_items) {
     __shared__ SmemFor<MODE> sm;
-    const WorkItem it = items[blockIdx.x];
-    run_item<MODE>(tensors[it.tensor], it.first, sm);
+    const uint32_t lo = static_cast<uint32_t>(static_cast<uint64_t>(blockIdx.x) * n_items / gridDim.x);
+    const uint32_t hi = static_cast<uint32_t>(static_cast<uint64_t>(blockIdx.x + 1) * n_items / gridDim.x);
+    uint32_t built = 0xffffffffu;
+    for (uint32_t i = lo; i < hi; ++i) {
+        const WorkItem it = items[i];
+        run_item<MODE>(tensors[it.tensor], it.first, sm, it.tensor != built);
+        built = it.tensor;
+    }
 }
 
 // Second stage of the GEMV: rows that straddle segments are summed in segment order.
@@ -926,21 +945,6 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     return ENTRO_OK;
 }
 
-// Lanes per workgroup of the main kernel of an operation.
-unsigned wg_of(entro_op op) {
-    return op == ENTRO_OP_DECODE ? kWgDecode : op == ENTRO_OP_DEQUANT ? kWgDequant : kWgGemv;
-}
-
-int mode_of(entro_op op, entro_dtype d) {
-    if (op == ENTRO_OP_GEMV) return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
-    switch (d) {
-        case ENTRO_U8: return kModeU8;
-        case ENTRO_U4_PACKED: return kModeU4;
-        case ENTRO_F32: return kModeF32;
-        default: return kModeBF16;
-    }
-}
-
 template <class F>
 void dispatch_mode(int mode, F f) {
     switch (mode) {
@@ -953,6 +957,43 @@ void dispatch_mode(int mode, F f) {
     }
 }
 
+// Lanes (= segments) per workgroup of the main kernel of a mode.
+unsigned wg_of(int mode) {
+    unsigned wg = 64;
+    dispatch_mode(mode, [&](auto m) { wg = 64u * Cfg<decltype(m)::value>::waves; });
+    return wg;
+}
+
+// The smallest of them over the modes of an operation: sizes the work list before the output type is known.
+unsigned wg_min(entro_op op) {
+    if (op == ENTRO_OP_DECODE) return std::min(wg_of(kModeU8), wg_of(kModeU4));
+    if (op == ENTRO_OP_DEQUANT) return std::min(wg_of(kModeF32), wg_of(kModeBF16));
+    return std::min(wg_of(kModeGemvF32), wg_of(kModeGemvBF16));
+}
+
+int mode_of(entro_op op, entro_dtype d) {
+    if (op == ENTRO_OP_GEMV) return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
+    switch (d) {
+        case ENTRO_U8: return kModeU8;
+        case ENTRO_U4_PACKED: return kModeU4;
+        case ENTRO_F32: return kModeF32;
+        default: return kModeBF16;
+    }
+}
+
+
+// Workgroups of the batched kernel of `mode` that the current device holds at once
+// (its LDS footprint decides); 0 if the device cannot be asked.
+unsigned resident_workgroups(int mode) {
+    int dev = 0, cus = 0;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return 0;
+    if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute")) return 0;
+    size_t smem = 1;
+    dispatch_mode(mode, [&](auto m) { smem = sizeof(SmemFor<decltype(m)::value>); });
+    const unsigned per_cu = static_cast<unsigned>((160u * 1024u) / smem);
+    return static_cast<unsigned>(cus) * (per_cu ? per_cu : 1u);
+}
+
 entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, float *partials,
                            void *hip_stream) {
     DevTensor dt;
@@ -960,9 +1001,9 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     if (st != ENTRO_OK) return st;
     dt.partials = partials;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const unsigned wg = wg_of(op);
-    const unsigned grid = (dt.n_chunks + wg - 1) / wg;
     const int mode = mode_of(op, d);
+    const unsigned wg = wg_of(mode);
+    const unsigned grid = (dt.n_chunks + wg - 1) / wg;
     dispatch_mode(mode, [&](auto m) { hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(wg), 0, s, dt); });
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
@@ -987,7 +1028,7 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
     for (uint32_t i = 0; i < count; ++i) {
         if (ts[i].chunk_symbols == 0 || ts[i].n == 0) return false;
         const uint64_t nc = entro_num_chunks(ts[i].n, ts[i].chunk_symbols);
-        items += (nc + wg_of(op) - 1) / wg_of(op);
+        items += (nc + wg_min(op) - 1) / wg_min(op);
         if (op == ENTRO_OP_GEMV && ts[i].cols && (ts[i].chunk_symbols % ts[i].cols) != 0) {
             fix += (static_cast<uint64_t>(ts[i].rows) + kFixWG - 1) / kFixWG;
             partial_floats += 2 * nc;
@@ -1058,11 +1099,12 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     WorkItem *items = reinterpret_cast<WorkItem *>(host.data() + L.off_items);
     WorkItem *fix = reinterpret_cast<WorkItem *>(host.data() + L.off_fix);
     uint64_t n_items = 0, n_fix = 0, partial_floats = 0;
+    const unsigned wg = wg_of(mode_of(op, out_type));
     float *partials_base = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + L.off_partials);
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, &dts[i]);
         if (st != ENTRO_OK) return st;
-        for (uint32_t c = 0; c < dts[i].n_chunks; c += wg_of(op)) items[n_items++] = WorkItem{i, c};
+        for (uint32_t c = 0; c < dts[i].n_chunks; c += wg) items[n_items++] = WorkItem{i, c};
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
@@ -1079,7 +1121,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     plan->op = op;
     plan->out = out_type;
     plan->count = count;
-    plan->n_items = L.n_items;
+    plan->n_items = static_cast<uint32_t>(n_items);      // at most L.n_items, which the smallest workgroup size gave
     plan->n_fix = L.n_fix;
     plan->flags = 0;
     plan->off_tensors = L.off_tensors;
@@ -1098,8 +1140,12 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const WorkItem *items = reinterpret_cast<const WorkItem *>(ws + plan->off_items);
     const WorkItem *fix = reinterpret_cast<const WorkItem *>(ws + plan->off_fix);
     const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out));
+    const unsigned slots = resident_workgroups(mode);
+    if (slots == 0) return ENTRO_ERR_DEVICE;
+    const unsigned grid = plan->n_items < slots ? plan->n_items : slots;
     dispatch_mode(mode, [&](auto m) {
-        hipLaunchKernelGGL(k_batch<decltype(m)::value>, dim3(plan->n_items), dim3(wg_of(static_cast<entro_op>(plan->op))), 0, s, dts, items);
+        hipLaunchKernelGGL(k_batch<decltype(m)::value>, dim3(grid), dim3(wg_of(mode)), 0, s, dts, items,
+                           plan->n_items);
     });
     if (!hip_ok(hipGetLastError(), "launch batched decode kernel")) return ENTRO_ERR_DEVICE;
     if (plan->n_fix) {
