@@ -212,28 +212,49 @@ def main():
                 E.entro_plan_run(p)
 
         wg, kg = timed(token_step, args.steps, args.warmup)
-        # check a few rows of the last layer's `down` and first layer's `q` against the oracle
-        for (x, y, idx, xb) in [k for k in keep if isinstance(k, tuple)][:1] + [k for k in keep if isinstance(k, tuple)][-1:]:
-            e = encs[idx]
-            yh = y.cpu().numpy().astype(np.float64)
-            rows = [0, e.rows // 2, e.rows - 1]
-            sub = np.empty((len(rows), e.cols), np.uint8)
-            for j, r in enumerate(rows):
-                k0, k1 = (r * e.cols) // e.chunk_symbols, ((r + 1) * e.cols - 1) // e.chunk_symbols
-                q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(),
-                                         k0, k1 - k0 + 1)
-                sub[j] = q[r * e.cols:(r + 1) * e.cols]
-            y_ref, _ = oracle.gemv(sub, len(rows), e.cols, e.qp.scale, e.qp.zero_point, xb)
-            rms = np.sqrt(np.mean(yh ** 2))
-            if np.max(np.abs(yh[rows] - y_ref) / np.maximum(np.abs(y_ref), rms)) > 1e-3:
-                print(f"bench.py: GEMV output differs from the oracle in tensor {e.name}", file=sys.stderr)
-                sys.exit(1)
+
+        def check_gemv(what):
+            """A few rows of the first layer's `q` and the last layer's `down` against the oracle."""
+            for (x, y, idx, xb) in [k for k in keep if isinstance(k, tuple)][:1] + [k for k in keep if isinstance(k, tuple)][-1:]:
+                e = encs[idx]
+                yh = y.cpu().numpy().astype(np.float64)
+                rows = [0, e.rows // 2, e.rows - 1]
+                sub = np.empty((len(rows), e.cols), np.uint8)
+                for j, r in enumerate(rows):
+                    k0, k1 = (r * e.cols) // e.chunk_symbols, ((r + 1) * e.cols - 1) // e.chunk_symbols
+                    q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(),
+                                             k0, k1 - k0 + 1)
+                    sub[j] = q[r * e.cols:(r + 1) * e.cols]
+                y_ref, _ = oracle.gemv(sub, len(rows), e.cols, e.qp.scale, e.qp.zero_point, xb)
+                rms = np.sqrt(np.mean(yh ** 2))
+                if np.max(np.abs(yh[rows] - y_ref) / np.maximum(np.abs(y_ref), rms)) > 1e-3:
+                    print(f"bench.py: GEMV output ({what}) differs from the oracle in tensor {e.name}", file=sys.stderr)
+                    sys.exit(1)
+
+        check_gemv("dependent launches")
         result["gemv"] = {"us_per_layer": round(wg * 1e3 / layers, 2), "kernel_us_per_layer": round(kg * 1e3 / layers, 2),
                           "launches_per_layer": len(groups),
                           "compressed_GBps": round(stream_bytes / (wg * 1e-3) / 1e9, 2),
                           "effective_uint8_GBps": round(n_sym / (wg * 1e-3) / 1e9, 2),
                           "hbm_frac": round((stream_bytes + offset_bytes) / (kg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         log(f"gemv: {result['gemv']['us_per_layer']} us/layer")
+
+        # the same 224 products as one launch (no dependencies between them): what the kernel sustains
+        # when the whole chip has work, against the latency-bound step above
+        log("timing entro_decode_gemv, all layers in one launch")
+        pairs = [k for k in keep if isinstance(k, tuple)]
+        tl_all = [dts[idx].ctensor(y, x) for (x, y, idx, xb) in pairs]
+        ws_all = torch.zeros(E.entro_workspace_bytes(tl_all, E.ENTRO_OP_GEMV), dtype=torch.uint8, device=dev)
+        plan_all = E.entro_plan_init(tl_all, E.ENTRO_OP_GEMV, E.ENTRO_F32, ws_all)
+        for (x, y, idx, xb) in pairs:
+            y.zero_()
+        wa, ka = timed(lambda: E.entro_plan_run(plan_all), args.steps, args.warmup)
+        check_gemv("one launch")
+        result["gemv_one_launch"] = {"us_per_layer": round(wa * 1e3 / layers, 2), "kernel_us_per_layer": round(ka * 1e3 / layers, 2),
+                                     "compressed_GBps": round(stream_bytes / (wa * 1e-3) / 1e9, 2),
+                                     "effective_uint8_GBps": round(n_sym / (wa * 1e-3) / 1e9, 2),
+                                     "hbm_frac": round((stream_bytes + offset_bytes) / (ka * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        log(f"gemv, one launch: {result['gemv_one_launch']['us_per_layer']} us/layer")
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

@@ -85,8 +85,8 @@ template <> struct Cfg<kModeU8> { static constexpr int spb = 64, waves = 9, piec
 template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 256; };
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 128; };
-template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 4, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 4, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 8, piece = 8, out_row = 0; };
 
 // Lookup tables of one workgroup (LDS).
 // Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
@@ -985,9 +985,16 @@ int mode_of(entro_op op, entro_dtype d) {
 // Workgroups of the batched kernel of `mode` that the current device holds at once
 // (its LDS footprint decides); 0 if the device cannot be asked.
 unsigned resident_workgroups(int mode) {
-    int dev = 0, cus = 0;
+    thread_local int cached_dev = -1, cached_cus = 0;
+    int dev = 0;
     if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return 0;
-    if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute")) return 0;
+    if (dev != cached_dev) {
+        int n = 0;
+        if (!hip_ok(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute")) return 0;
+        cached_dev = dev;
+        cached_cus = n;
+    }
+    const int cus = cached_cus;
     size_t smem = 1;
     dispatch_mode(mode, [&](auto m) { smem = sizeof(SmemFor<decltype(m)::value>); });
     const unsigned per_cu = static_cast<unsigned>((160u * 1024u) / smem);
