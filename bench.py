@@ -256,6 +256,46 @@ def main():
                                      "hbm_frac": round((stream_bytes + offset_bytes) / (ka * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         log(f"gemv, one launch: {result['gemv_one_launch']['us_per_layer']} us/layer")
 
+        # the dependent step again on layers encoded with segments of 1024 symbols: four times the lanes
+        # per launch, a quarter of the serial work per lane (segment size is a per-tensor encode choice)
+        small_layers = min(4, layers)
+        log(f"timing the dependent GEMV step with 1024-symbol segments ({small_layers} layers)")
+        encs_s = prepare_config(4, layers=small_layers, chunk_symbols=1024)
+        dts_s = [E.to_device(e, dev) for e in encs_s]
+        plans_s, keep_s = [], []
+        for layer in range(small_layers):
+            base = 7 * layer
+            for a, b in groups:
+                tl = []
+                for j in range(a, b):
+                    e = encs_s[base + j]
+                    x, y = pairs[base + j][0], torch.zeros(e.rows, dtype=torch.float32, device=dev)
+                    keep_s.append(y)
+                    tl.append(dts_s[base + j].ctensor(y, x))
+                wsg = torch.zeros(max(256, E.entro_workspace_bytes(tl, E.ENTRO_OP_GEMV)), dtype=torch.uint8, device=dev)
+                keep_s.append(wsg)
+                plans_s.append(E.entro_plan_init(tl, E.ENTRO_OP_GEMV, E.ENTRO_F32, wsg))
+
+        def token_step_small():
+            for p in plans_s:
+                E.entro_plan_run(p)
+
+        wsm, ksm = timed(token_step_small, args.steps, args.warmup)
+        # same weights, same x: the products must agree with the 4096-symbol run (rounding order apart)
+        y_small = torch.cat([k for k in keep_s if k.dtype == torch.float32])
+        y_big = torch.cat([pairs[i][1] for i in range(7 * small_layers)])
+        dev_rel = float((y_small - y_big).abs().max() / y_big.abs().max())
+        if dev_rel > 1e-4:
+            print(f"bench.py: GEMV with 1024-symbol segments disagrees with the 4096-symbol run ({dev_rel})", file=sys.stderr)
+            sys.exit(1)
+        s_stream = sum(e.stream.size for e in encs_s)
+        s_sym = sum(e.n for e in encs_s)
+        result["gemv_segments_1024"] = {"us_per_layer": round(wsm * 1e3 / small_layers, 2), "layers": small_layers,
+                                        "launches_per_layer": len(groups),
+                                        "mean_code_len_bits_incl_offsets": round((s_stream * 8 + sum(e.offsets.size for e in encs_s) * 64) / s_sym, 4),
+                                        "effective_uint8_GBps": round(s_sym / (wsm * 1e-3) / 1e9, 2)}
+        log(f"gemv, 1024-symbol segments: {result['gemv_segments_1024']['us_per_layer']} us/layer")
+
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)

@@ -26,8 +26,10 @@ def encode_spec(spec: "synth.TensorSpec", chunk_symbols: Optional[int] = None) -
 
 
 def prepare_config(cfg: int, layers: Optional[int] = None, threads: Optional[int] = None,
-                   progress=None) -> List[B.EncodedTensor]:
-    """Encoded tensors of workload `cfg` in the order of synth.config_tensors."""
+                   progress=None, chunk_symbols: Optional[int] = None) -> List[B.EncodedTensor]:
+    """Encoded tensors of workload `cfg` in the order of synth.config_tensors.
+
+    chunk_symbols overrides the workload's own segment size (an encode-time choice per tensor)."""
     specs = synth.config_tensors(cfg, layers)
     threads = threads or default_threads()
     # the host library spawns its own threads per call; keep the product bounded
@@ -35,7 +37,7 @@ def prepare_config(cfg: int, layers: Optional[int] = None, threads: Optional[int
     out: List[Optional[B.EncodedTensor]] = [None] * len(specs)
 
     def work(i):
-        out[i] = encode_spec(specs[i])
+        out[i] = encode_spec(specs[i], chunk_symbols)
         if progress:
             progress(i, len(specs))
         return i
