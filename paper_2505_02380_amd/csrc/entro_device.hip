@@ -81,10 +81,10 @@ enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 
 // converts per flush pass (a 16-byte store for all but fp32) and bytes that a
 // row becomes in memory.  The host glue sizes its launches with the same numbers.
 template <int MODE> struct Cfg;
-template <> struct Cfg<kModeU8> { static constexpr int spb = 64, waves = 9, piece = 16, out_row = 64; };
+template <> struct Cfg<kModeU8> { static constexpr int spb = 64, waves = 10, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 64; };
-template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 256; };
-template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 9, piece = 8, out_row = 128; };
+template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 10, piece = 8, out_row = 256; };
+template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 10, piece = 8, out_row = 128; };
 template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 8, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 8, piece = 8, out_row = 0; };
 
@@ -115,15 +115,22 @@ struct alignas(16) Tables {
 // Per-wave LDS: the lanes' stream rings and their output rows.
 // The ring is stored dword-major (dword d of lane l at d * 64 + l): whatever
 // dword each lane reads, lane l stays on bank l % 32.  A tile row holds the SPB
-// symbol bytes a lane decodes between two flushes; all lanes write the same
-// dword of their rows at the same time, and the odd dword stride puts those on
-// different banks, as it does for the row-wise reads of the flush.
+// symbol bytes a lane decodes between two flushes.  Rows have no padding; row r
+// is rotated by tile_rot(r) dwords instead, which spreads over all banks both
+// the writes (all lanes write the same dword of their rows at the same time) and
+// the row-wise reads of the flush.
 template <int SPB>
 struct alignas(16) WaveMem {
-    static constexpr int tile_stride = SPB / 4 + 1;
-    static_assert(tile_stride % 2 == 1, "odd stride keeps the lanes' rows on different banks");
+    static constexpr int row_dwords = SPB / 4;
+    static_assert(row_dwords == 16 || row_dwords == 32, "the rotation below is made for these");
     uint32_t ring[kRingDwords * 64];
-    uint32_t tile[64 * tile_stride];
+    uint32_t tile[64 * row_dwords];
+    // rows of 16 dwords alternate between the two halves of the 32 banks, so pairs of rows share a rotation
+    static __device__ __forceinline__ uint32_t tile_rot(uint32_t row) { return row_dwords == 16 ? row >> 1 : row; }
+    // where dword j of row `row` lives
+    static __device__ __forceinline__ uint32_t tile_at(uint32_t row, uint32_t j) {
+        return row * row_dwords + ((j + tile_rot(row)) & (row_dwords - 1));
+    }
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -509,15 +516,27 @@ __device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &t
     }
     packed = __builtin_amdgcn_ubfe(packed, 0, 8u * at) | (entry_sym(e) << (8u * at));
     r.q += entry_len(e);
-#pragma unroll 1
-    for (uint32_t i = 1; i < static_cast<uint32_t>(kGroup); ++i) {
-        if (i > at) {
-            if (ring_short(r, 0)) ring_reload(r);
-            const uint64_t wi = ring_read(r);
-            e = lut_at(tb, static_cast<uint32_t>(wi) & (kL1Mask << 1));
-            if (__builtin_expect(entry_len(e) == 0, 0)) e = decode_long(tb, e, static_cast<uint32_t>(wi >> 1), max_len);
-            packed |= entry_sym(e) << (8u * i);
-            r.q += entry_len(e);
+    if (at < static_cast<uint32_t>(kGroup) - 1u) {
+        // the symbols behind it: one fresh window holds them all unless another long code turns up
+        if (ring_short(r, 0)) ring_reload(r);
+        uint64_t wi = ring_read(r);
+#pragma unroll
+        for (uint32_t i = 1; i < static_cast<uint32_t>(kGroup); ++i) {
+            if (i > at) {
+                e = lut_at(tb, static_cast<uint32_t>(wi) & (kL1Mask << 1));
+                if (__builtin_expect(entry_len(e) == 0, 0)) {
+                    if (ring_short(r, 0)) ring_reload(r);
+                    wi = ring_read(r);
+                    e = decode_long(tb, e, static_cast<uint32_t>(wi >> 1), max_len);
+                    r.q += entry_len(e);
+                    if (ring_short(r, 0)) ring_reload(r);
+                    wi = ring_read(r);
+                } else {
+                    wi >>= entry_len(e);
+                    r.q += entry_len(e);
+                }
+                packed |= entry_sym(e) << (8u * i);
+            }
         }
     }
     // the groups that follow in this trip count on the usual margin
@@ -568,7 +587,6 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     constexpr bool GEMV = MODE == kModeGemvF32 || MODE == kModeGemvBF16;
     constexpr int SPB = Cfg<MODE>::spb;
     constexpr int OUT_ROW = Cfg<MODE>::out_row;
-    constexpr int TS = WaveMem<SPB>::tile_stride;
     constexpr uint32_t PIECE = Cfg<MODE>::piece;          // symbols one lane converts per pass
     constexpr uint32_t LPR = SPB / PIECE;                 // lanes that consume one row
     constexpr uint32_t RPI = 64 / LPR;                    // rows per pass
@@ -603,7 +621,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const uint32_t max_len = t.max_len;
     const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
     const float scale = t.scale;
-    lds_v32 my_row = (lds_v32)(wm.tile + lane * TS);
+    lds_v32 tile = (lds_v32)wm.tile;
 
     // GEMV: the lane sums, for the eight rows it serves, its eight-symbol piece of every block.
     // A segment is at most as long as a matrix row here, so it touches one row (acc_a) or the
@@ -627,7 +645,8 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         for (int trip = 0; trip < TRIPS; ++trip) {
             if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
 #pragma unroll
-            for (int g = 0; g < kTripGroups; ++g) my_row[trip * kTripGroups + g] = ring_group(r, tb, max_len);
+            for (int g = 0; g < kTripGroups; ++g)
+                tile[WaveMem<SPB>::tile_at(lane, trip * kTripGroups + g)] = ring_group(r, tb, max_len);
         }
         ring_topup(r);
         wave_sync_lds();
@@ -635,7 +654,9 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
             const uint32_t rr = it * RPI + lane / LPR;
             const uint32_t piece = lane % LPR;
-            const uint32_t *src = wm.tile + rr * TS + piece * (PIECE / 4);
+            uint32_t src[PIECE / 4];
+#pragma unroll
+            for (uint32_t j = 0; j < PIECE / 4; ++j) src[j] = tile[WaveMem<SPB>::tile_at(rr, piece * (PIECE / 4) + j)];
             const uint32_t kk = wave_first + rr;
             const bool full = kk < n_full;
             uint8_t *dst = row0 + static_cast<uint64_t>(it) * (RPI * bytes_per_chunk) + static_cast<uint64_t>(bs) * OUT_ROW;
