@@ -143,6 +143,7 @@ typedef u32x2 __attribute__((address_space(1))) *global_u2_wptr;
 // LDS pointers with the address space spelled out: the accesses compile to plain
 // ds_ instructions with 32-bit addresses
 typedef volatile uint32_t __attribute__((address_space(3))) *lds_v32;
+typedef const uint32_t __attribute__((address_space(3))) *lds_p32;
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -486,7 +487,8 @@ __device__ __forceinline__ void ring_topup(RingReader &r) {
 
 // The stream from bit q = p - 1 on: 63 valid bits above the stale one.
 __device__ __forceinline__ uint64_t ring_read(const RingReader &r) {
-    lds_v32 src = r.ring + ((r.q >> 5) & 31u) * 64u;
+    // a plain (not volatile) pointer: the compiler may fetch two of the dwords with one instruction
+    const lds_p32 src = (lds_p32)(r.ring + ((r.q >> 5) & 31u) * 64u);
     const uint32_t w0 = src[0], w1 = src[64], w2 = src[128];
     const uint32_t lo = __builtin_amdgcn_alignbit(w1, w0, r.q);     // uses q & 31
     const uint32_t hi = __builtin_amdgcn_alignbit(w2, w1, r.q);
