@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="layers of the mistral-7B-shaped set (32 = the full workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the u8 and GEMV legs")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the legs on configs[0..2]")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -295,6 +296,62 @@ def main():
                                         "mean_code_len_bits_incl_offsets": round((s_stream * 8 + sum(e.offsets.size for e in encs_s) * 64) / s_sym, 4),
                                         "effective_uint8_GBps": round(s_sym / (wsm * 1e-3) / 1e9, 2)}
         log(f"gemv, 1024-symbol segments: {result['gemv_segments_1024']['us_per_layer']} us/layer")
+
+    # ------------------------------------------------ the other workloads: integer decode
+    if not args.no_other_configs:
+        del out_bf16, views, ts, plan
+        others = {}
+        for cfg, label, dtype_out in ((1, "configs[0]: one 2048x2048 tensor, round trip -> u8", E.ENTRO_U8),
+                                      (2, "configs[1]: smolLM-1.7B-shaped, 24 layers + norm gains -> u8", E.ENTRO_U8),
+                                      (3, "configs[2]: phi3-mini-shaped, 32 layers, 4-bit -> packed u4", E.ENTRO_U4_PACKED)):
+            log(f"preparing and timing {label}")
+            enc_c = prepare_config(cfg)
+            dts_c = [E.to_device(e, dev) for e in enc_c]
+            packed = dtype_out == E.ENTRO_U4_PACKED
+            sizes = [(e.n + 1) // 2 if packed else e.n for e in enc_c]
+            pad = [(-sz) % 16 for sz in sizes]                       # keep every tensor's output 16-byte aligned
+            out_c = torch.zeros(sum(sizes) + sum(pad), dtype=torch.uint8, device=dev)
+            v_c, pos = [], 0
+            for sz, pd in zip(sizes, pad):
+                v_c.append(out_c[pos:pos + sz])
+                pos += sz + pd
+            ts_c = [d.ctensor(v) for d, v in zip(dts_c, v_c)]
+            ws_c = torch.zeros(E.entro_workspace_bytes(ts_c, E.ENTRO_OP_DECODE), dtype=torch.uint8, device=dev)
+            plan_c = E.entro_plan_init(ts_c, E.ENTRO_OP_DECODE, dtype_out, ws_c)
+            wc, kc = timed(lambda: E.entro_plan_run(plan_c), args.steps, args.warmup)
+            # sampled segments against the oracle (config 1: the whole tensor)
+            rngc = np.random.default_rng(cfg)
+            n_checks = 0
+            for _ in range(12):
+                i = int(rngc.integers(0, len(enc_c)))
+                e = enc_c[i]
+                k = int(rngc.integers(0, e.offsets.size - 1))
+                lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
+                q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
+                                         out=np.zeros(e.n, np.uint8))[lo:hi]
+                if packed:
+                    ref = oracle.pack_u4(q)
+                    got = v_c[i][lo // 2:(hi + 1) // 2].cpu().numpy()
+                else:
+                    ref, got = q, v_c[i][lo:hi].cpu().numpy()
+                if not np.array_equal(got, ref):
+                    print(f"bench.py: GPU output differs from the oracle in {label}, tensor {e.name} segment {k}", file=sys.stderr)
+                    sys.exit(1)
+                n_checks += 1
+            n_c = sum(e.n for e in enc_c)
+            sb_c = sum(e.stream.size for e in enc_c)
+            ob_c = sum(e.offsets.size * 8 for e in enc_c)
+            bits_c = sum(e.total_bits for e in enc_c) / n_c
+            others[f"config{cfg}"] = {"workload": label, "symbols": n_c, "tensors": len(enc_c),
+                                      "mean_code_len_bits": round(bits_c, 4), "ms_per_step": round(wc, 4),
+                                      "kernel_ms": round(kc, 4), "symbols_per_s": round(n_c / (wc * 1e-3), 0),
+                                      "decoded_GBps": round(sum(sizes) / (wc * 1e-3) / 1e9, 2),
+                                      "compressed_GBps": round(sb_c / (wc * 1e-3) / 1e9, 2),
+                                      "hbm_frac": round((sb_c + ob_c + sum(sizes)) / (kc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                      "verified_segments": n_checks}
+            log(f"config {cfg}: {wc:.3f} ms/step")
+            del enc_c, dts_c, out_c, v_c, ts_c, plan_c
+        result["other_configs"] = others
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
