@@ -368,15 +368,15 @@ template <> struct OutTraits<kModeU4> { static constexpr int ebits = 4; };
 template <> struct OutTraits<kModeF32> { static constexpr int ebits = 32; };
 template <> struct OutTraits<kModeBF16> { static constexpr int ebits = 16; };
 
-// All nsym symbols of segment k, element by element.
+// nsym symbols, element by element: the stream from absolute bit `pos` on holds the tensor's symbols
+// first_sym, first_sym + 1, ... (first_sym is even for packed 4-bit output).
 template <int MODE>
-__device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t nsym) {
+__device__ void decode_scalar_from(const DevTensor &t, const Tables &tb, uint64_t pos, uint64_t first_sym, uint32_t nsym) {
     ScalarReader r;
     r.stream = t.stream;
     r.last_off = t.stream_bytes - 8u;
-    r.pos = t.offsets[k];
+    r.pos = pos;
     r.buf = 0;
-    const uint64_t first_sym = static_cast<uint64_t>(k) * t.chunk_symbols;
     const uint32_t max_len = t.max_len;
     const int32_t z = t.zero_point;
     const float s = t.scale;
@@ -395,6 +395,12 @@ __device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, 
         if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, z, s);
     }
     if (MODE == kModeU4 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
+}
+
+// All nsym symbols of segment k, element by element.
+template <int MODE>
+__device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t nsym) {
+    decode_scalar_from<MODE>(t, tb, t.offsets[k], static_cast<uint64_t>(k) * t.chunk_symbols, nsym);
 }
 
 // ------------------------------------------------------------------ ring reader
@@ -608,8 +614,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
         nsym = left < C ? static_cast<uint32_t>(left) : C;
     }
-    // a shorter last segment goes through the scalar path as a whole
-    const bool fast = nsym == C;
+    // A shorter last segment takes the row path for its whole blocks and the scalar path for the
+    // rest (GEMV: the scalar path as a whole).  The lane moves on with the others past its own end;
+    // what it decodes there is not stored.
+    const bool fast = GEMV ? nsym == C : nsym != 0;
+    const uint32_t my_blocks = nsym / SPB;
+    uint64_t tail_pos = fast ? t.offsets[k] : 0;          // where the symbols behind the lane's last whole block start
     RingReader r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
@@ -618,6 +628,10 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     ring_load(r, fast ? t.offsets[k] : 0);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
     const uint32_t n_full = static_cast<uint32_t>(t.n / C);          // segments of full length
+    // whole blocks of the shorter last segment, if there is one (GEMV stores nothing of it here)
+    const uint32_t tail_blocks = GEMV ? 0u : static_cast<uint32_t>((t.n - static_cast<uint64_t>(n_full) * C) / SPB);
+    // a wave that holds only the shorter last segment stops after its blocks
+    const uint32_t wave_blocks = wave_first < n_full ? blocks_total : tail_blocks;
     // where the first row this lane serves in a flush pass begins; the passes are RPI rows apart
     uint8_t *const row0 = static_cast<uint8_t *>(t.out) + (wave_first + lane / LPR) * bytes_per_chunk;
     const uint32_t max_len = t.max_len;
@@ -642,7 +656,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         }
     }
 
-    for (uint32_t bs = 0; bs < blocks_total; ++bs) {
+    for (uint32_t bs = 0; bs < wave_blocks; ++bs) {
 #pragma unroll 1
         for (int trip = 0; trip < TRIPS; ++trip) {
             if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
@@ -650,6 +664,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             for (int g = 0; g < kTripGroups; ++g)
                 tile[WaveMem<SPB>::tile_at(lane, trip * kTripGroups + g)] = ring_group(r, tb, max_len);
         }
+        if (!GEMV && bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
         ring_topup(r);
         wave_sync_lds();
 #pragma unroll
@@ -660,7 +675,8 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
 #pragma unroll
             for (uint32_t j = 0; j < PIECE / 4; ++j) src[j] = tile[WaveMem<SPB>::tile_at(rr, piece * (PIECE / 4) + j)];
             const uint32_t kk = wave_first + rr;
-            const bool full = kk < n_full;
+            // the row has this block: always in a full segment, up to tail_blocks in the shorter last one
+            const bool full = kk < n_full || (kk == n_full && bs < tail_blocks);
             uint8_t *dst = row0 + static_cast<uint64_t>(it) * (RPI * bytes_per_chunk) + static_cast<uint64_t>(bs) * OUT_ROW;
             if constexpr (GEMV) {
                 const uint32_t d0 = src[0], d1 = src[1];
@@ -748,7 +764,9 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         }
         if (!fast && nsym) gemv_segment<MODE>(t, tb, k);
     } else {
-        if (!fast && nsym) decode_scalar<(GEMV ? kModeU8 : MODE)>(t, tb, k, nsym);
+        const uint32_t rest = nsym - my_blocks * SPB;
+        if (rest)
+            decode_scalar_from<(GEMV ? kModeU8 : MODE)>(t, tb, tail_pos, static_cast<uint64_t>(k) * C + my_blocks * SPB, rest);
     }
 }
 

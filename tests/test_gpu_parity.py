@@ -131,6 +131,30 @@ def test_odd_chunk_sizes_take_the_scalar_store_path():
         assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED), oracle.pack_u4(sym4)), chunk
 
 
+def test_shorter_last_segment_of_every_shape():
+    # the last segment's whole blocks go through the row path and the rest through the scalar path:
+    # sweep its length over none / less than a block / whole blocks / blocks and a rest, alone in the
+    # tensor, alone in its wave (65 segments) and beside full ones
+    rng = np.random.default_rng(77)
+    chunk = 512
+    base = np.minimum(rng.geometric(0.3, 66 * chunk) - 1, 255).astype(np.uint8)
+    base[rng.random(base.size) < 0.002] = 255                       # a few long codes
+    for full in (0, 1, 64, 65):
+        for last in (1, 63, 64, 65, 127, 128, 129, 256, 383, 511):
+            sym = base[: full * chunk + last]
+            enc = _oracle_encoded(sym, 8, chunk, s=0.0123, z=3)
+            tag = (full, last)
+            assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), sym), tag
+            assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch=True), sym), tag
+            ref32 = oracle.dequant_f32(sym, enc.qp.scale, 3)
+            assert np.array_equal(_gpu_dequant(enc, E.ENTRO_F32).view(np.uint32), ref32.view(np.uint32)), tag
+            refb = oracle.dequant_bf16(sym, enc.qp.scale, 3)
+            assert _bf16_ulp_diff(_gpu_dequant(enc, E.ENTRO_BF16, batch=True), refb).max() <= 1, tag
+            sym4 = (sym & 15).astype(np.uint8)
+            enc4 = _oracle_encoded(sym4, 4, chunk)
+            assert np.array_equal(_gpu_decode(enc4, E.ENTRO_U4_PACKED), oracle.pack_u4(sym4)), tag
+
+
 def test_codes_of_every_length_up_to_32():
     # lengths 1..31, 32, 32: the deepest code the format allows; symbols drawn so long codes are common
     ln = np.zeros(256, np.uint8)
