@@ -37,6 +37,7 @@ constexpr uint32_t kL1Mask = (1u << kL1) - 1u;
 constexpr int kL2Cap = 512;              // second-level entries (all long prefixes together)
 constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 20 bits
 constexpr int kL2MaxPrefixes = 64;       // more long prefixes than this: second level unused
+constexpr int kSingleBits = 9;             // pair tables: index bits of the table of single codes
 constexpr int kGroup = 4;                // symbols per ring read: 63 valid bits >= 4 * 14
 constexpr int kTripGroups = 4;           // ring reads between two checks of the ring's fill
 constexpr int kScalarProbes = 2;         // scalar reader: symbols per 64-bit load, 33 valid bits >= 2 * kL1
@@ -76,17 +77,20 @@ struct WorkItem {
 
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5 };
 
-// Per output mode: symbols of a lane that one flush takes (= bytes of its tile
-// row), waves per workgroup (what fits into the 160 KB of LDS), symbols one lane
-// converts per flush pass (a 16-byte store for all but fp32) and bytes that a
-// row becomes in memory.  The host glue sizes its launches with the same numbers.
+// Per output mode: symbols of a lane that one flush takes, bytes of its tile row
+// (one per table lookup: a symbol, or two 4-bit symbols already packed), waves
+// per workgroup (what fits into the 160 KB of LDS), tile bytes one lane consumes
+// per flush pass (a 16-byte store for all but fp32) and bytes that a row becomes
+// in memory.  The host glue sizes its launches with the same numbers.
 template <int MODE> struct Cfg;
-template <> struct Cfg<kModeU8> { static constexpr int spb = 64, waves = 10, piece = 16, out_row = 64; };
-template <> struct Cfg<kModeU4> { static constexpr int spb = 128, waves = 7, piece = 16, out_row = 64; };
-template <> struct Cfg<kModeF32> { static constexpr int spb = 64, waves = 10, piece = 8, out_row = 256; };
-template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, waves = 10, piece = 8, out_row = 128; };
-template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, waves = 8, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeU8> { static constexpr int spb = 64, row = 64, waves = 10, piece = 16, out_row = 64; };
+template <> struct Cfg<kModeU4> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 64; };
+template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 256; };
+template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
+template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
+// Packed 4-bit output decodes two symbols per lookup.
+template <int MODE> constexpr bool kPairMode = MODE == kModeU4;
 
 // Lookup tables of one workgroup (LDS).
 // Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
@@ -98,6 +102,12 @@ template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, waves = 8
 // Second level: per long prefix a block indexed by the following `depth` stream
 // bits; zero there sends the lane to the canonical search
 // (first / cnt / offs / sorted).
+// Pair tables (packed 4-bit output): a first-level entry holds the next TWO codes
+// where both fit into the kL1 index bits, their lengths added up and the two
+// symbols packed the way the output wants them (first one in the low nibble); a
+// zero entry otherwise.  There is no second level then; lut2 starts with a
+// table of single codes up to kSingleBits long instead, for what the pair table
+// leaves out and for the element-by-element paths.
 struct alignas(16) Tables {
     uint16_t lut[1 << kL1];
     uint16_t lut2[kL2Cap];
@@ -114,14 +124,14 @@ struct alignas(16) Tables {
 
 // Per-wave LDS: the lanes' stream rings and their output rows.
 // The ring is stored dword-major (dword d of lane l at d * 64 + l): whatever
-// dword each lane reads, lane l stays on bank l % 32.  A tile row holds the SPB
+// dword each lane reads, lane l stays on bank l % 32.  A tile row holds the ROW
 // symbol bytes a lane decodes between two flushes.  Rows have no padding; row r
 // is rotated by tile_rot(r) dwords instead, which spreads over all banks both
 // the writes (all lanes write the same dword of their rows at the same time) and
 // the row-wise reads of the flush.
-template <int SPB>
+template <int ROW>
 struct alignas(16) WaveMem {
-    static constexpr int row_dwords = SPB / 4;
+    static constexpr int row_dwords = ROW / 4;
     static_assert(row_dwords == 16 || row_dwords == 32, "the rotation below is made for these");
     uint32_t ring[kRingDwords * 64];
     uint32_t tile[64 * row_dwords];
@@ -167,7 +177,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 // Canonical code tables and both lookup levels, built from the 256 (or 16)
 // code lengths by the whole workgroup of WG >= 256 lanes (four waves hold the
 // symbols).  `wcnt` is scratch of 4 * 33 words.
-template <int WG>
+template <int WG, bool PAIR>
 __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
     static_assert(WG >= 256, "one lane per symbol");
     const uint32_t tid = threadIdx.x;
@@ -222,7 +232,7 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
     __syncthreads();
     uint32_t code = 0;
     const uint32_t first_prefix = tb.first_prefix;
-    const bool have_l2 = first_prefix < (1u << kL1);
+    const bool have_l2 = !PAIR && first_prefix < (1u << kL1);
     if (l) {
         for (uint32_t w = 0; w < wave; ++w) rank += wcnt[w * (ENTRO_MAX_CODE_LEN + 1) + l];
         code = tb.first[l] + rank;
@@ -276,6 +286,21 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
         cb[b] = __builtin_amdgcn_readfirstlane(tb.cnt[b]);
         ob[b] = __builtin_amdgcn_readfirstlane(tb.offs[b]);
     }
+    if constexpr (PAIR) {
+        // single codes of up to kSingleBits bits; zero: longer, or no code at all
+        for (uint32_t i = tid; i < (1u << kSingleBits); i += WG) {
+            const uint32_t v = __brev(i) >> (32 - kSingleBits);
+            uint32_t len = 0, idx = 0;
+#pragma unroll
+            for (int b = 1; b <= kSingleBits; ++b) {
+                const uint32_t d = (v >> (kSingleBits - b)) - fb[b];
+                const bool hit = d < cb[b];
+                len = hit ? static_cast<uint32_t>(b) : len;
+                idx = hit ? ob[b] + d : idx;
+            }
+            tb.lut2[i] = static_cast<uint16_t>(len ? pack_entry(tb.sorted[idx], len) : 0u);
+        }
+    }
     for (uint32_t i = tid; i < (1u << kL1); i += WG) {
         const uint32_t v = __brev(i) >> (32 - kL1);               // the index bits in code order
         uint32_t len = 0, idx = 0;
@@ -285,6 +310,28 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
             const bool hit = d < cb[b];                           // at most one length matches
             len = hit ? static_cast<uint32_t>(b) : len;
             idx = hit ? ob[b] + d : idx;
+        }
+        if constexpr (PAIR) {
+            // the first code as below (an index that starts no code moves one bit and gives symbol 0),
+            // then the code that the remaining index bits spell, if they hold all of it
+            uint32_t s0 = 0, l0 = 0;
+            if (len) { s0 = tb.sorted[idx]; l0 = len; }
+            else if (v < long_start) l0 = 1;
+            uint32_t e = 0;
+            if (l0) {
+                const uint32_t v2 = (v << l0) & kL1Mask;            // zeros behind the bits that are left
+                uint32_t len1 = 0, idx1 = 0;
+#pragma unroll
+                for (int b = 1; b <= kL1; ++b) {
+                    const uint32_t d = (v2 >> (kL1 - b)) - fb[b];
+                    const bool hit = d < cb[b];
+                    len1 = hit ? static_cast<uint32_t>(b) : len1;
+                    idx1 = hit ? ob[b] + d : idx1;
+                }
+                if (len1 && l0 + len1 <= static_cast<uint32_t>(kL1)) e = pack_entry(s0 | (static_cast<uint32_t>(tb.sorted[idx1]) << 4), l0 + len1);
+            }
+            tb.lut[i] = static_cast<uint16_t>(e);
+            continue;
         }
         // no match: the start of a longer code (the entry says where its second-level block is),
         // or, where a lone symbol leaves half of the code space unused, of none: symbol 0, one bit
@@ -299,11 +346,11 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
     __syncthreads();
 }
 
-// Canonical search over the lengths above kL1.  `window` holds the next 32
+// Canonical search over the lengths from `from` on.  `window` holds the next 32
 // stream bits, first bit in bit 0.
-__device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t window, uint32_t max_len) {
+__device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t window, uint32_t from, uint32_t max_len) {
     const uint32_t v = __brev(window);
-    for (uint32_t l = kL1 + 1; l <= max_len; ++l) {
+    for (uint32_t l = from; l <= max_len; ++l) {
         const uint32_t d = (v >> (32 - l)) - tb.first[l];
         if (d < tb.cnt[l]) return pack_entry(tb.sorted[tb.offs[l] + d], l);
     }
@@ -322,7 +369,14 @@ __device__ __forceinline__ uint32_t lookup_l2(const Tables &tb, uint32_t miss, u
 // The same with the canonical search behind it; `window` holds the next 32 stream bits.
 __device__ __forceinline__ uint32_t decode_long(const Tables &tb, uint32_t miss, uint32_t window, uint32_t max_len) {
     uint32_t e = lookup_l2(tb, miss, window);
-    if (__builtin_expect(e == 0, 0)) e = decode_canonical(tb, window, max_len);
+    if (__builtin_expect(e == 0, 0)) e = decode_canonical(tb, window, kL1 + 1, max_len);
+    return e;
+}
+
+// Pair tables: the single code at the start of `window` (the next 32 stream bits).
+__device__ __forceinline__ uint32_t single_entry(const Tables &tb, uint32_t window, uint32_t max_len) {
+    uint32_t e = tb.lut2[window & ((1u << kSingleBits) - 1u)];
+    if (__builtin_expect(e == 0, 0)) e = decode_canonical(tb, window, kSingleBits + 1, max_len);
     return e;
 }
 
@@ -349,10 +403,14 @@ struct ScalarReader {
 };
 
 // The next symbol's entry from the scalar reader; r.buf must hold kL1 valid bits.
+// With pair tables the table of single codes answers.
+template <bool PAIR>
 __device__ __forceinline__ uint32_t next_entry(ScalarReader &r, const Tables &tb, uint32_t max_len) {
-    uint32_t e = tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
+    uint32_t e = PAIR ? tb.lut2[static_cast<uint32_t>(r.buf) & ((1u << kSingleBits) - 1u)]
+                      : tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
     if (__builtin_expect(entry_len(e) == 0, 0)) {
-        e = decode_long(tb, e, static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off)), max_len);
+        const uint32_t window = static_cast<uint32_t>(load_bits(r.stream, r.pos, r.last_off));
+        e = PAIR ? decode_canonical(tb, window, kSingleBits + 1, max_len) : decode_long(tb, e, window, max_len);
         r.pos += entry_len(e);
         r.buf = load_bits(r.stream, r.pos, r.last_off);
     } else {
@@ -384,7 +442,7 @@ __device__ void decode_scalar_from(const DevTensor &t, const Tables &tb, uint64_
     uint32_t pending = 0;     // low nibble waiting for its partner (packed 4-bit)
     for (uint32_t i = 0; i < nsym; ++i) {
         if (i % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint32_t sym = entry_sym(next_entry(r, tb, max_len));
+        const uint32_t sym = entry_sym(next_entry<kPairMode<MODE>>(r, tb, max_len));
         const uint64_t idx = first_sym + i;
         if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
         if (MODE == kModeU4) {
@@ -512,15 +570,40 @@ __device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) 
 // with the bits still in the window (at least 63 - 3 * 14 of them; it needs 20)
 // or, failing that, out of the canonical search; the symbols behind it are
 // looked up one by one, each with a window of its own.
+// With pair tables a miss is a pair that the index bits do not hold in full: its
+// two codes, and whatever pair after it misses again, come from the table of
+// single codes, every one with a window of its own.
+template <bool PAIR>
 __device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &tb, uint32_t max_len, uint32_t e0,
                                                   uint32_t e1, uint32_t e2, uint32_t e3, uint64_t w, uint32_t packed) {
     const uint32_t l0 = entry_len(e0), l1 = entry_len(e1), l2 = entry_len(e2);
     const uint32_t at = l0 == 0 ? 0u : l1 == 0 ? 1u : l2 == 0 ? 2u : 3u;     // place of the long code
     r.q += l0 + l1 + l2;                                                   // its entries add nothing
+    if constexpr (PAIR) {
+        packed = __builtin_amdgcn_ubfe(packed, 0, 8u * at);
+#pragma unroll 1
+        for (uint32_t i = at; i < static_cast<uint32_t>(kGroup); ++i) {
+            if (ring_short(r, 0)) ring_reload(r);
+            uint32_t e = lut_at(tb, static_cast<uint32_t>(ring_read(r)) & (kL1Mask << 1));
+            if (entry_len(e) == 0) {
+                const uint32_t a = single_entry(tb, static_cast<uint32_t>(ring_read(r) >> 1), max_len);
+                r.q += entry_len(a);
+                if (ring_short(r, 0)) ring_reload(r);
+                const uint32_t b = single_entry(tb, static_cast<uint32_t>(ring_read(r) >> 1), max_len);
+                r.q += entry_len(b);
+                e = ((entry_sym(a) & 0xfu) | ((entry_sym(b) & 0xfu) << 4)) << 8;
+            } else {
+                r.q += entry_len(e);
+            }
+            packed |= entry_sym(e) << (8u * i);
+        }
+        if (ring_short(r, kTripBits - 64)) ring_reload(r);
+        return packed;
+    }
     uint32_t e = lookup_l2(tb, e3, static_cast<uint32_t>(w >> 1));
     if (__builtin_expect(e == 0, 0)) {
         if (ring_short(r, 0)) ring_reload(r);
-        e = decode_canonical(tb, static_cast<uint32_t>(ring_read(r) >> 1), max_len);
+        e = decode_canonical(tb, static_cast<uint32_t>(ring_read(r) >> 1), kL1 + 1, max_len);
     }
     packed = __builtin_amdgcn_ubfe(packed, 0, 8u * at) | (entry_sym(e) << (8u * at));
     r.q += entry_len(e);
@@ -558,6 +641,7 @@ __device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &t
 // bits and give the same entry of length zero); if the wave has such a lane, the
 // rest of its group is decoded with more care.  Returns the group's four symbols,
 // first one lowest.
+template <bool PAIR>
 __device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, uint32_t max_len) {
     uint64_t w = ring_read(r);
     const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
@@ -573,7 +657,7 @@ __device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, 
     const bool miss = entry_len(e3) == 0;
     if (__builtin_expect(__builtin_amdgcn_ballot_w64(miss) != 0, 0)) {
         if (miss) {
-            packed = careful_group(r, tb, max_len, e0, e1, e2, e3, w, packed);
+            packed = careful_group<PAIR>(r, tb, max_len, e0, e1, e2, e3, w, packed);
             q_next = r.q;
         }
     }
@@ -590,20 +674,24 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 // type, so that every store instruction covers whole rows, or (GEMV) multiply it
 // into the activation vector.
 template <int MODE>
-__device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::spb> *wms,
+__device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::row> *wms,
                                             uint32_t first_chunk) {
     constexpr bool GEMV = MODE == kModeGemvF32 || MODE == kModeGemvBF16;
-    constexpr int SPB = Cfg<MODE>::spb;
+    constexpr bool PAIR = kPairMode<MODE>;
+    constexpr int SPB = Cfg<MODE>::spb;                   // symbols of a lane per block
+    constexpr int ROW = Cfg<MODE>::row;                   // bytes they make in the tile
     constexpr int OUT_ROW = Cfg<MODE>::out_row;
-    constexpr uint32_t PIECE = Cfg<MODE>::piece;          // symbols one lane converts per pass
-    constexpr uint32_t LPR = SPB / PIECE;                 // lanes that consume one row
+    constexpr uint32_t PIECE = Cfg<MODE>::piece;          // tile bytes one lane consumes per pass
+    constexpr uint32_t LPR = ROW / PIECE;                 // lanes that consume one row
     constexpr uint32_t RPI = 64 / LPR;                    // rows per pass
     constexpr uint32_t EBITS = GEMV ? 0 : OutTraits<GEMV ? kModeU8 : MODE>::ebits;
-    constexpr int TRIPS = SPB / (kGroup * kTripGroups);
-    static_assert(SPB % (kGroup * kTripGroups) == 0, "a row is a whole number of trips");
+    constexpr int TRIPS = ROW / (kGroup * kTripGroups);
+    static_assert(ROW % (kGroup * kTripGroups) == 0, "a row is a whole number of trips");
+    static_assert(SPB == (PAIR ? 2 : 1) * ROW, "one tile byte per lookup");
+    static_assert(!GEMV || SPB == ROW, "the GEMV indexes columns by tile bytes");
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
-    WaveMem<SPB> &wm = wms[wave];
+    WaveMem<ROW> &wm = wms[wave];
     const uint32_t wave_first = first_chunk + wave * 64u;
     if (wave_first >= t.n_chunks) return;
     const uint32_t C = t.chunk_symbols;
@@ -662,7 +750,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
 #pragma unroll
             for (int g = 0; g < kTripGroups; ++g)
-                tile[WaveMem<SPB>::tile_at(lane, trip * kTripGroups + g)] = ring_group(r, tb, max_len);
+                tile[WaveMem<ROW>::tile_at(lane, trip * kTripGroups + g)] = ring_group<PAIR>(r, tb, max_len);
         }
         if (!GEMV && bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
         ring_topup(r);
@@ -673,7 +761,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             const uint32_t piece = lane % LPR;
             uint32_t src[PIECE / 4];
 #pragma unroll
-            for (uint32_t j = 0; j < PIECE / 4; ++j) src[j] = tile[WaveMem<SPB>::tile_at(rr, piece * (PIECE / 4) + j)];
+            for (uint32_t j = 0; j < PIECE / 4; ++j) src[j] = tile[WaveMem<ROW>::tile_at(rr, piece * (PIECE / 4) + j)];
             const uint32_t kk = wave_first + rr;
             // the row has this block: always in a full segment, up to tail_blocks in the shorter last one
             const bool full = kk < n_full || (kk == n_full && bs < tail_blocks);
@@ -697,18 +785,10 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                     acc_a[it] += second ? 0.0f : part;
                     acc_b[it] += second ? part : 0.0f;
                 }
-            } else if constexpr (MODE == kModeU8) {
+            } else if constexpr (MODE == kModeU8 || MODE == kModeU4) {
+                // the tile bytes are the output bytes (4-bit pairs come packed out of the table)
                 const u32x4 v = {src[0], src[1], src[2], src[3]};
                 if (full) *(global_u4_wptr)(dst + piece * 16u) = v;
-            } else if constexpr (MODE == kModeU4) {
-                // 16 symbols, one per byte -> 8 bytes, even symbol in the low nibble
-                const u32x4 v = {src[0], src[1], src[2], src[3]};
-                u32x2 pk;
-                uint32_t a = (v.x | (v.x >> 4)) & 0x00ff00ffu, b = (v.y | (v.y >> 4)) & 0x00ff00ffu;
-                pk.x = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
-                a = (v.z | (v.z >> 4)) & 0x00ff00ffu; b = (v.w | (v.w >> 4)) & 0x00ff00ffu;
-                pk.y = ((a | (a >> 8)) & 0xffffu) | (((b | (b >> 8)) & 0xffffu) << 16);
-                if (full) *(global_u2_wptr)(dst + piece * 8u) = pk;
             } else {
                 // 8 symbols -> w = (q - z) * s: exact difference, one fp32 multiply
                 const uint32_t d0 = src[0], d1 = src[1];
@@ -796,7 +876,7 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     float head = 0.0f, tail = 0.0f;
     for (uint32_t i = 0; i < nsym; ++i) {
         if (i % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint32_t sym = entry_sym(next_entry(r, tb, max_len));
+        const uint32_t sym = entry_sym(next_entry<false>(r, tb, max_len));
         const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
         acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - z), xv, acc);
         if (++col == cols) {
@@ -824,7 +904,7 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 }
 
 // The GEMV kernels need the tables and the scratch table only.
-template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::spb> wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
 
 template <int MODE>
 __device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, SmemFor<MODE> &sm, bool build) {
@@ -832,7 +912,7 @@ __device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chun
     if (build) {
         __syncthreads();                                     // nobody reads the previous tensor's tables any more
         // the per-wave symbol counts live in the first wave's buffers, which are not in use now
-        build_tables<WG>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+        build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
     }
     if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
         // row path: a segment tiles into blocks, pieces of eight never straddle a matrix row,

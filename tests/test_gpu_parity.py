@@ -187,6 +187,30 @@ def test_more_long_prefixes_than_the_second_level_holds():
         assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch=True), sym)
 
 
+@pytest.mark.parametrize("lengths", [
+    list(range(1, 15)) + [15, 15],                 # the deepest complete code over 16 symbols
+    [1, 3, 3, 4, 4, 5, 5, 6, 6, 7, 7, 8, 8, 8, 8, 0],   # complete over 15 symbols; codes up to 8 bits
+    [7, 7, 7, 7, 7, 7, 7, 7, 8, 8, 8, 8, 8, 8, 8, 8],   # incomplete: pairs of 14..16 bits straddle the table width
+])
+def test_4bit_packed_pairs_that_the_table_does_not_hold(lengths):
+    # packed 4-bit output decodes two symbols per lookup where both codes fit into the table index;
+    # here many pairs do not (symbols drawn uniformly, so long codes are as common as short ones)
+    ln = np.zeros(16, np.uint8)
+    ln[:] = lengths
+    rng = np.random.default_rng(sum(lengths))
+    used = int(np.count_nonzero(ln))
+    sym = rng.integers(0, used, 96 * 1024 + 301).astype(np.uint8)
+    sym[: 40 * 1024] = np.minimum(rng.geometric(0.5, 40 * 1024) - 1, used - 1)   # and a stretch of mostly short ones
+    code = oracle.canonical_codes(ln)
+    for chunk in (256, 4096, 1002):
+        stream, off = oracle.encode(sym, ln, code, chunk)
+        cb = E.entro_codebook_from_lengths(ln, 4)
+        enc = B.EncodedTensor(stream, off, sym.size, chunk, cb, B.QParams(1.0, 0, 4, 1))
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED), oracle.pack_u4(sym)), chunk
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED, batch=True), oracle.pack_u4(sym)), chunk
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), sym), chunk
+
+
 def test_phi3_shaped_4bit_packed():
     spec = synth.config_tensors(3)[1]                          # o: 3072 x 3072, Laplace, 4-bit
     w = synth.make_tensor(spec)
