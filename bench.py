@@ -257,11 +257,11 @@ def main():
                                      "hbm_frac": round((stream_bytes + offset_bytes) / (ka * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         log(f"gemv, one launch: {result['gemv_one_launch']['us_per_layer']} us/layer")
 
-        # the dependent step again on layers encoded with segments of 1024 symbols: four times the lanes
-        # per launch, a quarter of the serial work per lane (segment size is a per-tensor encode choice)
+        # the dependent step again on layers encoded with segments of 512 symbols: eight times the lanes
+        # per launch, an eighth of the serial work per lane (segment size is a per-tensor encode choice)
         small_layers = min(4, layers)
-        log(f"timing the dependent GEMV step with 1024-symbol segments ({small_layers} layers)")
-        encs_s = prepare_config(4, layers=small_layers, chunk_symbols=1024)
+        log(f"timing the dependent GEMV step with 512-symbol segments ({small_layers} layers)")
+        encs_s = prepare_config(4, layers=small_layers, chunk_symbols=512)
         dts_s = [E.to_device(e, dev) for e in encs_s]
         plans_s, keep_s = [], []
         for layer in range(small_layers):
@@ -287,15 +287,15 @@ def main():
         y_big = torch.cat([pairs[i][1] for i in range(7 * small_layers)])
         dev_rel = float((y_small - y_big).abs().max() / y_big.abs().max())
         if dev_rel > 1e-4:
-            print(f"bench.py: GEMV with 1024-symbol segments disagrees with the 4096-symbol run ({dev_rel})", file=sys.stderr)
+            print(f"bench.py: GEMV with 512-symbol segments disagrees with the 4096-symbol run ({dev_rel})", file=sys.stderr)
             sys.exit(1)
         s_stream = sum(e.stream.size for e in encs_s)
         s_sym = sum(e.n for e in encs_s)
-        result["gemv_segments_1024"] = {"us_per_layer": round(wsm * 1e3 / small_layers, 2), "layers": small_layers,
+        result["gemv_segments_512"] = {"us_per_layer": round(wsm * 1e3 / small_layers, 2), "layers": small_layers,
                                         "launches_per_layer": len(groups),
                                         "mean_code_len_bits_incl_offsets": round((s_stream * 8 + sum(e.offsets.size for e in encs_s) * 64) / s_sym, 4),
                                         "effective_uint8_GBps": round(s_sym / (wsm * 1e-3) / 1e9, 2)}
-        log(f"gemv, 1024-symbol segments: {result['gemv_segments_1024']['us_per_layer']} us/layer")
+        log(f"gemv, 512-symbol segments: {result['gemv_segments_512']['us_per_layer']} us/layer")
 
     # ------------------------------------------------ the other workloads: integer decode
     if not args.no_other_configs:

@@ -87,8 +87,8 @@ template <> struct Cfg<kModeU8> { static constexpr int spb = 64, row = 64, waves
 template <> struct Cfg<kModeU4> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 256; };
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
-template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
 // Packed 4-bit output decodes two symbols per lookup.
 template <int MODE> constexpr bool kPairMode = MODE == kModeU4;
 
@@ -745,6 +745,19 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     }
 
     for (uint32_t bs = 0; bs < wave_blocks; ++bs) {
+        // GEMV: ask for the block's activations now, so that they arrive while the symbols are decoded
+        // (eight bf16 per pass; always inside x: columns come in pieces of eight and cols % 8 == 0)
+        u32x4 xblk[GEMV ? 64 / RPI : 1];
+        bool xsecond[GEMV ? 64 / RPI : 1];
+        if constexpr (GEMV) {
+#pragma unroll
+            for (uint32_t it = 0; it < 64 / RPI; ++it) {
+                uint32_t col = col0[it] + bs * SPB + (lane % LPR) * PIECE;
+                xsecond[it] = col >= cols;                            // past the row end: next row, from column 0
+                col -= xsecond[it] ? cols : 0u;
+                xblk[it] = *(global_u4_ptr)(xvec + col);
+            }
+        }
 #pragma unroll 1
         for (int trip = 0; trip < TRIPS; ++trip) {
             if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
@@ -769,14 +782,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             if constexpr (GEMV) {
                 const uint32_t d0 = src[0], d1 = src[1];
                 if (full) {
-                    uint32_t col = col0[it] + bs * SPB + piece * PIECE;
-                    const bool second = col >= cols;                  // past the row end: next row, from column 0
-                    col -= second ? cols : 0u;
-                    const u32x4 xv = *(global_u4_ptr)(xvec + col);    // eight bf16 activations
+                    const bool second = xsecond[it];
+                    const u32x4 xv = xblk[it];
                     float part = 0.0f;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint32_t xa = j < 2 ? xv[0] : xv[1], xb = j < 2 ? xv[2] : xv[3];
+                        const uint32_t xa = j < 2 ? xv.x : xv.y, xb = j < 2 ? xv.z : xv.w;
                         const float x0 = __uint_as_float((j & 1) ? (xa & 0xffff0000u) : (xa << 16));
                         const float x1 = __uint_as_float((j & 1) ? (xb & 0xffff0000u) : (xb << 16));
                         part = fmaf(static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf, x0, part);
