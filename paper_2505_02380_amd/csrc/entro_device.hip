@@ -36,7 +36,7 @@ constexpr int kL1 = 14;                  // stream bits that index the first-lev
 constexpr uint32_t kL1Mask = (1u << kL1) - 1u;
 constexpr int kL2Cap = 512;              // second-level entries (all long prefixes together)
 constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 20 bits
-constexpr int kL2MaxPrefixes = 64;       // more long prefixes than this: second level unused
+constexpr int kL2MaxPrefixes = 32;       // more long prefixes than this: second level unused (32 blocks of 16 fill it)
 constexpr int kSingleBits = 9;             // pair tables: index bits of the table of single codes
 constexpr int kGroup = 4;                // symbols per ring read: 63 valid bits >= 4 * 14
 constexpr int kTripGroups = 4;           // ring reads between two checks of the ring's fill
@@ -97,8 +97,9 @@ template <int MODE> constexpr bool kPairMode = MODE == kModeU4;
 // entry serves as a 64-bit shift amount as it stands.
 // First level: indexed by the next kL1 stream bits.  A zero length marks a prefix
 // whose code is longer than kL1 bits (a lane that looks one up does not move);
-// bits 6..8 then are the depth of the prefix's block in the second level (7: it
-// has none) and bits 9..14 the block's start in units of eight entries.
+// the whole low byte is zero then, bits 8..10 are the depth of the prefix's block
+// in the second level (7: it has none) and bits 11..15 the block's start in units
+// of sixteen entries.
 // Second level: per long prefix a block indexed by the following `depth` stream
 // bits; zero there sends the lane to the canonical search
 // (first / cnt / offs / sorted).
@@ -115,7 +116,7 @@ struct alignas(16) Tables {
     uint32_t first[ENTRO_MAX_CODE_LEN + 2];
     uint32_t offs[ENTRO_MAX_CODE_LEN + 2];
     uint32_t pdepth[kL2MaxPrefixes];     // per long prefix: bits its second-level block resolves
-    uint32_t pbase[kL2MaxPrefixes];      // and where the block starts (a multiple of 8)
+    uint32_t pbase[kL2MaxPrefixes];      // and where the block starts (a multiple of 16)
     uint32_t first_prefix;               // smallest kL1-bit prefix of a long code; 2^kL1 if level 2 is unused
     uint32_t long_start;                 // the same, but kept when level 2 is unused
     uint32_t pad[2];
@@ -130,7 +131,7 @@ struct alignas(16) Tables {
 // the writes (all lanes write the same dword of their rows at the same time) and
 // the row-wise reads of the flush.
 template <int ROW>
-struct alignas(16) WaveMem {
+struct alignas(256) WaveMem {
     static constexpr int row_dwords = ROW / 4;
     static_assert(row_dwords == 16 || row_dwords == 32, "the rotation below is made for these");
     uint32_t ring[kRingDwords * 64];
@@ -248,7 +249,7 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
             uint32_t total = 0;
             for (uint32_t q = 0; q < n_prefix; ++q) {
                 const uint32_t d = tb.pdepth[q] < cap ? tb.pdepth[q] : cap;
-                total += d < 3 ? 8u : 1u << d;
+                total += d < 4 ? 16u : 1u << d;
             }
             if (total <= static_cast<uint32_t>(kL2Cap) || cap == 0) break;
             --cap;
@@ -258,7 +259,7 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
             const uint32_t d = tb.pdepth[q] < cap ? tb.pdepth[q] : cap;
             tb.pdepth[q] = d;
             tb.pbase[q] = base;
-            base += d < 3 ? 8u : 1u << d;
+            base += d < 4 ? 16u : 1u << d;
         }
     }
     __syncthreads();
@@ -337,8 +338,8 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
         // or, where a lone symbol leaves half of the code space unused, of none: symbol 0, one bit
         uint32_t e = pack_entry(0, 1);
         if (v >= long_start) {
-            e = 7u << 6;
-            if (v >= first_prefix) e = (tb.pdepth[v - first_prefix] << 6) | ((tb.pbase[v - first_prefix] >> 3) << 9);
+            e = 7u << 8;
+            if (v >= first_prefix) e = (tb.pdepth[v - first_prefix] << 8) | ((tb.pbase[v - first_prefix] >> 4) << 11);
         }
         if (len) e = pack_entry(tb.sorted[idx], len);
         tb.lut[i] = static_cast<uint16_t>(e);
@@ -361,9 +362,9 @@ __device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t win
 // miss entry `miss`: second level (needs kL1 + kL2MaxBits valid bits).  Zero if
 // the code is longer still.
 __device__ __forceinline__ uint32_t lookup_l2(const Tables &tb, uint32_t miss, uint32_t window) {
-    const uint32_t depth = (miss >> 6) & 7u;
+    const uint32_t depth = (miss >> 8) & 7u;
     if (depth > static_cast<uint32_t>(kL2MaxBits)) return 0;
-    return tb.lut2[(((miss >> 9) << 3) + __builtin_amdgcn_ubfe(window, kL1, depth)) & (kL2Cap - 1)];
+    return tb.lut2[(((miss >> 11) << 4) + __builtin_amdgcn_ubfe(window, kL1, depth)) & (kL2Cap - 1)];
 }
 
 // The same with the canonical search behind it; `window` holds the next 32 stream bits.
@@ -654,7 +655,7 @@ __device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, 
     // byte 1 of each entry, in order
     uint32_t packed = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u) | __builtin_amdgcn_perm(e3, e2, 0x05010c0cu);
     uint32_t q_next = r.q + ((e0 + e1 + e2 + e3) & 0xffu);            // lengths add up in the low byte (<= 56)
-    const bool miss = entry_len(e3) == 0;
+    const bool miss = (e3 & 0xffu) == 0;                              // a miss entry's low byte is zero
     if (__builtin_expect(__builtin_amdgcn_ballot_w64(miss) != 0, 0)) {
         if (miss) {
             packed = careful_group<PAIR>(r, tb, max_len, e0, e1, e2, e3, w, packed);
