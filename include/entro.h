@@ -118,9 +118,9 @@ typedef struct {
     uint32_t op;          /* entro_op */
     uint32_t out;         /* entro_dtype */
     uint32_t count;       /* tensors */
-    uint32_t n_items;     /* workgroup-sized work items in the launch */
+    uint32_t n_items;     /* work items in the launch */
     uint32_t n_fix;       /* GEMV: rows that need the second-stage sum */
-    uint32_t flags;
+    uint32_t item_units;  /* units (64 segments of one tensor) per work item */
     uint64_t off_tensors, off_items, off_partials, off_fix;   /* byte offsets inside the workspace */
 } entro_plan;
 

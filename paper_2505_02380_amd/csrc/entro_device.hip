@@ -38,6 +38,7 @@ constexpr int kL2Cap = 512;              // second-level entries (all long prefi
 constexpr int kL2MaxBits = 6;            // the second level resolves codes of up to kL1 + 6 = 20 bits
 constexpr int kL2MaxPrefixes = 32;       // more long prefixes than this: second level unused (32 blocks of 16 fill it)
 constexpr int kSingleBits = 9;             // pair tables: index bits of the table of single codes
+constexpr uint32_t kUnit = 64;           // segments a wavefront decodes at a time: one per lane
 constexpr int kGroup = 4;                // symbols per ring read: 63 valid bits >= 4 * 14
 constexpr int kTripGroups = 4;           // ring reads between two checks of the ring's fill
 constexpr int kScalarProbes = 2;         // scalar reader: symbols per 64-bit load, 33 valid bits >= 2 * kL1
@@ -669,14 +670,15 @@ __device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, 
 template <int MODE>
 __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &tb, uint32_t k);
 
-// Decode the workgroup's segments SPB symbols per lane at a time into the wave's
+// Decode the kUnit segments from wave_first on, one per lane of this wavefront,
+// SPB symbols per lane at a time into the wave's
 // LDS tile (one row of symbol bytes per lane; all lanes move in step, four
 // symbols per group), then consume the tile row-wise: write it out in the output
 // type, so that every store instruction covers whole rows, or (GEMV) multiply it
 // into the activation vector.
 template <int MODE>
 __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::row> *wms,
-                                            uint32_t first_chunk) {
+                                            uint32_t wave_first) {
     constexpr bool GEMV = MODE == kModeGemvF32 || MODE == kModeGemvBF16;
     constexpr bool PAIR = kPairMode<MODE>;
     constexpr int SPB = Cfg<MODE>::spb;                   // symbols of a lane per block
@@ -693,7 +695,6 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     WaveMem<ROW> &wm = wms[wave];
-    const uint32_t wave_first = first_chunk + wave * 64u;
     if (wave_first >= t.n_chunks) return;
     const uint32_t C = t.chunk_symbols;
     const uint32_t blocks_total = C / SPB;
@@ -918,56 +919,91 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 // The GEMV kernels need the tables and the scratch table only.
 template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
 
+// Does the tensor go through decode_rows?  Segments must tile into blocks; for the
+// GEMV, pieces of eight must not straddle a matrix row and a segment must touch at
+// most two rows.
 template <int MODE>
-__device__ __forceinline__ void run_item(const DevTensor &t, uint32_t first_chunk, SmemFor<MODE> &sm, bool build) {
-    constexpr int WG = 64 * Cfg<MODE>::waves;
-    if (build) {
-        __syncthreads();                                     // nobody reads the previous tensor's tables any more
-        // the per-wave symbol counts live in the first wave's buffers, which are not in use now
-        build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
-    }
-    if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
-        // row path: a segment tiles into blocks, pieces of eight never straddle a matrix row,
-        // and a segment touches at most two rows
-        if (t.chunk_symbols % Cfg<MODE>::spb == 0 && t.cols % 8 == 0 && t.cols >= t.chunk_symbols) {
-            decode_rows<MODE>(t, sm.tb, sm.wm, first_chunk);
+__device__ __forceinline__ bool rows_fit(const DevTensor &t) {
+    if (t.chunk_symbols % Cfg<MODE>::spb != 0) return false;
+    if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) return t.cols % 8 == 0 && t.cols >= t.chunk_symbols;
+    return true;
+}
+
+// Segments [first, end) of a tensor that does not fit the row path: one lane per
+// segment, element by element, the whole workgroup striding over them.
+template <int MODE>
+__device__ __forceinline__ void scalar_chunks(const DevTensor &t, const Tables &tb, uint32_t first, uint32_t end) {
+    constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
+    for (uint32_t k = first + threadIdx.x; k < end; k += WG) {
+        if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
+            gemv_segment<MODE>(t, tb, k);
         } else {
-            const uint32_t k = first_chunk + threadIdx.x;
-            if (k < t.n_chunks) gemv_segment<MODE>(t, sm.tb, k);
-        }
-    } else {
-        if (t.chunk_symbols % Cfg<MODE>::spb == 0) {
-            decode_rows<MODE>(t, sm.tb, sm.wm, first_chunk);
-        } else {                                             // segment size does not tile into blocks
-            const uint32_t k = first_chunk + threadIdx.x;
-            if (k < t.n_chunks) {
-                const uint64_t left = t.n - static_cast<uint64_t>(k) * t.chunk_symbols;
-                decode_scalar<MODE>(t, sm.tb, k, left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols);
-            }
+            const uint64_t left = t.n - static_cast<uint64_t>(k) * t.chunk_symbols;
+            decode_scalar<MODE>(t, tb, k, left < t.chunk_symbols ? static_cast<uint32_t>(left) : t.chunk_symbols);
         }
     }
 }
 
+// One tensor per launch: workgroup b builds the tables and takes the segments
+// [b * WG, (b + 1) * WG), 64 per wavefront.
 template <int MODE>
 __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t) {
+    constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     __shared__ SmemFor<MODE> sm;
-    run_item<MODE>(t, blockIdx.x * (64 * Cfg<MODE>::waves), sm, true);
+    // the per-wave symbol counts of the build live in the first wave's buffers, which are not in use yet
+    build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+    const uint32_t first = blockIdx.x * WG;
+    if (rows_fit<MODE>(t)) {
+        decode_rows<MODE>(t, sm.tb, sm.wm, first + (threadIdx.x >> 6) * kUnit);
+    } else {
+        const uint32_t end = first + WG;
+        scalar_chunks<MODE>(t, sm.tb, first, end < t.n_chunks ? end : t.n_chunks);
+    }
 }
 
-// Workgroup b takes the work items [b * n / G, (b + 1) * n / G) of a launch of G
-// workgroups, about one workgroup per compute unit: neighbouring items mostly
-// belong to one tensor, whose tables the workgroup then builds once.
+// Many tensors per launch.  A unit is kUnit consecutive segments of one tensor:
+// what a wavefront decodes at a time.  The work list has one item per
+// `item_units` units of a tensor (fewer at the tensor's end), in tensor order;
+// workgroup b of G takes the items [b * n / G, (b + 1) * n / G): a few stretches
+// of one tensor each.  Per stretch it builds the tensor's tables once, then its
+// wavefronts draw units from a counter in LDS until the stretch is used up.  The
+// wavefronts of a workgroup do not run equally fast (ten of them share four
+// SIMDs, three on two of them and two on the others), so a fixed split would
+// leave the faster ones waiting.
 template <int MODE>
 __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor *__restrict__ tensors,
-                                                                 const WorkItem *__restrict__ items, uint32_t n_items) {
+                                                                 const WorkItem *__restrict__ items, uint32_t n_items,
+                                                                 uint32_t item_units) {
+    constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     __shared__ SmemFor<MODE> sm;
+    __shared__ uint32_t next_unit;
     const uint32_t lo = static_cast<uint32_t>(static_cast<uint64_t>(blockIdx.x) * n_items / gridDim.x);
     const uint32_t hi = static_cast<uint32_t>(static_cast<uint64_t>(blockIdx.x + 1) * n_items / gridDim.x);
-    uint32_t built = 0xffffffffu;
-    for (uint32_t i = lo; i < hi; ++i) {
+    uint32_t i = lo;
+    while (i < hi) {
         const WorkItem it = items[i];
-        run_item<MODE>(tensors[it.tensor], it.first, sm, it.tensor != built);
-        built = it.tensor;
+        const DevTensor &t = tensors[it.tensor];
+        // the stretch ends with the tensor or with the workgroup's share
+        const uint32_t left_in_tensor = (t.n_chunks - it.first + kUnit - 1) / kUnit;
+        const uint64_t share = static_cast<uint64_t>(hi - i) * item_units;
+        const uint32_t n_units = left_in_tensor < share ? left_in_tensor : static_cast<uint32_t>(share);
+        __syncthreads();                                     // nobody reads the previous tables or the counter any more
+        build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+        if (rows_fit<MODE>(t)) {
+            if (threadIdx.x == 0) next_unit = 0;
+            __syncthreads();
+            for (;;) {
+                uint32_t u = 0;
+                if ((threadIdx.x & 63u) == 0) u = atomicAdd(&next_unit, 1u);
+                u = __builtin_amdgcn_readfirstlane(u);
+                if (u >= n_units) break;
+                decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
+            }
+        } else {
+            const uint32_t end = it.first + n_units * kUnit;
+            scalar_chunks<MODE>(t, sm.tb, it.first, end < t.n_chunks ? end : t.n_chunks);
+        }
+        i += (n_units + item_units - 1) / item_units;
     }
 }
 
@@ -1097,13 +1133,6 @@ unsigned wg_of(int mode) {
     return wg;
 }
 
-// The smallest of them over the modes of an operation: sizes the work list before the output type is known.
-unsigned wg_min(entro_op op) {
-    if (op == ENTRO_OP_DECODE) return std::min(wg_of(kModeU8), wg_of(kModeU4));
-    if (op == ENTRO_OP_DEQUANT) return std::min(wg_of(kModeF32), wg_of(kModeBF16));
-    return std::min(wg_of(kModeGemvF32), wg_of(kModeGemvBF16));
-}
-
 int mode_of(entro_op op, entro_dtype d) {
     if (op == ENTRO_OP_GEMV) return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
     switch (d) {
@@ -1168,7 +1197,7 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
     for (uint32_t i = 0; i < count; ++i) {
         if (ts[i].chunk_symbols == 0 || ts[i].n == 0) return false;
         const uint64_t nc = entro_num_chunks(ts[i].n, ts[i].chunk_symbols);
-        items += (nc + wg_min(op) - 1) / wg_min(op);
+        items += (nc + kUnit - 1) / kUnit;
         if (op == ENTRO_OP_GEMV && ts[i].cols && (ts[i].chunk_symbols % ts[i].cols) != 0) {
             fix += (static_cast<uint64_t>(ts[i].rows) + kFixWG - 1) / kFixWG;
             partial_floats += 2 * nc;
@@ -1238,19 +1267,27 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     DevTensor *dts = reinterpret_cast<DevTensor *>(host.data() + L.off_tensors);
     WorkItem *items = reinterpret_cast<WorkItem *>(host.data() + L.off_items);
     WorkItem *fix = reinterpret_cast<WorkItem *>(host.data() + L.off_fix);
-    uint64_t n_items = 0, n_fix = 0, partial_floats = 0;
-    const unsigned wg = wg_of(mode_of(op, out_type));
+    uint64_t n_items = 0, n_fix = 0, partial_floats = 0, total_units = 0;
     float *partials_base = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + L.off_partials);
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, &dts[i]);
         if (st != ENTRO_OK) return st;
-        for (uint32_t c = 0; c < dts[i].n_chunks; c += wg) items[n_items++] = WorkItem{i, c};
+        total_units += (dts[i].n_chunks + kUnit - 1) / kUnit;
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
             for (uint32_t r = 0; r < dts[i].rows; r += kFixWG) fix[n_fix++] = WorkItem{i, r};
         }
     }
+    // A work item is what a workgroup takes in one round when the launch is large (a unit per
+    // wavefront), and less when the launch would not give every compute unit an item otherwise.
+    const int mode = mode_of(op, out_type);
+    const unsigned slots = resident_workgroups(mode);
+    if (slots == 0) return ENTRO_ERR_DEVICE;
+    const uint64_t waves = wg_of(mode) / 64u;
+    const uint32_t item_units = static_cast<uint32_t>(std::min<uint64_t>(waves, std::max<uint64_t>(1, total_units / slots)));
+    for (uint32_t i = 0; i < count; ++i)
+        for (uint32_t c = 0; c < dts[i].n_chunks; c += item_units * kUnit) items[n_items++] = WorkItem{i, c};
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (!hip_ok(hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, s), "copy plan table"))
         return ENTRO_ERR_DEVICE;
@@ -1261,9 +1298,9 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     plan->op = op;
     plan->out = out_type;
     plan->count = count;
-    plan->n_items = static_cast<uint32_t>(n_items);      // at most L.n_items, which the smallest workgroup size gave
+    plan->n_items = static_cast<uint32_t>(n_items);
     plan->n_fix = L.n_fix;
-    plan->flags = 0;
+    plan->item_units = item_units;
     plan->off_tensors = L.off_tensors;
     plan->off_items = L.off_items;
     plan->off_partials = L.off_partials;
@@ -1273,7 +1310,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
 
 entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     if (!plan || !plan->workspace) return ENTRO_ERR_NULL;
-    if (plan->n_items == 0) return ENTRO_ERR_SIZE;
+    if (plan->n_items == 0 || plan->item_units == 0) return ENTRO_ERR_SIZE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const unsigned char *ws = static_cast<const unsigned char *>(plan->workspace);
     const DevTensor *dts = reinterpret_cast<const DevTensor *>(ws + plan->off_tensors);
@@ -1285,7 +1322,7 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const unsigned grid = plan->n_items < slots ? plan->n_items : slots;
     dispatch_mode(mode, [&](auto m) {
         hipLaunchKernelGGL(k_batch<decltype(m)::value>, dim3(grid), dim3(wg_of(mode)), 0, s, dts, items,
-                           plan->n_items);
+                           plan->n_items, plan->item_units);
     });
     if (!hip_ok(hipGetLastError(), "launch batched decode kernel")) return ENTRO_ERR_DEVICE;
     if (plan->n_fix) {
