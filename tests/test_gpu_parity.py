@@ -312,6 +312,40 @@ def test_many_tensors_in_one_launch():
         assert _bf16_ulp_diff(got, oracle.dequant_bf16(r, e.qp.scale, e.qp.zero_point)).max() <= 1
 
 
+def test_launch_with_a_few_units_per_work_item():
+    # 64-symbol segments make many units (64 segments each) out of little data: ~880 units over the
+    # chip's workgroups give work items of a few units, workgroup shares that start and end inside
+    # tensors, stretches shorter than a workgroup has wavefronts, and a last unit that is not full
+    rng = np.random.default_rng(88)
+    chunk, cols = 64, 128
+    encs, refs, xs = [], [], []
+    for i, units in enumerate((300, 77, 500, 1)):
+        n = units * 64 * chunk - (0 if i != 2 else 38 * chunk)          # tensor 2 ends inside a unit
+        sym = np.minimum(rng.geometric(0.2 + 0.1 * i, n) - 1, 255).astype(np.uint8)
+        encs.append(_oracle_encoded(sym, 8, chunk, rows=n // cols, cols=cols, s=np.float32(0.02), z=3 + i))
+        refs.append(sym)
+        xs.append(synth.make_x_bf16(9, i, cols))
+    dts = [E.to_device(e, DEV) for e in encs]
+    outs = [torch.zeros(e.n, dtype=torch.uint8, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DECODE), dtype=torch.uint8, device=DEV)
+    plan = E.entro_plan_init(ts, E.ENTRO_OP_DECODE, E.ENTRO_U8, ws)
+    assert 1 < plan.item_units < 10
+    E.entro_plan_run(plan)
+    torch.cuda.synchronize()
+    for o, r in zip(outs, refs):
+        assert np.array_equal(o.cpu().numpy(), r)
+    ys = [torch.zeros(e.rows, dtype=torch.float32, device=DEV) for e in encs]
+    xd = [torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16) for x in xs]
+    ts = [d.ctensor(y, x) for d, y, x in zip(dts, ys, xd)]
+    wsg = torch.zeros(max(256, E.entro_workspace_bytes(ts, E.ENTRO_OP_GEMV)), dtype=torch.uint8, device=DEV)
+    E.entro_decode_gemv_batch(ts, E.ENTRO_F32, wsg)
+    torch.cuda.synchronize()
+    for e, y, r, x in zip(encs, ys, refs, xs):
+        y_ref, _ = oracle.gemv(r, e.rows, cols, e.qp.scale, e.qp.zero_point, x)
+        _assert_gemv_close(y.cpu().numpy().astype(np.float64), y_ref)
+
+
 def test_mistral_layer_launch_shape_sampled_against_oracle():
     """Four mistral-7B-shaped layers in the batched launch bench.py uses (more work items than the chip
     holds workgroups, so workgroups walk several items and tensors); sampled segments vs the oracle."""
