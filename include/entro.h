@@ -207,7 +207,12 @@ entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *
 uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
 
 /* Validate, build the table on the host and copy it into the workspace
- * (stream-ordered).  The tensors' device buffers are referenced, not copied. */
+ * (stream-ordered).  The tensors' device buffers are referenced, not copied.
+ * The work list is cut for the current device (its number of compute units
+ * decides how many units a work item holds): run the plan on the device it was
+ * prepared on.  The launch is one workgroup per compute unit at most; inside a
+ * workgroup the wavefronts draw their segments from a counter, so which
+ * wavefront decodes which segment differs from run to run, the result does not. */
 entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
                              entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
                              void *hip_stream);
