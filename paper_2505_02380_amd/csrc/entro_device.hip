@@ -944,19 +944,21 @@ __device__ __forceinline__ void scalar_chunks(const DevTensor &t, const Tables &
     }
 }
 
-// One tensor per launch: workgroup b builds the tables and takes the segments
-// [b * WG, (b + 1) * WG), 64 per wavefront.
+// One tensor per launch: workgroup b builds the tables and takes `wg_units` units
+// (kUnit segments each, one unit per wavefront; at most as many as it has
+// wavefronts) from unit b * wg_units on.
 template <int MODE>
-__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t) {
+__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t, uint32_t wg_units) {
     constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     __shared__ SmemFor<MODE> sm;
     // the per-wave symbol counts of the build live in the first wave's buffers, which are not in use yet
     build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
-    const uint32_t first = blockIdx.x * WG;
+    const uint32_t first = blockIdx.x * wg_units * kUnit;
     if (rows_fit<MODE>(t)) {
-        decode_rows<MODE>(t, sm.tb, sm.wm, first + (threadIdx.x >> 6) * kUnit);
+        const uint32_t wave = threadIdx.x >> 6;
+        if (wave < wg_units) decode_rows<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
     } else {
-        const uint32_t end = first + WG;
+        const uint32_t end = first + wg_units * kUnit;
         scalar_chunks<MODE>(t, sm.tb, first, end < t.n_chunks ? end : t.n_chunks);
     }
 }
@@ -1172,8 +1174,16 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int mode = mode_of(op, d);
     const unsigned wg = wg_of(mode);
-    const unsigned grid = (dt.n_chunks + wg - 1) / wg;
-    dispatch_mode(mode, [&](auto m) { hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(wg), 0, s, dt); });
+    // a unit per wavefront when the tensor is large; fewer units per workgroup, down to one, when
+    // that would leave compute units without a workgroup
+    const unsigned slots = resident_workgroups(mode);
+    if (slots == 0) return ENTRO_ERR_DEVICE;
+    const unsigned units = (dt.n_chunks + kUnit - 1) / kUnit;
+    const unsigned wg_units = std::min(wg / 64u, std::max(1u, units / slots));
+    const unsigned grid = (units + wg_units - 1) / wg_units;
+    dispatch_mode(mode, [&](auto m) {
+        hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(wg), 0, s, dt, static_cast<uint32_t>(wg_units));
+    });
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
         const unsigned g2 = (dt.rows + kFixWG - 1) / kFixWG;
