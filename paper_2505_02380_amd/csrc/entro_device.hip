@@ -465,26 +465,32 @@ __device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, 
 
 // ------------------------------------------------------------------ ring reader
 // Each lane keeps up to 128 bytes of its segment in a ring in LDS (eight 16-byte
-// blocks, block j in slot j & 7) and the 64-byte line that follows the ring's
-// contents in registers: a lane asks memory for a whole line at a time.  Dwords
+// blocks, block j in slot j & 7) and the line that follows the ring's contents
+// in registers: a lane asks memory for a whole line at a time, 128 bytes in the
+// kernels that write their output (the lanes' requests are scattered over the
+// stream, and memory serves two neighbouring 64-byte halves together far better
+// than one now and one later), 64 bytes in the GEMV.  Dwords
 // 32 and 33 of the lane's ring mirror dwords 0 and 1, so a three-dword read
 // starting in the last ring dwords needs no wrap.
-// Positions are bits relative to line 0, the 64-byte line in which the segment
-// starts.  The lane tracks q = p - 1, p being its position: a window read at bit
+// Positions are bits relative to line 0, the line in which the segment starts.  The lane tracks q = p - 1, p being its position: a window read at bit
 // q carries one stale low bit, which makes bits 1..14 the first-level table's
 // byte offset of the code that starts at p.
-// Registers move into the ring only between blocks of output (ring_topup), half
-// a line at a time, at the point where the wave's previous stores have long been
+// Registers move into the ring only between blocks of output (ring_topup), two
+// blocks at a time, at the point where the wave's previous stores have long been
 // written: a wait for the line then does not wait for stores.  A lane whose codes
 // are so long that the ring runs dry in between loads its ring afresh.
+// LB: blocks per line, 8 (128 bytes) or 4 (64 bytes).
+template <int LB>
 struct RingReader {
+    static_assert(LB == 4 || LB == 8, "a line is a half or a whole 128-byte memory line");
+    static constexpr uint32_t line_bytes = 16u * LB;
     const uint8_t *stream;
     lds_v32 ring;          // this lane's dword 0; dword d is ring[d * 64]
-    uint32_t start64;      // byte offset of line 0
+    uint32_t start64;      // byte offset of line 0 (a multiple of the line size)
     uint32_t last_blk;     // stream_bytes - 16
     uint32_t q;            // p - 1
-    uint32_t end;          // the ring holds the stream up to here; a multiple of 256, at most 1024 past p's block
-    u32x4 nx[4];           // the line at `end` (its first half is in the ring already if end is not a multiple of 512)
+    uint32_t end;          // the ring holds the stream up to here; a multiple of 256, at most kRingBits past p's block
+    u32x4 nx[LB];          // the line at `end`; its pairs of blocks in front of `end` are in the ring already
 };
 
 __device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t off, uint32_t last_blk) {
@@ -492,67 +498,79 @@ __device__ __forceinline__ u32x4 load_block(const uint8_t *stream, uint32_t off,
     return *(global_u4_ptr)(stream + off);
 }
 
-// Line `line` into the registers; quarters past the end of the stream repeat its
+// Line `line` into the registers; blocks past the end of the stream repeat its
 // last block (nothing decodes them).
-__device__ __forceinline__ void load_line(RingReader &r, uint32_t line) {
-    const uint32_t base = r.start64 + (line << 6);
+template <int LB>
+__device__ __forceinline__ void load_line(RingReader<LB> &r, uint32_t line) {
+    const uint32_t base = r.start64 + line * RingReader<LB>::line_bytes;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r.nx[i] = load_block(r.stream, base + 16u * i, r.last_blk);
+    for (int i = 0; i < LB; ++i) r.nx[i] = load_block(r.stream, base + 16u * i, r.last_blk);
 }
 
 // Block `blk` (16 bytes, counted from line 0) into its slot.
-__device__ __forceinline__ void ring_store(RingReader &r, uint32_t blk, const u32x4 v) {
+template <int LB>
+__device__ __forceinline__ void ring_store(RingReader<LB> &r, uint32_t blk, const u32x4 v) {
     const uint32_t slot = blk & 7u;
     lds_v32 dst = r.ring + slot * 256u;
     dst[0] = v.x; dst[64] = v.y; dst[128] = v.z; dst[192] = v.w;
     if (slot == 0) { r.ring[32 * 64] = v.x; r.ring[33 * 64] = v.y; }
 }
 
-// Fill the ring with the two lines from absolute stream bit `pos` on and ask for the third.
-__device__ __forceinline__ void ring_load(RingReader &r, uint64_t pos) {
-    r.start64 = static_cast<uint32_t>(pos >> 3) & ~63u;
+// Fill the ring with the 128 bytes from the 64-byte half line that holds absolute
+// stream bit `pos` on, and ask for the line that holds what comes next (with
+// 128-byte lines and p in the second half of line 0 that is line 1, whose first
+// half is in the ring then).  RARE: the loads are a loop, to stay small where
+// this is inlined into paths that hardly ever run.
+template <bool RARE, int LB>
+__device__ __forceinline__ void ring_fill(RingReader<LB> &r, uint64_t pos) {
+    r.start64 = static_cast<uint32_t>(pos >> 3) & ~(RingReader<LB>::line_bytes - 1u);
     r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - 1u;
-    r.end = kRingBits;
+    const uint32_t first = ((r.q + 1u) >> 9) * 4u;                  // first block of the half line that holds p
+    r.end = kRingBits + first * 128u;
+    if (RARE) {
+#pragma unroll 1
+        for (uint32_t b = 0; b < 8; ++b) ring_store(r, first + b, load_block(r.stream, r.start64 + 16u * (first + b), r.last_blk));
+    } else {
 #pragma unroll
-    for (uint32_t b = 0; b < 8; ++b) ring_store(r, b, load_block(r.stream, r.start64 + 16u * b, r.last_blk));
-    load_line(r, 2);
+        for (uint32_t b = 0; b < 8; ++b) ring_store(r, first + b, load_block(r.stream, r.start64 + 16u * (first + b), r.last_blk));
+    }
+    load_line(r, r.end / (128u * LB));
 }
+
+template <int LB>
+__device__ __forceinline__ void ring_load(RingReader<LB> &r, uint64_t pos) { ring_fill<false>(r, pos); }
 
 // A ring read at q takes the dword that holds bit q and the two after it: it
 // stays inside the ring's contents while q + 64 < end.
-__device__ __forceinline__ bool ring_short(const RingReader &r, uint32_t ahead) { return r.q + ahead + 64u >= r.end; }
+template <int LB>
+__device__ __forceinline__ bool ring_short(const RingReader<LB> &r, uint32_t ahead) { return r.q + ahead + 64u >= r.end; }
 
-// Rare: written as a loop to stay small where it is inlined.
-__device__ __forceinline__ void ring_reload(RingReader &r) {
-    const uint64_t pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
-    r.start64 = static_cast<uint32_t>(pos >> 3) & ~63u;
-    r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - 1u;
-    r.end = kRingBits;
-#pragma unroll 1
-    for (uint32_t b = 0; b < 8; ++b) ring_store(r, b, load_block(r.stream, r.start64 + 16u * b, r.last_blk));
-    load_line(r, 2);
+// Rare: a lane whose codes are so long that the ring ran dry starts it afresh at p.
+template <int LB>
+__device__ __forceinline__ void ring_reload(RingReader<LB> &r) {
+    ring_fill<true>(r, (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u);
 }
 
-// Move what the registers hold into the blocks p has left behind: half a line
-// when two slots are free, and the other half, followed by the request for the
-// next line, when two more are.
-__device__ __forceinline__ void ring_topup(RingReader &r) {
+// Move what the registers hold into the blocks p has left behind, two blocks at
+// a time while two slots are free; after the line's last pair, ask for the next
+// line.
+template <int LB>
+__device__ __forceinline__ void ring_topup(RingReader<LB> &r) {
     const uint32_t pblk = ((r.q + 1u) >> 7) << 7;                    // start of the block that holds p
-    if ((r.end & 256u) == 0 && r.end - pblk <= kRingBits - 256u) {
-        ring_store(r, r.end >> 7, r.nx[0]);
-        ring_store(r, (r.end >> 7) + 1u, r.nx[1]);
-        r.end += 256u;
-    }
-    if ((r.end & 256u) != 0 && r.end - pblk <= kRingBits - 256u) {
-        ring_store(r, r.end >> 7, r.nx[2]);
-        ring_store(r, (r.end >> 7) + 1u, r.nx[3]);
-        r.end += 256u;
-        load_line(r, r.end >> 9);
+#pragma unroll
+    for (uint32_t pair = 0; pair < LB / 2; ++pair) {
+        if (((r.end >> 8) & (LB / 2 - 1u)) == pair && r.end - pblk <= kRingBits - 256u) {
+            ring_store(r, r.end >> 7, r.nx[2 * pair]);
+            ring_store(r, (r.end >> 7) + 1u, r.nx[2 * pair + 1]);
+            r.end += 256u;
+            if (pair == LB / 2 - 1) load_line(r, r.end / (128u * LB));
+        }
     }
 }
 
 // The stream from bit q = p - 1 on: 63 valid bits above the stale one.
-__device__ __forceinline__ uint64_t ring_read(const RingReader &r) {
+template <int LB>
+__device__ __forceinline__ uint64_t ring_read(const RingReader<LB> &r) {
     // a plain (not volatile) pointer: the compiler may fetch two of the dwords with one instruction
     const lds_p32 src = (lds_p32)(r.ring + ((r.q >> 5) & 31u) * 64u);
     const uint32_t w0 = src[0], w1 = src[64], w2 = src[128];
@@ -575,8 +593,8 @@ __device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) 
 // With pair tables a miss is a pair that the index bits do not hold in full: its
 // two codes, and whatever pair after it misses again, come from the table of
 // single codes, every one with a window of its own.
-template <bool PAIR>
-__device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &tb, uint32_t max_len, uint32_t e0,
+template <bool PAIR, int LB>
+__device__ __forceinline__ uint32_t careful_group(RingReader<LB> &r, const Tables &tb, uint32_t max_len, uint32_t e0,
                                                   uint32_t e1, uint32_t e2, uint32_t e3, uint64_t w, uint32_t packed) {
     const uint32_t l0 = entry_len(e0), l1 = entry_len(e1), l2 = entry_len(e2);
     const uint32_t at = l0 == 0 ? 0u : l1 == 0 ? 1u : l2 == 0 ? 2u : 3u;     // place of the long code
@@ -643,8 +661,8 @@ __device__ __forceinline__ uint32_t careful_group(RingReader &r, const Tables &t
 // bits and give the same entry of length zero); if the wave has such a lane, the
 // rest of its group is decoded with more care.  Returns the group's four symbols,
 // first one lowest.
-template <bool PAIR>
-__device__ __forceinline__ uint32_t ring_group(RingReader &r, const Tables &tb, uint32_t max_len) {
+template <bool PAIR, int LB>
+__device__ __forceinline__ uint32_t ring_group(RingReader<LB> &r, const Tables &tb, uint32_t max_len) {
     uint64_t w = ring_read(r);
     const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
     w >>= (e0 & 63u);
@@ -710,7 +728,9 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const bool fast = GEMV ? nsym == C : nsym != 0;
     const uint32_t my_blocks = nsym / SPB;
     uint64_t tail_pos = fast ? t.offsets[k] : 0;          // where the symbols behind the lane's last whole block start
-    RingReader r;
+    // memory serves a scattered 128-byte request far better than two of 64 bytes at different times;
+    // the GEMV, which writes nothing, does better with the smaller line and the registers it saves
+    RingReader<GEMV ? 4 : 8> r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(wm.ring + lane);
