@@ -350,6 +350,37 @@ def main():
                                       "hbm_frac": round((sb_c + ob_c + sum(sizes)) / (kc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                       "verified_segments": n_checks}
             log(f"config {cfg}: {wc:.3f} ms/step")
+            if cfg == 3:
+                # the same 4-bit set dequantized to bf16 (what an inference engine asks for), sampled like the rest
+                out_b = torch.zeros(n_c, dtype=torch.bfloat16, device=dev)
+                v_b, pos = [], 0
+                for e in enc_c:
+                    v_b.append(out_b[pos:pos + e.n])
+                    pos += e.n
+                ts_b = [d.ctensor(v) for d, v in zip(dts_c, v_b)]
+                ws_b = torch.zeros(E.entro_workspace_bytes(ts_b, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=dev)
+                plan_b = E.entro_plan_init(ts_b, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws_b)
+                wb, kb = timed(lambda: E.entro_plan_run(plan_b), args.steps, args.warmup)
+                for _ in range(12):
+                    i = int(rngc.integers(0, len(enc_c)))
+                    e = enc_c[i]
+                    k = int(rngc.integers(0, e.offsets.size - 1))
+                    lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
+                    q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
+                                             out=np.zeros(e.n, np.uint8))[lo:hi]
+                    ref = oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
+                    got = v_b[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+                    if not np.array_equal(got, ref):
+                        print(f"bench.py: bf16 output differs from the oracle in {label}, tensor {e.name} segment {k}", file=sys.stderr)
+                        sys.exit(1)
+                others["config3_bf16"] = {"workload": "configs[2] tensors, entro_decode_dequant -> bf16", "symbols": n_c,
+                                          "ms_per_step": round(wb, 4), "kernel_ms": round(kb, 4),
+                                          "symbols_per_s": round(n_c / (wb * 1e-3), 0),
+                                          "decoded_GBps": round(2 * n_c / (wb * 1e-3) / 1e9, 2),
+                                          "hbm_frac": round((sb_c + ob_c + 2 * n_c) / (kb * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                          "verified_segments": 12}
+                log(f"config 3 -> bf16: {wb:.3f} ms/step")
+                del out_b, v_b, ts_b, plan_b, ws_b
             del enc_c, dts_c, out_c, v_c, ts_c, plan_c
         result["other_configs"] = others
 

@@ -76,7 +76,12 @@ struct WorkItem {
     uint32_t first;             // first segment (main kernels) or first row (second-stage sum)
 };
 
-enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5 };
+// The P modes are the byte, fp32 and bf16 outputs of launches whose tensors all hold 4-bit symbols:
+// they decode two symbols per lookup, like the packed output.
+enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5,
+            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8 };
+// the output format of a mode
+constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
 // Per output mode: symbols of a lane that one flush takes, bytes of its tile row
 // (one per table lookup: a symbol, or two 4-bit symbols already packed), waves
@@ -90,8 +95,11 @@ template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, wave
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
 template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
-// Packed 4-bit output decodes two symbols per lookup.
-template <int MODE> constexpr bool kPairMode = MODE == kModeU4;
+template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 128; };
+template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 512; };
+template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 256; };
+// Packed 4-bit output decodes two symbols per lookup, and so do the P modes.
+template <int MODE> constexpr bool kPairMode = MODE == kModeU4 || MODE == kModeU8P || MODE == kModeF32P || MODE == kModeBF16P;
 
 // Lookup tables of one workgroup (LDS).
 // Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
@@ -170,6 +178,13 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
 __device__ __forceinline__ uint32_t pack_entry(uint32_t sym, uint32_t len) { return len | (sym << 8); }
 __device__ __forceinline__ uint32_t entry_len(uint32_t e) { return e & 0x3fu; }
 __device__ __forceinline__ uint32_t entry_sym(uint32_t e) { return e >> 8; }
+
+// The eight 4-bit symbols of four pair bytes, one per byte, in order.
+__device__ __forceinline__ void unpack_nibbles(uint32_t d, uint32_t &lo, uint32_t &hi) {
+    const uint32_t even = d & 0x0f0f0f0fu, odd = (d >> 4) & 0x0f0f0f0fu;   // symbols 0, 2, 4, 6 and 1, 3, 5, 7
+    lo = __builtin_amdgcn_perm(odd, even, 0x05010400u);
+    hi = __builtin_amdgcn_perm(odd, even, 0x07030602u);
+}
 
 __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -427,6 +442,9 @@ template <> struct OutTraits<kModeU8> { static constexpr int ebits = 8; };
 template <> struct OutTraits<kModeU4> { static constexpr int ebits = 4; };
 template <> struct OutTraits<kModeF32> { static constexpr int ebits = 32; };
 template <> struct OutTraits<kModeBF16> { static constexpr int ebits = 16; };
+template <> struct OutTraits<kModeU8P> { static constexpr int ebits = 8; };
+template <> struct OutTraits<kModeF32P> { static constexpr int ebits = 32; };
+template <> struct OutTraits<kModeBF16P> { static constexpr int ebits = 16; };
 
 // nsym symbols, element by element: the stream from absolute bit `pos` on holds the tensor's symbols
 // first_sym, first_sym + 1, ... (first_sym is even for packed 4-bit output).
@@ -446,13 +464,14 @@ __device__ void decode_scalar_from(const DevTensor &t, const Tables &tb, uint64_
         if (i % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
         const uint32_t sym = entry_sym(next_entry<kPairMode<MODE>>(r, tb, max_len));
         const uint64_t idx = first_sym + i;
-        if (MODE == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
-        if (MODE == kModeU4) {
+        constexpr int OUT = base_mode(MODE);
+        if (OUT == kModeU8) out8[idx] = static_cast<uint8_t>(sym);
+        if (OUT == kModeU4) {
             if (idx & 1) out8[idx >> 1] = static_cast<uint8_t>(pending | ((sym & 0xfu) << 4));
             else pending = sym & 0xfu;
         }
-        if (MODE == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(bf16_bits(dequant(sym, z, s)));
-        if (MODE == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, z, s);
+        if (OUT == kModeBF16) reinterpret_cast<uint16_t *>(t.out)[idx] = static_cast<uint16_t>(bf16_bits(dequant(sym, z, s)));
+        if (OUT == kModeF32) reinterpret_cast<float *>(t.out)[idx] = dequant(sym, z, s);
     }
     if (MODE == kModeU4 && (nsym & 1)) out8[(first_sym + nsym - 1) >> 1] = static_cast<uint8_t>(pending);
 }
@@ -794,15 +813,13 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
             const uint32_t rr = it * RPI + lane / LPR;
             const uint32_t piece = lane % LPR;
-            uint32_t src[PIECE / 4];
-#pragma unroll
-            for (uint32_t j = 0; j < PIECE / 4; ++j) src[j] = tile[WaveMem<ROW>::tile_at(rr, piece * (PIECE / 4) + j)];
             const uint32_t kk = wave_first + rr;
             // the row has this block: always in a full segment, up to tail_blocks in the shorter last one
             const bool full = kk < n_full || (kk == n_full && bs < tail_blocks);
             uint8_t *dst = row0 + static_cast<uint64_t>(it) * (RPI * bytes_per_chunk) + static_cast<uint64_t>(bs) * OUT_ROW;
             if constexpr (GEMV) {
-                const uint32_t d0 = src[0], d1 = src[1];
+                // the lane's eight symbols of the row
+                const uint32_t d0 = tile[WaveMem<ROW>::tile_at(rr, piece * 2u)], d1 = tile[WaveMem<ROW>::tile_at(rr, piece * 2u + 1u)];
                 if (full) {
                     const bool second = xsecond[it];
                     const u32x4 xv = xblk[it];
@@ -818,35 +835,70 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                     acc_a[it] += second ? 0.0f : part;
                     acc_b[it] += second ? part : 0.0f;
                 }
-            } else if constexpr (MODE == kModeU8 || MODE == kModeU4) {
-                // the tile bytes are the output bytes (4-bit pairs come packed out of the table)
-                const u32x4 v = {src[0], src[1], src[2], src[3]};
-                if (full) *(global_u4_wptr)(dst + piece * 16u) = v;
             } else {
-                // 8 symbols -> w = (q - z) * s: exact difference, one fp32 multiply
-                const uint32_t d0 = src[0], d1 = src[1];
-                float f[8];
+                // Store k of the pass writes the bytes [k * LPR * 16, (k + 1) * LPR * 16) of the row's
+                // piece of this block, 16 per lane, so that every store instruction covers whole
+                // stretches of memory; the lane fetches the tile bytes that become its 16 bytes.
+                constexpr int OUT = base_mode(MODE);
+                constexpr uint32_t SYMS = OUT == kModeF32 ? 4u : OUT == kModeBF16 ? 8u : OUT == kModeU8 ? 16u : 32u;   // per 16 bytes
+                constexpr uint32_t TB = PAIR && OUT != kModeU4 ? SYMS / 2u : OUT == kModeU4 ? 16u : SYMS;   // tile bytes for them
+                constexpr uint32_t NST = ROW / (LPR * TB);
+                static_assert(NST * LPR * TB == ROW && NST * LPR * 16u == static_cast<uint32_t>(OUT_ROW), "the stores tile the row");
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    f[j] = (static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf) * scale;
-                    f[4 + j] = (static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf) * scale;
-                }
-                if constexpr (MODE == kModeF32) {
-                    const u32x4 v0 = {__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
-                    const u32x4 v1 = {__float_as_uint(f[4]), __float_as_uint(f[5]), __float_as_uint(f[6]), __float_as_uint(f[7])};
-                    if (full) {
-                        *(global_u4_wptr)(dst + piece * 32u) = v0;
-                        *(global_u4_wptr)(dst + piece * 32u + 16u) = v1;
-                    }
-                } else {
-                    u32x4 v;
+                for (uint32_t k = 0; k < NST; ++k) {
+                    const uint32_t tb0 = (k * LPR + piece) * TB;        // first tile byte of this lane's share
+                    uint32_t raw[TB >= 4 ? TB / 4 : 1];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const f32x2 pr = {f[2 * j], f[2 * j + 1]};
-                        const bf16x2 b = __builtin_convertvector(pr, bf16x2);   // round to nearest even
-                        v[j] = __builtin_bit_cast(uint32_t, b);
+                    for (uint32_t j = 0; j < (TB >= 4 ? TB / 4 : 1); ++j) raw[j] = tile[WaveMem<ROW>::tile_at(rr, tb0 / 4 + j)];
+                    if (TB < 4) raw[0] = (raw[0] >> (8u * (tb0 & 3u))) & 0xffffu;    // two pair bytes out of a dword
+                    uint8_t *const at = dst + k * (LPR * 16u) + piece * 16u;
+                    if constexpr (OUT == kModeU8 || OUT == kModeU4) {
+                        u32x4 v;
+                        if constexpr (PAIR && OUT == kModeU8) {
+                            // 8 pair bytes -> 16 symbol bytes
+                            uint32_t u[4];
+                            unpack_nibbles(raw[0], u[0], u[1]);
+                            unpack_nibbles(raw[1], u[2], u[3]);
+                            v = u32x4{u[0], u[1], u[2], u[3]};
+                        } else {
+                            // the tile bytes are the output bytes (4-bit pairs come packed out of the table)
+                            v = u32x4{raw[0], raw[1], raw[2], raw[3]};
+                        }
+                        if (full) *(global_u4_wptr)at = v;
+                    } else {
+                        // w = (q - z) * s: exact difference, one fp32 multiply
+                        uint32_t sym4[SYMS / 4];                         // one symbol per byte
+                        if constexpr (PAIR) {
+                            if constexpr (SYMS == 8) {
+                                unpack_nibbles(raw[0], sym4[0], sym4[1]);
+                            } else {
+                                uint32_t unused;
+                                unpack_nibbles(raw[0], sym4[0], unused);
+                            }
+                        } else {
+#pragma unroll
+                            for (uint32_t j = 0; j < SYMS / 4; ++j) sym4[j] = raw[j];
+                        }
+                        float f[SYMS];
+#pragma unroll
+                        for (uint32_t j = 0; j < SYMS; ++j)
+                            f[j] = (static_cast<float>((sym4[j / 4] >> (8 * (j % 4))) & 0xffu) - zf) * scale;
+                        u32x4 v;
+                        if constexpr (OUT == kModeF32) {
+                            v = u32x4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const f32x2 pr = {f[2 * j], f[2 * j + 1]};
+                                const bf16x2 b = __builtin_convertvector(pr, bf16x2);   // round to nearest even
+                                v[j] = __builtin_bit_cast(uint32_t, b);
+                            }
+                        }
+                        if (full) {
+                            if constexpr (OUT == kModeF32) *(global_u4_wptr)at = v;
+                            else __builtin_nontemporal_store(v, (global_u4_wptr)at);
+                        }
                     }
-                    if (full) __builtin_nontemporal_store(v, (global_u4_wptr)(dst + piece * 16u));
                 }
             }
         }
@@ -1144,6 +1196,9 @@ void dispatch_mode(int mode, F f) {
         case kModeF32: f(std::integral_constant<int, kModeF32>{}); break;
         case kModeBF16: f(std::integral_constant<int, kModeBF16>{}); break;
         case kModeGemvF32: f(std::integral_constant<int, kModeGemvF32>{}); break;
+        case kModeU8P: f(std::integral_constant<int, kModeU8P>{}); break;
+        case kModeF32P: f(std::integral_constant<int, kModeF32P>{}); break;
+        case kModeBF16P: f(std::integral_constant<int, kModeBF16P>{}); break;
         default: f(std::integral_constant<int, kModeGemvBF16>{}); break;
     }
 }
@@ -1155,13 +1210,14 @@ unsigned wg_of(int mode) {
     return wg;
 }
 
-int mode_of(entro_op op, entro_dtype d) {
+// `pairs`: every tensor of the launch holds 4-bit symbols, so the tables can hold two codes per entry.
+int mode_of(entro_op op, entro_dtype d, bool pairs) {
     if (op == ENTRO_OP_GEMV) return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
     switch (d) {
-        case ENTRO_U8: return kModeU8;
+        case ENTRO_U8: return pairs ? kModeU8P : kModeU8;
         case ENTRO_U4_PACKED: return kModeU4;
-        case ENTRO_F32: return kModeF32;
-        default: return kModeBF16;
+        case ENTRO_F32: return pairs ? kModeF32P : kModeF32;
+        default: return pairs ? kModeBF16P : kModeBF16;
     }
 }
 
@@ -1192,7 +1248,7 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     if (st != ENTRO_OK) return st;
     dt.partials = partials;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int mode = mode_of(op, d);
+    const int mode = mode_of(op, d, dt.bits == 4);
     const unsigned wg = wg_of(mode);
     // a unit per wavefront when the tensor is large; fewer units per workgroup, down to one, when
     // that would leave compute units without a workgroup
@@ -1298,11 +1354,13 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     WorkItem *items = reinterpret_cast<WorkItem *>(host.data() + L.off_items);
     WorkItem *fix = reinterpret_cast<WorkItem *>(host.data() + L.off_fix);
     uint64_t n_items = 0, n_fix = 0, partial_floats = 0, total_units = 0;
+    bool pairs = true;                                       // every tensor 4-bit: two codes per table entry
     float *partials_base = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + L.off_partials);
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, &dts[i]);
         if (st != ENTRO_OK) return st;
         total_units += (dts[i].n_chunks + kUnit - 1) / kUnit;
+        pairs = pairs && dts[i].bits == 4;
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
@@ -1311,7 +1369,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     }
     // A work item is what a workgroup takes in one round when the launch is large (a unit per
     // wavefront), and less when the launch would not give every compute unit an item otherwise.
-    const int mode = mode_of(op, out_type);
+    const int mode = mode_of(op, out_type, pairs);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const uint64_t waves = wg_of(mode) / 64u;
@@ -1331,6 +1389,8 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     plan->n_items = static_cast<uint32_t>(n_items);
     plan->n_fix = L.n_fix;
     plan->item_units = item_units;
+    plan->pair_tables = pairs ? 1u : 0u;
+    plan->reserved = 0;
     plan->off_tensors = L.off_tensors;
     plan->off_items = L.off_items;
     plan->off_partials = L.off_partials;
@@ -1346,7 +1406,7 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const DevTensor *dts = reinterpret_cast<const DevTensor *>(ws + plan->off_tensors);
     const WorkItem *items = reinterpret_cast<const WorkItem *>(ws + plan->off_items);
     const WorkItem *fix = reinterpret_cast<const WorkItem *>(ws + plan->off_fix);
-    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out));
+    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const unsigned grid = plan->n_items < slots ? plan->n_items : slots;

@@ -153,6 +153,8 @@ def test_shorter_last_segment_of_every_shape():
             sym4 = (sym & 15).astype(np.uint8)
             enc4 = _oracle_encoded(sym4, 4, chunk)
             assert np.array_equal(_gpu_decode(enc4, E.ENTRO_U4_PACKED), oracle.pack_u4(sym4)), tag
+            assert np.array_equal(_gpu_decode(enc4, E.ENTRO_U8), sym4), tag
+            assert _bf16_ulp_diff(_gpu_dequant(enc4, E.ENTRO_BF16), oracle.dequant_bf16(sym4, enc4.qp.scale, 0)).max() <= 1, tag
 
 
 def test_codes_of_every_length_up_to_32():
@@ -218,6 +220,37 @@ def test_phi3_shaped_4bit_packed():
     enc = _oracle_encoded(q, 4, 8192, s=s, z=z)
     assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED, batch=True), oracle.pack_u4(q))
     assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), q)
+    # the byte, fp32 and bf16 outputs of an all-4-bit launch also decode two symbols per lookup
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch=True), q)
+    f = _gpu_dequant(enc, E.ENTRO_F32, batch=True)
+    assert np.array_equal(f.view(np.uint32), oracle.dequant_f32(q, s, z).view(np.uint32))
+    b = _gpu_dequant(enc, E.ENTRO_BF16)
+    assert _bf16_ulp_diff(b, oracle.dequant_bf16(q, s, z)).max() <= 1
+
+
+def test_4bit_and_8bit_tensors_in_one_launch():
+    # a launch with both alphabets cannot use the two-codes-per-entry tables: every tensor, the 4-bit
+    # ones included, goes through the single-code tables
+    rng = np.random.default_rng(48)
+    encs, refs = [], []
+    for bits, n in ((4, 300 * 1024 + 5), (8, 200 * 1024), (4, 64 * 1024)):
+        sym = np.minimum(rng.geometric(0.35, n) - 1, (1 << bits) - 1).astype(np.uint8)
+        encs.append(_oracle_encoded(sym, bits, 1024, s=np.float32(0.05), z=2))
+        refs.append(sym)
+    dts = [E.to_device(e, DEV) for e in encs]
+    outs = [torch.zeros(e.n, dtype=torch.bfloat16, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=DEV)
+    plan = E.entro_plan_init(ts, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws)
+    assert plan.pair_tables == 0
+    E.entro_plan_run(plan)
+    torch.cuda.synchronize()
+    for e, o, r in zip(encs, outs, refs):
+        got = o.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert _bf16_ulp_diff(got, oracle.dequant_bf16(r, e.qp.scale, e.qp.zero_point)).max() <= 1
+    only4 = [ts[0], ts[2]]
+    plan4 = E.entro_plan_init(only4, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws)
+    assert plan4.pair_tables == 1
 
 
 # ----------------------------------------------------------------------- dequant
