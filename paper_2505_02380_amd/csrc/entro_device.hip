@@ -785,6 +785,10 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         }
     }
 
+    // integer outputs whose blocks make 64 bytes per row: the even block's pieces, kept for the odd block's flush
+    constexpr bool HOLD = !GEMV && OUT_ROW == 64;
+    u32x4 held[HOLD ? 64 / RPI : 1];
+    bool held_full[HOLD ? 64 / RPI : 1];
     for (uint32_t bs = 0; bs < wave_blocks; ++bs) {
         // GEMV: ask for the block's activations now, so that they arrive while the symbols are decoded
         // (eight bf16 per pass; always inside x: columns come in pieces of eight and cols % 8 == 0)
@@ -864,7 +868,21 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                             // the tile bytes are the output bytes (4-bit pairs come packed out of the table)
                             v = u32x4{raw[0], raw[1], raw[2], raw[3]};
                         }
-                        if (full) *(global_u4_wptr)at = v;
+                        if constexpr (HOLD) {
+                            // a block makes only 64 bytes per row: the even block's piece waits for the odd
+                            // block's, and the two go out in neighbouring store instructions, which the L2
+                            // merges into whole 128-byte lines (64 bytes at a time reach memory at 2.8 TB/s,
+                            // the merged lines at 4.8)
+                            if ((bs & 1u) == 0 && bs + 1 < wave_blocks) {
+                                held[it] = v;
+                                held_full[it] = full;
+                            } else {
+                                if ((bs & 1u) && held_full[it]) *(global_u4_wptr)(at - OUT_ROW) = held[it];
+                                if (full) *(global_u4_wptr)at = v;
+                            }
+                        } else {
+                            if (full) *(global_u4_wptr)at = v;
+                        }
                     } else {
                         // w = (q - z) * s: exact difference, one fp32 multiply
                         uint32_t sym4[SYMS / 4];                         // one symbol per byte
