@@ -145,6 +145,18 @@ entro_status entro_build_codebook(const uint8_t *q, uint64_t n, int bits, entro_
 /* Same, from a ready histogram of 2^bits counts. */
 entro_status entro_codebook_from_counts(const uint64_t *counts, int bits, entro_codebook *cb);
 
+/* Length-limited variants (an extension towards the hardware-aware coding the
+ * paper's conclusions name as future work): the cheapest prefix code none of
+ * whose codes is longer than max_len bits (package-merge), so that a decoder's
+ * single-level table of max_len index bits holds every code and the slow path for
+ * long codes never runs.  1 <= max_len <= ENTRO_MAX_CODE_LEN; the alphabet must
+ * fit (ENTRO_ERR_CODE_TOO_LONG if more than 2^max_len symbols occur).  With
+ * max_len at or above the longest unrestricted Huffman code the cost equals the
+ * unrestricted optimum.  The device side needs no change: a codebook is a
+ * codebook. */
+entro_status entro_codebook_from_counts_limited(const uint64_t *counts, int bits, int max_len, entro_codebook *cb);
+entro_status entro_build_codebook_limited(const uint8_t *q, uint64_t n, int bits, int max_len, entro_codebook *cb);
+
 /* Canonical code values for given lengths (0 = absent).  Rejects lengths above
  * ENTRO_MAX_CODE_LEN and length sets whose Kraft sum exceeds 1. */
 entro_status entro_codebook_from_lengths(const uint8_t *len, int bits, entro_codebook *cb);

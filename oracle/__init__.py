@@ -57,6 +57,9 @@ def lib():
         L.oracle_gemv.restype = None
         L.oracle_bruteforce_min_cost.argtypes = [u64p, C.c_int]
         L.oracle_bruteforce_min_cost.restype = C.c_uint64
+        L.oracle_limited_lengths.argtypes = [u64p, C.c_int, C.c_int, u8p, u64p]
+        L.oracle_bruteforce_min_cost_limited.argtypes = [u64p, C.c_int, C.c_int]
+        L.oracle_bruteforce_min_cost_limited.restype = C.c_uint64
         _lib = L
     return _lib
 
@@ -192,6 +195,21 @@ def gemv(q, rows: int, cols: int, s, z: int, x_bf16):
 def bruteforce_min_cost(cnt) -> int:
     cnt = _c(cnt, np.uint64)
     return int(lib().oracle_bruteforce_min_cost(_p(cnt, C.c_uint64), cnt.size))
+
+
+def limited_lengths(cnt, max_len: int):
+    """Cheapest prefix-code lengths with no code longer than max_len (<= 16); -> (len uint8[A], cost)."""
+    cnt = _c(cnt, np.uint64)
+    ln = np.zeros(cnt.size, np.uint8)
+    cost = C.c_uint64(0)
+    _check(lib().oracle_limited_lengths(_p(cnt, C.c_uint64), cnt.size, int(max_len), _p(ln, C.c_uint8), C.byref(cost)),
+           "limited_lengths")
+    return ln, int(cost.value)
+
+
+def bruteforce_min_cost_limited(cnt, max_len: int) -> int:
+    cnt = _c(cnt, np.uint64)
+    return int(lib().oracle_bruteforce_min_cost_limited(_p(cnt, C.c_uint64), cnt.size, int(max_len)))
 
 
 def codebook_from_symbols(q, bits: int):

@@ -412,3 +412,69 @@ uint64_t oracle_bruteforce_min_cost(const uint64_t *cnt, int m)
     brute_rec(cnt, m, 0, 0, m - 1, 0, &best);
     return best;
 }
+
+/* ------------------------------------------------- length-limited prefix codes
+ * An extension in the direction the paper's conclusions name as future work
+ * (hardware-aware optimisation of the coder): the prefix code with the smallest
+ * sum(cnt[i] * len[i]) among those whose codes are at most max_len bits long, so
+ * that a decoder's single-level table holds every code.
+ *
+ * This is the definition written out, not a construction: every assignment of
+ * lengths 1..max_len to the symbols with a positive count whose Kraft sum
+ * sum(2^-len) is at most 1 is the length vector of a prefix code, and the
+ * minimum over all of them is taken by dynamic programming over the Kraft budget
+ * in units of 2^-max_len: best[i][u] = min over len of best[i-1][u - 2^(max_len
+ * - len)] + cnt[i] * len.  max_len <= 16 keeps the table small.
+ * len_out gets one optimal length vector (0 for absent symbols); returns 0, or 1
+ * for bad arguments (more symbols than 2^max_len codes, no symbol at all). */
+int oracle_limited_lengths(const uint64_t *cnt, int nsym, int max_len, uint8_t *len_out, uint64_t *cost_out)
+{
+    if (!cnt || !len_out || nsym < 1 || nsym > 256 || max_len < 1 || max_len > 16) return 1;
+    int idx[256], m = 0;
+    for (int s = 0; s < nsym; ++s) { len_out[s] = 0; if (cnt[s]) idx[m++] = s; }
+    if (m == 0 || ((uint64_t)m > ((uint64_t)1 << max_len))) return 1;
+    if (m == 1) { len_out[idx[0]] = 1; if (cost_out) *cost_out = cnt[idx[0]]; return 0; }
+    const uint32_t U = (uint32_t)1 << max_len;
+    uint64_t *prev = malloc(sizeof(uint64_t) * (U + 1)), *cur = malloc(sizeof(uint64_t) * (U + 1));
+    uint8_t *choice = malloc((size_t)m * (U + 1));
+    if (!prev || !cur || !choice) { free(prev); free(cur); free(choice); return 1; }
+    for (uint32_t u = 0; u <= U; ++u) prev[u] = 0;                 /* no symbol placed: cost 0 at any budget */
+    for (int i = 0; i < m; ++i) {
+        const uint64_t c = cnt[idx[i]];
+        for (uint32_t u = 0; u <= U; ++u) {
+            uint64_t best = UINT64_MAX;
+            uint8_t bl = 0;
+            for (int l = 1; l <= max_len; ++l) {
+                const uint32_t need = (uint32_t)1 << (max_len - l);
+                if (need > u || prev[u - need] == UINT64_MAX) continue;
+                const uint64_t v = prev[u - need] + c * (uint64_t)l;
+                if (v < best) { best = v; bl = (uint8_t)l; }
+            }
+            cur[u] = best;
+            choice[(size_t)i * (U + 1) + u] = bl;
+        }
+        uint64_t *t = prev; prev = cur; cur = t;
+    }
+    /* prev[u]: cheapest way to place all symbols within budget exactly-or-under u (budgets are "at most":
+     * prev of an earlier row is defined for every u, so spare budget is simply left unused) */
+    if (prev[U] == UINT64_MAX) { free(prev); free(cur); free(choice); return 1; }
+    if (cost_out) *cost_out = prev[U];
+    uint32_t u = U;
+    for (int i = m - 1; i >= 0; --i) {
+        const uint8_t l = choice[(size_t)i * (U + 1) + u];
+        len_out[idx[i]] = l;
+        u -= (uint32_t)1 << (max_len - l);
+    }
+    free(prev); free(cur); free(choice);
+    return 0;
+}
+
+/* The same minimum by plain enumeration, for m <= 8 symbols with positive counts. */
+uint64_t oracle_bruteforce_min_cost_limited(const uint64_t *cnt, int m, int max_len)
+{
+    if (m < 1 || m > 8 || max_len < 1 || max_len > 12) return 0;
+    if (m == 1) return cnt[0];
+    uint64_t best = UINT64_MAX;
+    brute_rec(cnt, m, 0, 0, max_len, 0, &best);
+    return best;
+}

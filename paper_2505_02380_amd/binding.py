@@ -81,6 +81,8 @@ def lib():
         "entro_build_codebook": (C.c_int, [u8p, C.c_uint64, C.c_int, cbp]),
         "entro_codebook_from_counts": (C.c_int, [u64p, C.c_int, cbp]),
         "entro_codebook_from_lengths": (C.c_int, [u8p, C.c_int, cbp]),
+        "entro_codebook_from_counts_limited": (C.c_int, [u64p, C.c_int, C.c_int, cbp]),
+        "entro_build_codebook_limited": (C.c_int, [u8p, C.c_uint64, C.c_int, C.c_int, cbp]),
         "entro_num_chunks": (C.c_uint64, [C.c_uint64, C.c_uint32]),
         "entro_encode_bound": (C.c_uint64, [C.c_uint64, cbp]),
         "entro_encode": (C.c_int, [u8p, C.c_uint64, cbp, C.c_uint32, u8p, C.c_uint64, u64p, u64p]),
@@ -109,7 +111,7 @@ def lib():
 
 
 EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_counts",
-            "entro_codebook_from_lengths", "entro_num_chunks", "entro_encode_bound", "entro_encode",
+            "entro_codebook_from_lengths", "entro_codebook_from_counts_limited", "entro_build_codebook_limited", "entro_num_chunks", "entro_encode_bound", "entro_encode",
             "entro_check_offsets", "entro_bits_saved", "entro_theoretical_speedup", "entro_status_string",
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
@@ -157,6 +159,23 @@ def entro_codebook_from_counts(counts: np.ndarray, bits: int) -> Codebook:
     cb = Codebook()
     _check(lib().entro_codebook_from_counts(_ptr(counts, C.c_uint64), bits, C.byref(cb)),
            "entro_codebook_from_counts")
+    return cb
+
+
+def entro_codebook_from_counts_limited(counts: np.ndarray, bits: int, max_len: int) -> Codebook:
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    assert counts.size == 1 << bits
+    cb = Codebook()
+    _check(lib().entro_codebook_from_counts_limited(_ptr(counts, C.c_uint64), bits, int(max_len), C.byref(cb)),
+           "entro_codebook_from_counts_limited")
+    return cb
+
+
+def entro_build_codebook_limited(q: np.ndarray, bits: int, max_len: int) -> Codebook:
+    q = np.ascontiguousarray(q, dtype=np.uint8).ravel()
+    cb = Codebook()
+    _check(lib().entro_build_codebook_limited(_ptr(q, C.c_uint8), q.size, bits, int(max_len), C.byref(cb)),
+           "entro_build_codebook_limited")
     return cb
 
 
@@ -227,10 +246,10 @@ class EncodedTensor:
 
 
 def encode_tensor(w: np.ndarray, bits: int, scheme: int, chunk_symbols: int, rows: int = 0, cols: int = 0,
-                  name: str = "", return_q: bool = False):
-    """entro_quantize -> entro_build_codebook -> entro_encode."""
+                  name: str = "", return_q: bool = False, max_len: int = 0):
+    """entro_quantize -> entro_build_codebook (length-limited if max_len is given) -> entro_encode."""
     q, qp = entro_quantize(w, bits, scheme)
-    cb = entro_build_codebook(q, bits)
+    cb = entro_build_codebook_limited(q, bits, max_len) if max_len else entro_build_codebook(q, bits)
     stream, offsets = entro_encode(q, cb, chunk_symbols)
     enc = EncodedTensor(stream, offsets, q.size, chunk_symbols, cb, qp, rows, cols, name)
     return (enc, q) if return_q else enc

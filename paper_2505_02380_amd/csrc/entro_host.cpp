@@ -93,6 +93,71 @@ entro_status huffman_lengths(const uint64_t *counts, int nsym, uint8_t *len) {
     return ENTRO_OK;
 }
 
+// Cheapest prefix-code lengths under a length limit, by package-merge (Larmore and
+// Hirschberg): at every level from the limit up to 1 the leaves are merged, by
+// weight, with the pairs ("packages") of the level below; the 2m - 2 lightest
+// items of the top level are kept, and a symbol's length is the number of kept
+// items its leaf is part of.  A package is a weight and, per leaf, how often it
+// holds it.
+entro_status limited_lengths(const uint64_t *counts, int nsym, int max_len, uint8_t *len) {
+    if (max_len < 1 || max_len > ENTRO_MAX_CODE_LEN) return ENTRO_ERR_SIZE;
+    std::vector<int> order;
+    for (int s = 0; s < nsym; ++s) {
+        len[s] = 0;
+        if (counts[s]) order.push_back(s);
+    }
+    const int m = static_cast<int>(order.size());
+    if (m == 0) return ENTRO_ERR_SIZE;
+    if (m == 1) {
+        len[order[0]] = 1;
+        return ENTRO_OK;
+    }
+    if (max_len < 31 && (uint64_t{1} << max_len) < static_cast<uint64_t>(m)) return ENTRO_ERR_CODE_TOO_LONG;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return counts[a] < counts[b]; });
+    struct Item {
+        unsigned __int128 w;            // sums of up to 2^31 counts of up to 2^64: more than 64 bits
+        std::vector<uint8_t> holds;     // per leaf (in sorted order): times this item holds it
+    };
+    auto leaf_items = [&]() {
+        std::vector<Item> v(m);
+        for (int i = 0; i < m; ++i) {
+            v[i].w = counts[order[i]];
+            v[i].holds.assign(m, 0);
+            v[i].holds[i] = 1;
+        }
+        return v;
+    };
+    std::vector<Item> level = leaf_items();                         // the deepest level: leaves only
+    for (int depth = max_len - 1; depth >= 1; --depth) {
+        // packages of the level below: its items paired up in weight order (an odd one out is dropped)
+        std::vector<Item> packages;
+        for (size_t i = 0; i + 1 < level.size(); i += 2) {
+            Item p;
+            p.w = level[i].w + level[i + 1].w;
+            p.holds = level[i].holds;
+            for (int j = 0; j < m; ++j) p.holds[j] = static_cast<uint8_t>(p.holds[j] + level[i + 1].holds[j]);
+            packages.push_back(std::move(p));
+        }
+        std::vector<Item> leaves = leaf_items(), merged;
+        merged.reserve(leaves.size() + packages.size());
+        size_t a = 0, b = 0;
+        while (a < leaves.size() || b < packages.size()) {
+            // a leaf first on equal weight: keeps codes short for the heavier symbols
+            if (b >= packages.size() || (a < leaves.size() && leaves[a].w <= packages[b].w)) merged.push_back(std::move(leaves[a++]));
+            else merged.push_back(std::move(packages[b++]));
+        }
+        level.swap(merged);
+    }
+    std::vector<int> depth_of(m, 0);
+    for (int i = 0; i < 2 * m - 2; ++i)
+        for (int j = 0; j < m; ++j) depth_of[j] += level[i].holds[j];
+    for (int j = 0; j < m; ++j) {
+        if (depth_of[j] < 1 || depth_of[j] > max_len) return ENTRO_ERR_CODE_TOO_LONG;   // cannot happen
+        len[order[j]] = static_cast<uint8_t>(depth_of[j]);
+    }
+    return ENTRO_OK;
+}
+
 entro_status assign_canonical(entro_codebook *cb) {
     const int nsym = 1 << cb->bits;
     uint32_t per_len[ENTRO_MAX_CODE_LEN + 2] = {0};
@@ -267,10 +332,40 @@ entro_status entro_codebook_from_counts(const uint64_t *counts, int bits, entro_
     return assign_canonical(cb);
 }
 
+entro_status entro_codebook_from_counts_limited(const uint64_t *counts, int bits, int max_len, entro_codebook *cb) {
+    if (!counts || !cb) return ENTRO_ERR_NULL;
+    if (!bits_ok(bits)) return ENTRO_ERR_BITS;
+    std::memset(cb, 0, sizeof(*cb));
+    cb->bits = bits;
+    entro_status st = limited_lengths(counts, 1 << bits, max_len, cb->len);
+    if (st != ENTRO_OK) return st;
+    return assign_canonical(cb);
+}
+
+static entro_status histogram_of(const uint8_t *q, uint64_t n, int bits, uint64_t *counts);
+
+entro_status entro_build_codebook_limited(const uint8_t *q, uint64_t n, int bits, int max_len, entro_codebook *cb) {
+    if (!q || !cb) return ENTRO_ERR_NULL;
+    if (!bits_ok(bits)) return ENTRO_ERR_BITS;
+    if (n == 0) return ENTRO_ERR_SIZE;
+    uint64_t counts[256];
+    entro_status st = histogram_of(q, n, bits, counts);
+    if (st != ENTRO_OK) return st;
+    return entro_codebook_from_counts_limited(counts, bits, max_len, cb);
+}
+
 entro_status entro_build_codebook(const uint8_t *q, uint64_t n, int bits, entro_codebook *cb) {
     if (!q || !cb) return ENTRO_ERR_NULL;
     if (!bits_ok(bits)) return ENTRO_ERR_BITS;
     if (n == 0) return ENTRO_ERR_SIZE;
+    uint64_t counts[256];
+    entro_status st = histogram_of(q, n, bits, counts);
+    if (st != ENTRO_OK) return st;
+    return entro_codebook_from_counts(counts, bits, cb);
+}
+
+// Symbol counts of q, on all host threads.
+static entro_status histogram_of(const uint8_t *q, uint64_t n, int bits, uint64_t *counts) {
     const unsigned parts = worker_count(n, 1u << 22);
     std::vector<uint64_t> hist(static_cast<size_t>(parts) * 256, 0);
     parallel_ranges(n, 1u << 22, [&](unsigned p, uint64_t b, uint64_t e) {
@@ -287,12 +382,12 @@ entro_status entro_build_codebook(const uint8_t *q, uint64_t n, int bits, entro_
         uint64_t *dst = &hist[static_cast<size_t>(p) * 256];
         for (int s = 0; s < 256; ++s) dst[s] = h[0][s] + h[1][s] + h[2][s] + h[3][s];
     });
-    uint64_t counts[256] = {0};
+    for (int s = 0; s < 256; ++s) counts[s] = 0;
     for (unsigned p = 0; p < parts; ++p)
         for (int s = 0; s < 256; ++s) counts[s] += hist[static_cast<size_t>(p) * 256 + s];
     for (int s = 1 << bits; s < 256; ++s)
         if (counts[s]) return ENTRO_ERR_SYMBOL;
-    return entro_codebook_from_counts(counts, bits, cb);
+    return ENTRO_OK;
 }
 
 uint64_t entro_num_chunks(uint64_t n, uint32_t chunk_symbols) {

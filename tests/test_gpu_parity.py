@@ -213,6 +213,30 @@ def test_4bit_packed_pairs_that_the_table_does_not_hold(lengths):
         assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8), sym), chunk
 
 
+@pytest.mark.parametrize("max_len", [11, 14, 16])
+def test_length_limited_codebooks_decode_like_any_other(max_len):
+    # codes capped below, at and above the first-level table's width; lengths from the oracle's
+    # minimisation, stream from the oracle's encoder, decoded on the GPU and by the oracle's tree walk
+    spec = synth.config_tensors(4)[1]                          # k: 1024 x 4096, the longest codes of the set
+    w = synth.make_tensor(spec)
+    q, s, z = oracle.quantize(w, 8, oracle.ASYMMETRIC)
+    cnt = oracle.histogram(q, 8)
+    ln, cost = oracle.limited_lengths(cnt, max_len)
+    assert ln.max() <= max_len and oracle.huffman_lengths(cnt).max() > 16
+    code = oracle.canonical_codes(ln)
+    stream, off = oracle.encode(q, ln, code, 4096)
+    assert int(off[-1]) == cost
+    cb = E.entro_codebook_from_lengths(ln, 8)
+    enc = B.EncodedTensor(stream, off, q.size, 4096, cb, B.QParams(np.float32(s), int(z), 8, E.ENTRO_ASYMMETRIC))
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch=True), q)
+    assert np.array_equal(oracle.decode(stream, off, q.size, 4096, ln, code), q)
+    assert _bf16_ulp_diff(_gpu_dequant(enc, E.ENTRO_BF16), oracle.dequant_bf16(q, s, z)).max() <= 1
+    # the library's own limited codebook costs the same and decodes the same
+    enc2 = E.encode_tensor(w, 8, E.ENTRO_ASYMMETRIC, 4096, max_len=max_len)
+    assert enc2.cb.max_len <= max_len and enc2.total_bits == cost
+    assert np.array_equal(_gpu_decode(enc2, E.ENTRO_U8), q)
+
+
 def test_phi3_shaped_4bit_packed():
     spec = synth.config_tensors(3)[1]                          # o: 3072 x 3072, Laplace, 4-bit
     w = synth.make_tensor(spec)

@@ -134,6 +134,54 @@ def test_codebook_limits():
 
 
 @pytest.mark.parametrize("bits", [4, 8])
+def test_limited_codebook_cost_equals_oracle(bits):
+    # package-merge in the library against the oracle's minimisation over the Kraft budget: the cost is
+    # unique, the length vector is not
+    rng = np.random.default_rng(40 + bits)
+    A = 1 << bits
+    for trial in range(16):
+        kind = trial % 4
+        if kind == 0:
+            cnt = rng.integers(0, 1000, A)
+        elif kind == 1:
+            cnt = rng.integers(0, 3, A)
+        elif kind == 2:
+            cnt = (rng.pareto(0.7, A) * 5).astype(np.int64)
+        else:
+            cnt = (2.0 ** rng.integers(0, 30, A)).astype(np.int64)
+        if cnt.sum() == 0:
+            cnt[0] = 1
+        present = int((cnt > 0).sum())
+        lo = max(1, int(np.ceil(np.log2(present)))) if present > 1 else 1
+        for L in sorted({lo, lo + 1, 9, 12, 14, 16}):
+            if L < lo:
+                continue
+            cb = E.entro_codebook_from_counts_limited(cnt.astype(np.uint64), bits, L)
+            ln = cb.lengths()
+            _, ocost = oracle.limited_lengths(cnt, L)
+            assert int(np.sum(cnt * ln.astype(np.int64))) == ocost, (trial, L)
+            assert ln.max() <= L and np.array_equal(ln > 0, cnt > 0)
+            assert _kraft(ln) <= 1 and cb.max_len == ln.max() and cb.n_used == present
+            assert np.array_equal(cb.codes(), oracle.canonical_codes(ln))
+    # a generous limit gives the unrestricted optimum; from symbols as from counts
+    q = np.minimum(rng.geometric(0.2, 50000) - 1, A - 1).astype(np.uint8)
+    cnt = np.bincount(q, minlength=A)
+    free = E.entro_build_codebook(q, bits)
+    lim = E.entro_build_codebook_limited(q, bits, 32)
+    assert int(np.sum(cnt * lim.lengths().astype(np.int64))) == int(np.sum(cnt * free.lengths().astype(np.int64)))
+    tight = E.entro_build_codebook_limited(q, bits, bits + 1)
+    assert tight.max_len <= bits + 1
+    assert np.array_equal(tight.lengths(), E.entro_codebook_from_counts_limited(cnt.astype(np.uint64), bits, bits + 1).lengths())
+    # errors: more symbols than codes, limits outside 1..32
+    with pytest.raises(E.EntroError) as e:
+        E.entro_codebook_from_counts_limited(np.ones(A, np.uint64), bits, bits - 1)
+    assert e.value.status == B.ENTRO_ERR_CODE_TOO_LONG
+    for bad in (0, 33):
+        with pytest.raises(E.EntroError):
+            E.entro_codebook_from_counts_limited(np.ones(A, np.uint64), bits, bad)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
 def test_encode_equals_oracle_bit_for_bit(bits):
     for name, sym, chunk in synth.adversarial_symbol_cases(bits):
         cb = E.entro_build_codebook(sym, bits)

@@ -142,6 +142,87 @@ def test_c_bruteforce_matches_python_bruteforce_at_7_and_8_symbols():
         assert oracle.bruteforce_min_cost(cnt) == int(np.sum(cnt * ln.astype(np.int64)))
 
 
+# ------------------------------------------------- length-limited codes (extension)
+def _py_bruteforce_limited(cnt, max_len):
+    m = len(cnt)
+    if m == 1:
+        return cnt[0]
+    best = None
+    for lens in itertools.product(range(1, max_len + 1), repeat=m):
+        if sum(Fraction(1, 2 ** v) for v in lens) <= 1:
+            c = sum(a * b for a, b in zip(cnt, lens))
+            best = c if best is None or c < best else best
+    return best
+
+
+def test_limited_lengths_are_optimal_by_brute_force():
+    # every length vector up to the limit that satisfies Kraft's inequality, enumerated in Python;
+    # the C enumeration for the larger cases is itself checked against the Python one first
+    rng = np.random.default_rng(15)
+    for m in range(2, 7):
+        for trial in range(6):
+            cnt = rng.integers(1, 60, m) if trial % 2 else (2.0 ** rng.integers(0, 10, m)).astype(np.int64)
+            lo = max(1, math.ceil(math.log2(m)))
+            for L in range(lo, min(lo + 3, 5) + 1):
+                ln, cost = oracle.limited_lengths(cnt, L)
+                assert cost == int(np.sum(cnt * ln.astype(np.int64)))
+                assert ln.max() <= L and ln.min() >= 1 and _kraft_exact(ln) <= 1
+                assert cost == _py_bruteforce_limited([int(c) for c in cnt], L), (cnt, L, ln)
+                assert cost == oracle.bruteforce_min_cost_limited(cnt, L)
+    for _ in range(4):
+        cnt = rng.integers(1, 1000, 8)
+        for L in (3, 4, 6):
+            assert oracle.limited_lengths(cnt, L)[1] == oracle.bruteforce_min_cost_limited(cnt, L)
+
+
+def test_limited_lengths_closed_forms():
+    # the example of the dyadic pin: {4,2,1,1} wants lengths {1,2,3,3} (cost 14); limited to 2 bits all four
+    # symbols get 2 (cost 16)
+    ln, cost = oracle.limited_lengths(np.array([4, 2, 1, 1]), 3)
+    assert ln.tolist() == [1, 2, 3, 3] and cost == 14
+    ln, cost = oracle.limited_lengths(np.array([4, 2, 1, 1]), 2)
+    assert ln.tolist() == [2, 2, 2, 2] and cost == 16
+    # as many symbols as the limit has codes: fixed width, whatever the counts
+    rng = np.random.default_rng(16)
+    for k in (1, 3, 5, 8):
+        cnt = rng.integers(1, 10 ** 6, 2 ** k)
+        ln, cost = oracle.limited_lengths(cnt, k)
+        assert set(ln.tolist()) == {k} and cost == k * int(cnt.sum())
+    # more symbols than codes: refused
+    with pytest.raises(oracle.OracleError):
+        oracle.limited_lengths(np.ones(9, np.int64), 3)
+    # absent symbols get no code, a lone symbol one bit
+    ln, _ = oracle.limited_lengths(np.array([0, 7, 0, 0]), 5)
+    assert ln.tolist() == [0, 1, 0, 0]
+
+
+def test_limited_lengths_against_unrestricted_huffman():
+    # a limit at or above the longest Huffman code changes nothing (same cost); a tighter one costs more,
+    # the more the tighter; the cost never drops below the entropy bound
+    rng = np.random.default_rng(17)
+    for trial in range(6):
+        m = int(rng.integers(20, 257))
+        cnt = np.zeros(256, np.int64)
+        cnt[:m] = (rng.pareto(0.8, m) * 50 + 1).astype(np.int64)
+        hl = oracle.huffman_lengths(cnt)
+        hcost = int(np.sum(cnt * hl.astype(np.int64)))
+        hmax = int(hl.max())
+        prev = None
+        for L in range(min(hmax, 16), 7, -1):
+            ln, cost = oracle.limited_lengths(cnt, L)
+            assert ln.max() <= L and _kraft_exact(ln) <= 1 and np.all((ln > 0) == (cnt > 0))
+            if L >= hmax:
+                assert cost == hcost
+            else:
+                assert cost >= hcost
+            if prev is not None:
+                assert cost >= prev
+            prev = cost
+        n = int(cnt.sum())
+        H = -sum(c / n * math.log2(c / n) for c in cnt[cnt > 0])
+        assert prev / n >= H - 1e-9
+
+
 def test_huffman_dyadic_counts_hit_entropy_exactly():
     for k in range(1, 12):
         cnt = [2 ** (k - 1 - i) for i in range(k)] + [1]           # {2^(k-1),...,2,1,1}
