@@ -297,6 +297,51 @@ def main():
                                         "effective_uint8_GBps": round(s_sym / (wsm * 1e-3) / 1e9, 2)}
         log(f"gemv, 512-symbol segments: {result['gemv_segments_512']['us_per_layer']} us/layer")
 
+    # ------------------------------------------------ the headline set again with length-limited codebooks
+    if not args.no_extras:
+        # no code longer than the decoder's first-level table is wide: the slow path for long codes never
+        # runs; what it costs in bits is reported beside what it gains
+        log("preparing the headline set with codes of at most 14 bits")
+        encs_l = prepare_config(4, layers=args.layers, max_len=14)
+        dts_l = [E.to_device(e, dev) for e in encs_l]
+        ts_l = [d.ctensor(v) for d, v in zip(dts_l, views)]
+        ws_l = torch.zeros(E.entro_workspace_bytes(ts_l, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=dev)
+        plan_l = E.entro_plan_init(ts_l, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws_l)
+        wl, kl = timed(lambda: E.entro_plan_run(plan_l), args.steps, args.warmup)
+        rngl = np.random.default_rng(14)
+        for _ in range(12):
+            i = int(rngl.integers(0, len(encs_l)))
+            e = encs_l[i]
+            k = int(rngl.integers(0, e.offsets.size - 1))
+            lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
+            q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
+                                     out=np.zeros(e.n, np.uint8))[lo:hi]
+            ref = oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
+            got = views[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+            if not np.array_equal(got, ref):
+                print(f"bench.py: length-limited leg differs from the oracle in tensor {e.name} segment {k}", file=sys.stderr)
+                sys.exit(1)
+        tl_l = [dts_l[idx].ctensor(y, x) for (x, y, idx, xb) in pairs]
+        ws_lg = torch.zeros(E.entro_workspace_bytes(tl_l, E.ENTRO_OP_GEMV), dtype=torch.uint8, device=dev)
+        plan_lg = E.entro_plan_init(tl_l, E.ENTRO_OP_GEMV, E.ENTRO_F32, ws_lg)
+        y_before = torch.cat([y for (x, y, idx, xb) in pairs]).clone()
+        wlg, klg = timed(lambda: E.entro_plan_run(plan_lg), args.steps, args.warmup)
+        y_after = torch.cat([y for (x, y, idx, xb) in pairs])
+        # same symbols, same x, same summation order: the products must not change at all
+        if not torch.equal(y_before, y_after):
+            print("bench.py: GEMV over length-limited streams differs from the unrestricted run", file=sys.stderr)
+            sys.exit(1)
+        bits_l = sum(e.total_bits for e in encs_l) / n_sym
+        sb_l = sum(e.stream.size for e in encs_l)
+        result["length_limited_14"] = {
+            "mean_code_len_bits": round(bits_l, 4), "extra_bits_per_symbol": round(bits_l - mean_len, 5),
+            "max_code_len": max(e.cb.max_len for e in encs_l), "max_code_len_unrestricted": max(e.cb.max_len for e in encs),
+            "dequant_bf16_ms": round(wl, 4), "dequant_bf16_kernel_ms": round(kl, 4),
+            "dequant_bf16_hbm_frac": round((sb_l + offset_bytes + 2 * n_sym) / (kl * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "gemv_one_launch_us_per_layer": round(wlg * 1e3 / layers, 2), "verified_segments": 12}
+        log(f"length-limited: {wl:.3f} ms/step, gemv {wlg * 1e3 / layers:.1f} us/layer, +{bits_l - mean_len:.5f} bits/symbol")
+        del encs_l, dts_l, ts_l, plan_l, tl_l, plan_lg, ws_l, ws_lg
+
     # ------------------------------------------------ the other workloads: integer decode
     if not args.no_other_configs:
         del out_bf16, views, ts, plan
