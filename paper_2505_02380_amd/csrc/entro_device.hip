@@ -78,8 +78,12 @@ struct WorkItem {
 
 // The P modes are the byte, fp32 and bf16 outputs of launches whose tensors all hold 4-bit symbols:
 // they decode two symbols per lookup, like the packed output.
+// The M modes are the GEMV of launches with a tensor whose segments are longer than its matrix rows.
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5,
-            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8 };
+            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32M = 9, kModeGemvBF16M = 10 };
+constexpr bool is_gemv(int mode) { return mode == kModeGemvF32 || mode == kModeGemvBF16 || mode == kModeGemvF32M || mode == kModeGemvBF16M; }
+constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32M; }
+constexpr bool gemv_multirow(int mode) { return mode == kModeGemvF32M || mode == kModeGemvBF16M; }
 // the output format of a mode
 constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
@@ -95,6 +99,9 @@ template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, wave
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
 template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
+// eight waves: the row bookkeeping needs more registers than ten waves leave
+template <> struct Cfg<kModeGemvF32M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 128; };
 template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 512; };
 template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 256; };
@@ -716,7 +723,8 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 template <int MODE>
 __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::row> *wms,
                                             uint32_t wave_first) {
-    constexpr bool GEMV = MODE == kModeGemvF32 || MODE == kModeGemvBF16;
+    constexpr bool GEMV = is_gemv(MODE);
+    constexpr bool MROW = gemv_multirow(MODE);           // GEMV whose segments may hold whole matrix rows
     constexpr bool PAIR = kPairMode<MODE>;
     constexpr int SPB = Cfg<MODE>::spb;                   // symbols of a lane per block
     constexpr int ROW = Cfg<MODE>::row;                   // bytes they make in the tile
@@ -775,6 +783,13 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const uint16_t *xvec = t.x;
     float acc_a[64 / RPI], acc_b[64 / RPI];
     uint32_t col0[64 / RPI];
+    // Segments longer than matrix rows (MROW): acc_a is the first row the segment touches, acc_b the
+    // row it is in after that, acc_c what a block adds to the row after that one; col0 then is the
+    // column of the current block's first symbol and moves along.
+    float acc_c[MROW ? 64 / RPI : 1];
+    uint32_t row_first[MROW ? 64 / RPI : 1], rows_done[MROW ? 64 / RPI : 1];   // the segment's first row; row ends passed
+    uint32_t in_first = 0xffu;               // MROW, bit it: still in the first row
+    uint32_t starts_row = 0;                 // MROW, bit it: the segment starts at column 0
     if constexpr (GEMV) {
 #pragma unroll
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
@@ -782,6 +797,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             acc_a[it] = 0.0f;
             acc_b[it] = 0.0f;
             col0[it] = static_cast<uint32_t>((static_cast<uint64_t>(kk) * C) % cols);
+            if constexpr (MROW) {
+                acc_c[it] = 0.0f;
+                starts_row |= (col0[it] == 0 ? 1u : 0u) << it;
+                row_first[it] = static_cast<uint32_t>((static_cast<uint64_t>(kk) * C) / cols);
+                rows_done[it] = 0;
+            }
         }
     }
 
@@ -797,7 +818,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         if constexpr (GEMV) {
 #pragma unroll
             for (uint32_t it = 0; it < 64 / RPI; ++it) {
-                uint32_t col = col0[it] + bs * SPB + (lane % LPR) * PIECE;
+                uint32_t col = col0[it] + (MROW ? 0u : bs * SPB) + (lane % LPR) * PIECE;
                 xsecond[it] = col >= cols;                            // past the row end: next row, from column 0
                 col -= xsecond[it] ? cols : 0u;
                 xblk[it] = *(global_u4_ptr)(xvec + col);
@@ -836,8 +857,39 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                         part = fmaf(static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf, x0, part);
                         part = fmaf(static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf, x1, part);
                     }
-                    acc_a[it] += second ? 0.0f : part;
-                    acc_b[it] += second ? part : 0.0f;
+                    if constexpr (!MROW) {
+                        acc_a[it] += second ? 0.0f : part;
+                        acc_b[it] += second ? part : 0.0f;
+                    } else {
+                        const bool first = (in_first >> it) & 1u;
+                        acc_a[it] += first && !second ? part : 0.0f;
+                        acc_b[it] += first == second ? part : 0.0f;          // first row's successor, or the current row
+                        acc_c[it] += !first && second ? part : 0.0f;
+                    }
+                }
+                if constexpr (MROW) {
+                    // a matrix row ends inside this block (at most one does: cols >= 64)
+                    if (col0[it] + SPB >= cols) {
+                        if (!((in_first >> it) & 1u)) {
+                            // a whole row that lies inside the segment: its eight lanes add up and store it
+                            float a = acc_b[it];
+#pragma unroll
+                            for (uint32_t m = 1; m < LPR; m <<= 1) a += __shfl_xor(a, m, 64);
+                            if (full && piece == 0) {
+                                const uint32_t row = row_first[it] + rows_done[it];
+                                const float y = a * scale;
+                                if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
+                                else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
+                            }
+                            acc_b[it] = acc_c[it];
+                            acc_c[it] = 0.0f;
+                        }
+                        in_first &= ~(1u << it);
+                        rows_done[it] += 1u;
+                        col0[it] = col0[it] + SPB - cols;
+                    } else {
+                        col0[it] += SPB;
+                    }
                 }
             } else {
                 // Store k of the pass writes the bytes [k * LPR * 16, (k + 1) * LPR * 16) of the row's
@@ -934,13 +986,29 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             }
             const uint32_t kk = wave_first + it * RPI + lane / LPR;
             const bool full = kk < n_full;
+            if constexpr (MROW) {
+                if (full && (lane % LPR) == 0) {
+                    // the first row: whole if the segment starts at column 0 and holds its end, else the head
+                    // fragment; what is left of the last row (if it goes on in the next segment): the tail
+                    const bool first = (in_first >> it) & 1u;
+                    if (((starts_row >> it) & 1u) && !first) {
+                        const float y = a * scale;
+                        if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row_first[it]] = y;
+                        else reinterpret_cast<uint16_t *>(t.out)[row_first[it]] = static_cast<uint16_t>(bf16_bits(y));
+                    } else {
+                        t.partials[2 * static_cast<uint64_t>(kk)] = a;
+                    }
+                    if (!first && col0[it] != 0) t.partials[2 * static_cast<uint64_t>(kk) + 1] = b;
+                }
+                continue;
+            }
             if (full && (lane % LPR) == 0) {
                 if (t.need_fix) {                                   // row fragments: summed by the second stage
                     t.partials[2 * static_cast<uint64_t>(kk)] = a;
                     t.partials[2 * static_cast<uint64_t>(kk) + 1] = b;
                 } else {                                            // segment == row
                     const float y = a * scale;
-                    if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[kk] = y;
+                    if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[kk] = y;
                     else reinterpret_cast<uint16_t *>(t.out)[kk] = static_cast<uint16_t>(bf16_bits(y));
                 }
             }
@@ -987,7 +1055,7 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
                 head = acc;                              // row began in an earlier segment
             } else {
                 const float y = acc * t.scale;
-                if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[row] = y;
+                if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
                 else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
             }
             first_fragment = false;
@@ -1015,7 +1083,8 @@ template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<M
 template <int MODE>
 __device__ __forceinline__ bool rows_fit(const DevTensor &t) {
     if (t.chunk_symbols % Cfg<MODE>::spb != 0) return false;
-    if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) return t.cols % 8 == 0 && t.cols >= t.chunk_symbols;
+    if constexpr (gemv_multirow(MODE)) return t.cols % 8 == 0 && t.cols >= 64;
+    if constexpr (is_gemv(MODE)) return t.cols % 8 == 0 && t.cols >= t.chunk_symbols;
     return true;
 }
 
@@ -1025,7 +1094,7 @@ template <int MODE>
 __device__ __forceinline__ void scalar_chunks(const DevTensor &t, const Tables &tb, uint32_t first, uint32_t end) {
     constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     for (uint32_t k = first + threadIdx.x; k < end; k += WG) {
-        if constexpr (MODE == kModeGemvF32 || MODE == kModeGemvBF16) {
+        if constexpr (is_gemv(MODE)) {
             gemv_segment<MODE>(t, tb, k);
         } else {
             const uint64_t left = t.n - static_cast<uint64_t>(k) * t.chunk_symbols;
@@ -1114,7 +1183,7 @@ __device__ __forceinline__ void fix_row(const DevTensor &t, uint32_t row) {
         acc += t.partials[2 * static_cast<uint64_t>(k) + (first_row == row ? 0 : 1)];
     }
     const float y = acc * t.scale;
-    if (MODE == kModeGemvF32) reinterpret_cast<float *>(t.out)[row] = y;
+    if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
     else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
 }
 
@@ -1217,6 +1286,8 @@ void dispatch_mode(int mode, F f) {
         case kModeU8P: f(std::integral_constant<int, kModeU8P>{}); break;
         case kModeF32P: f(std::integral_constant<int, kModeF32P>{}); break;
         case kModeBF16P: f(std::integral_constant<int, kModeBF16P>{}); break;
+        case kModeGemvF32M: f(std::integral_constant<int, kModeGemvF32M>{}); break;
+        case kModeGemvBF16M: f(std::integral_constant<int, kModeGemvBF16M>{}); break;
         default: f(std::integral_constant<int, kModeGemvBF16>{}); break;
     }
 }
@@ -1229,8 +1300,12 @@ unsigned wg_of(int mode) {
 }
 
 // `pairs`: every tensor of the launch holds 4-bit symbols, so the tables can hold two codes per entry.
-int mode_of(entro_op op, entro_dtype d, bool pairs) {
-    if (op == ENTRO_OP_GEMV) return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
+// `multirow`: GEMV with a tensor whose segments are longer than its matrix rows.
+int mode_of(entro_op op, entro_dtype d, bool pairs, bool multirow) {
+    if (op == ENTRO_OP_GEMV) {
+        if (multirow) return d == ENTRO_F32 ? kModeGemvF32M : kModeGemvBF16M;
+        return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
+    }
     switch (d) {
         case ENTRO_U8: return pairs ? kModeU8P : kModeU8;
         case ENTRO_U4_PACKED: return kModeU4;
@@ -1266,7 +1341,7 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     if (st != ENTRO_OK) return st;
     dt.partials = partials;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int mode = mode_of(op, d, dt.bits == 4);
+    const int mode = mode_of(op, d, dt.bits == 4, dt.cols < dt.chunk_symbols);
     const unsigned wg = wg_of(mode);
     // a unit per wavefront when the tensor is large; fewer units per workgroup, down to one, when
     // that would leave compute units without a workgroup
@@ -1281,7 +1356,7 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
         const unsigned g2 = (dt.rows + kFixWG - 1) / kFixWG;
-        if (mode == kModeGemvF32) hipLaunchKernelGGL(k_fix_single<kModeGemvF32>, dim3(g2), dim3(kFixWG), 0, s, dt);
+        if (gemv_f32(mode)) hipLaunchKernelGGL(k_fix_single<kModeGemvF32>, dim3(g2), dim3(kFixWG), 0, s, dt);
         else hipLaunchKernelGGL(k_fix_single<kModeGemvBF16>, dim3(g2), dim3(kFixWG), 0, s, dt);
         if (!hip_ok(hipGetLastError(), "launch row-sum kernel")) return ENTRO_ERR_DEVICE;
     }
@@ -1373,12 +1448,14 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     WorkItem *fix = reinterpret_cast<WorkItem *>(host.data() + L.off_fix);
     uint64_t n_items = 0, n_fix = 0, partial_floats = 0, total_units = 0;
     bool pairs = true;                                       // every tensor 4-bit: two codes per table entry
+    bool multirow = false;                                   // GEMV: a tensor's segments are longer than its rows
     float *partials_base = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + L.off_partials);
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, &dts[i]);
         if (st != ENTRO_OK) return st;
         total_units += (dts[i].n_chunks + kUnit - 1) / kUnit;
         pairs = pairs && dts[i].bits == 4;
+        multirow = multirow || (op == ENTRO_OP_GEMV && dts[i].cols < dts[i].chunk_symbols);
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
@@ -1387,7 +1464,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     }
     // A work item is what a workgroup takes in one round when the launch is large (a unit per
     // wavefront), and less when the launch would not give every compute unit an item otherwise.
-    const int mode = mode_of(op, out_type, pairs);
+    const int mode = mode_of(op, out_type, pairs, multirow);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const uint64_t waves = wg_of(mode) / 64u;
@@ -1408,7 +1485,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     plan->n_fix = L.n_fix;
     plan->item_units = item_units;
     plan->pair_tables = pairs ? 1u : 0u;
-    plan->reserved = 0;
+    plan->gemv_multirow = multirow ? 1u : 0u;
     plan->off_tensors = L.off_tensors;
     plan->off_items = L.off_items;
     plan->off_partials = L.off_partials;
@@ -1424,7 +1501,8 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const DevTensor *dts = reinterpret_cast<const DevTensor *>(ws + plan->off_tensors);
     const WorkItem *items = reinterpret_cast<const WorkItem *>(ws + plan->off_items);
     const WorkItem *fix = reinterpret_cast<const WorkItem *>(ws + plan->off_fix);
-    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0);
+    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0,
+                             plan->gemv_multirow != 0);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const unsigned grid = plan->n_items < slots ? plan->n_items : slots;
@@ -1434,7 +1512,7 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     });
     if (!hip_ok(hipGetLastError(), "launch batched decode kernel")) return ENTRO_ERR_DEVICE;
     if (plan->n_fix) {
-        if (mode == kModeGemvF32) hipLaunchKernelGGL(k_fix_batch<kModeGemvF32>, dim3(plan->n_fix), dim3(kFixWG), 0, s, dts, fix);
+        if (gemv_f32(mode)) hipLaunchKernelGGL(k_fix_batch<kModeGemvF32>, dim3(plan->n_fix), dim3(kFixWG), 0, s, dts, fix);
         else hipLaunchKernelGGL(k_fix_batch<kModeGemvBF16>, dim3(plan->n_fix), dim3(kFixWG), 0, s, dts, fix);
         if (!hip_ok(hipGetLastError(), "launch batched row-sum kernel")) return ENTRO_ERR_DEVICE;
     }

@@ -313,6 +313,11 @@ def test_dequant_ragged_and_unsigned_and_offgrid_zero_point():
     (77, 300, 4096),         # rows do not divide segments
     (5, 9000, 1024),         # long rows, ragged last segment
     (1, 100, 4096),          # a single short row
+    (512, 128, 1024),        # eight whole rows per segment
+    (300, 192, 1024),        # five and a third rows per segment
+    (160, 3072, 8192),       # the phi3 shapes: two and two thirds rows per segment
+    (4096 + 11, 64, 4096),   # the shortest rows the row path takes: one per block; ragged last segment
+    (100, 72, 512),          # a block may hold the end of one row and the start of the next
 ])
 @pytest.mark.parametrize("batch", [False, True])
 def test_gemv_against_fp64_oracle(rows, cols, chunk, batch):
