@@ -408,6 +408,55 @@ def test_launch_with_a_few_units_per_work_item():
         _assert_gemv_close(y.cpu().numpy().astype(np.float64), y_ref)
 
 
+def test_random_shapes_all_outputs():
+    """Seeded sweep over sizes, segment lengths, alphabets and code-length profiles, every output type,
+    single and batched: bit-exact integers and fp32, bf16 within 1 ulp, GEMV within 1e-3."""
+    rng = np.random.default_rng(2025)
+    chunks8 = [1, 64, 128, 192, 256, 1000, 1024, 4096, 8192]
+    for case in range(150):
+        bits = 4 if case % 3 == 0 else 8
+        A = 1 << bits
+        chunk = int(rng.choice(chunks8))
+        if bits == 4 and chunk % 2:
+            chunk += 1
+        n = int(rng.integers(1, 40 * chunk + 2)) if chunk > 64 else int(rng.integers(1, 5000))
+        if case % 2:                                             # a matrix shape, for the GEMV below
+            cols = int(rng.choice([8192, 4096, 3072, 1024, 192, 72, 64, 40, 7]))
+            n = cols * max(1, n // cols)
+        kind = case % 4
+        if kind == 0:
+            sym = np.minimum(rng.geometric(rng.uniform(0.05, 0.7), n) - 1, A - 1)
+        elif kind == 1:
+            sym = rng.integers(0, A, n)
+        elif kind == 2:
+            sym = np.where(rng.random(n) < 0.97, rng.integers(0, 3, n), rng.integers(0, A, n))   # rare long codes
+        else:
+            sym = np.full(n, int(rng.integers(0, A)))
+            sym[rng.integers(0, n, max(1, n // 50))] = int(rng.integers(0, A))
+        sym = sym.astype(np.uint8)
+        z = int(rng.integers(-3, A + 3))
+        enc = _oracle_encoded(sym, bits, chunk, s=np.float32(rng.uniform(1e-3, 1.0)), z=z)
+        tag = (case, bits, chunk, n, kind)
+        batch = bool(case & 1)
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch), sym), tag
+        if bits == 4:
+            assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED, not batch), oracle.pack_u4(sym)), tag
+        f = _gpu_dequant(enc, E.ENTRO_F32, not batch)
+        assert np.array_equal(f.view(np.uint32), oracle.dequant_f32(sym, enc.qp.scale, z).view(np.uint32)), tag
+        b = _gpu_dequant(enc, E.ENTRO_BF16, batch)
+        assert _bf16_ulp_diff(b, oracle.dequant_bf16(sym, enc.qp.scale, z)).max() <= 1, tag
+        # a matrix shape for the same symbols, if n factors conveniently
+        for cols in (8192, 4096, 3072, 1024, 192, 72, 64, 40, 7):
+            if n % cols == 0:
+                rows = n // cols
+                encg = _oracle_encoded(sym, bits, chunk, rows=rows, cols=cols, s=enc.qp.scale, z=z)
+                xb = synth.make_x_bf16(case, 0, cols)
+                y_ref, _ = oracle.gemv(sym, rows, cols, enc.qp.scale, z, xb)
+                if np.linalg.norm(y_ref) > 0:
+                    _assert_gemv_close(_gpu_gemv(encg, xb, E.ENTRO_F32, batch), y_ref)
+                break
+
+
 def test_mistral_layer_launch_shape_sampled_against_oracle():
     """Four mistral-7B-shaped layers in the batched launch bench.py uses (more work items than the chip
     holds workgroups, so workgroups walk several items and tensors); sampled segments vs the oracle."""
