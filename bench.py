@@ -142,6 +142,15 @@ def main():
         checked += 1
     log(f"{checked} sampled segments match the oracle")
 
+    # ------------------------- what this GPU's memory takes of a plain stream with the same read/write mix
+    rb = (stream_bytes + offset_bytes + 15) // 16 * 16
+    probe_src = torch.zeros(rb, dtype=torch.uint8, device=dev)
+    probe_scratch = torch.zeros(16, dtype=torch.uint8, device=dev)
+    wp, kp = timed(lambda: E.entro_stream_probe(probe_src, rb, out_bf16, out_bytes, probe_scratch), args.steps, args.warmup)
+    ceiling = (rb + out_bytes) / (kp * 1e-3) / 1e9
+    log(f"stream probe with the same byte counts: {kp:.3f} ms, {ceiling:.0f} GB/s")
+    del probe_src
+
     result = {
         "metric": "decoded weights GB/s (entro_decode_dequant -> bf16, mistral-7B-shaped 8-bit set)",
         "value": round(decoded_gbps, 2),
@@ -169,6 +178,10 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": round(kern_ms, 4),
                      "traffic": measured_traffic() if args.layers == 32 else None},
+        # a coalesced kernel that reads and writes the same byte counts, reads and writes interleaved in
+        # their ratio: the rate memory takes a plain stream of this mix at, and the launch against it
+        "stream_ceiling": {"GBps": round(ceiling, 1), "kernel_ms": round(kp, 4), "frac_of_peak": round(ceiling / HBM_PEAK_GBPS, 4),
+                           "launch_frac_of_ceiling": round(achieved / ceiling, 4)},
     }
 
     # ------------------------------------------------------------ extra legs: u8 and GEMV

@@ -242,6 +242,15 @@ entro_status entro_decode_dequant_batch(const entro_tensor *ts, uint32_t count, 
 entro_status entro_decode_gemv_batch(const entro_tensor *ts, uint32_t count, entro_dtype y_type,
                                      void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
+/* Calibration for the roofline figures, not part of the path: one kernel that reads
+ * read_bytes from src and writes write_bytes to dst (device pointers, 16-byte
+ * aligned, sizes multiples of 16), perfectly coalesced, reads and writes interleaved
+ * in the ratio of the two sizes.  Timed by the caller, it gives the rate at which
+ * this GPU's memory takes a plain stream with a decode launch's read/write mix.
+ * scratch4: four bytes of device memory the kernel may write. */
+entro_status entro_stream_probe(const void *src, uint64_t read_bytes, void *dst, uint64_t write_bytes, void *scratch4,
+                                void *hip_stream);
+
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char *entro_last_device_error(void);
 

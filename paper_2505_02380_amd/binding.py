@@ -101,6 +101,7 @@ def lib():
         "entro_decode_dequant_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_decode_gemv_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_last_device_error": (C.c_char_p, []),
+        "entro_stream_probe": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -115,7 +116,8 @@ EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_count
             "entro_check_offsets", "entro_bits_saved", "entro_theoretical_speedup", "entro_status_string",
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
-            "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error"]
+            "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
+            "entro_stream_probe"]
 
 
 def _ptr(a: np.ndarray, t):
@@ -341,6 +343,12 @@ def _batch(fn_name: str, ts, out_type, workspace, stream):
     fn = getattr(lib(), fn_name)
     _check(fn(arr, len(ts), out_type, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
               _stream_ptr(stream)), fn_name)
+
+
+def entro_stream_probe(src, read_bytes: int, dst, write_bytes: int, scratch, stream=None):
+    """Calibration kernel: read read_bytes of src, write write_bytes of dst (torch device tensors)."""
+    _check(lib().entro_stream_probe(src.data_ptr(), int(read_bytes), dst.data_ptr(), int(write_bytes), scratch.data_ptr(),
+                                    _stream_ptr(stream)), "entro_stream_probe")
 
 
 def entro_decode_batch(ts, out_type, workspace, stream=None):
