@@ -80,10 +80,11 @@ struct WorkItem {
 // they decode two symbols per lookup, like the packed output.
 // The M modes are the GEMV of launches with a tensor whose segments are longer than its matrix rows.
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5,
-            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32M = 9, kModeGemvBF16M = 10 };
-constexpr bool is_gemv(int mode) { return mode == kModeGemvF32 || mode == kModeGemvBF16 || mode == kModeGemvF32M || mode == kModeGemvBF16M; }
-constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32M; }
-constexpr bool gemv_multirow(int mode) { return mode == kModeGemvF32M || mode == kModeGemvBF16M; }
+            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32M = 9, kModeGemvBF16M = 10,
+            kModeGemvF32MP = 11, kModeGemvBF16MP = 12 };       // MP: the M kernel with two 4-bit symbols per lookup
+constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32M || mode == kModeGemvF32MP; }
+constexpr bool is_gemv(int mode) { return gemv_f32(mode) || mode == kModeGemvBF16 || mode == kModeGemvBF16M || mode == kModeGemvBF16MP; }
+constexpr bool gemv_multirow(int mode) { return is_gemv(mode) && mode != kModeGemvF32 && mode != kModeGemvBF16; }
 // the output format of a mode
 constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
@@ -102,11 +103,14 @@ template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64,
 // eight waves: the row bookkeeping needs more registers than ten waves leave
 template <> struct Cfg<kModeGemvF32M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32MP> { static constexpr int spb = 128, row = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16MP> { static constexpr int spb = 128, row = 64, waves = 8, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 128; };
 template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 512; };
 template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 256; };
 // Packed 4-bit output decodes two symbols per lookup, and so do the P modes.
-template <int MODE> constexpr bool kPairMode = MODE == kModeU4 || MODE == kModeU8P || MODE == kModeF32P || MODE == kModeBF16P;
+template <int MODE> constexpr bool kPairMode = MODE == kModeU4 || MODE == kModeU8P || MODE == kModeF32P || MODE == kModeBF16P ||
+                                               MODE == kModeGemvF32MP || MODE == kModeGemvBF16MP;
 
 // Lookup tables of one workgroup (LDS).
 // Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
@@ -185,6 +189,19 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
 __device__ __forceinline__ uint32_t pack_entry(uint32_t sym, uint32_t len) { return len | (sym << 8); }
 __device__ __forceinline__ uint32_t entry_len(uint32_t e) { return e & 0x3fu; }
 __device__ __forceinline__ uint32_t entry_sym(uint32_t e) { return e >> 8; }
+
+// sum over eight symbols (one per byte of d0, d1) of (q - z) * x, x being eight bf16 values.
+__device__ __forceinline__ float dot8(uint32_t d0, uint32_t d1, const u32x4 xv, float zf, float part) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t xa = j < 2 ? xv.x : xv.y, xb = j < 2 ? xv.z : xv.w;
+        const float x0 = __uint_as_float((j & 1) ? (xa & 0xffff0000u) : (xa << 16));
+        const float x1 = __uint_as_float((j & 1) ? (xb & 0xffff0000u) : (xb << 16));
+        part = fmaf(static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf, x0, part);
+        part = fmaf(static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf, x1, part);
+    }
+    return part;
+}
 
 // The eight 4-bit symbols of four pair bytes, one per byte, in order.
 __device__ __forceinline__ void unpack_nibbles(uint32_t d, uint32_t &lo, uint32_t &hi) {
@@ -736,7 +753,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     constexpr int TRIPS = ROW / (kGroup * kTripGroups);
     static_assert(ROW % (kGroup * kTripGroups) == 0, "a row is a whole number of trips");
     static_assert(SPB == (PAIR ? 2 : 1) * ROW, "one tile byte per lookup");
-    static_assert(!GEMV || SPB == ROW, "the GEMV indexes columns by tile bytes");
+    constexpr uint32_t SYM_PIECE = PIECE * (PAIR ? 2u : 1u);   // symbols of a lane's piece
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     WaveMem<ROW> &wm = wms[wave];
@@ -813,15 +830,16 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     for (uint32_t bs = 0; bs < wave_blocks; ++bs) {
         // GEMV: ask for the block's activations now, so that they arrive while the symbols are decoded
         // (eight bf16 per pass; always inside x: columns come in pieces of eight and cols % 8 == 0)
-        u32x4 xblk[GEMV ? 64 / RPI : 1];
+        u32x4 xblk[GEMV ? 64 / RPI : 1][PAIR ? 2 : 1];
         bool xsecond[GEMV ? 64 / RPI : 1];
         if constexpr (GEMV) {
 #pragma unroll
             for (uint32_t it = 0; it < 64 / RPI; ++it) {
-                uint32_t col = col0[it] + (MROW ? 0u : bs * SPB) + (lane % LPR) * PIECE;
+                uint32_t col = col0[it] + (MROW ? 0u : bs * SPB) + (lane % LPR) * SYM_PIECE;
                 xsecond[it] = col >= cols;                            // past the row end: next row, from column 0
                 col -= xsecond[it] ? cols : 0u;
-                xblk[it] = *(global_u4_ptr)(xvec + col);
+                xblk[it][0] = *(global_u4_ptr)(xvec + col);
+                if constexpr (PAIR) xblk[it][1] = *(global_u4_ptr)(xvec + col + 8u);
             }
         }
 #pragma unroll 1
@@ -847,15 +865,16 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
                 const uint32_t d0 = tile[WaveMem<ROW>::tile_at(rr, piece * 2u)], d1 = tile[WaveMem<ROW>::tile_at(rr, piece * 2u + 1u)];
                 if (full) {
                     const bool second = xsecond[it];
-                    const u32x4 xv = xblk[it];
-                    float part = 0.0f;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const uint32_t xa = j < 2 ? xv.x : xv.y, xb = j < 2 ? xv.z : xv.w;
-                        const float x0 = __uint_as_float((j & 1) ? (xa & 0xffff0000u) : (xa << 16));
-                        const float x1 = __uint_as_float((j & 1) ? (xb & 0xffff0000u) : (xb << 16));
-                        part = fmaf(static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf, x0, part);
-                        part = fmaf(static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf, x1, part);
+                    float part;
+                    if constexpr (PAIR) {
+                        // eight pair bytes: sixteen symbols against sixteen activations
+                        uint32_t a0, a1, b0, b1;
+                        unpack_nibbles(d0, a0, a1);
+                        unpack_nibbles(d1, b0, b1);
+                        part = dot8(a0, a1, xblk[it][0], zf, 0.0f);
+                        part = dot8(b0, b1, xblk[it][1], zf, part);
+                    } else {
+                        part = dot8(d0, d1, xblk[it][0], zf, 0.0f);
                     }
                     if constexpr (!MROW) {
                         acc_a[it] += second ? 0.0f : part;
@@ -1047,7 +1066,7 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     float head = 0.0f, tail = 0.0f;
     for (uint32_t i = 0; i < nsym; ++i) {
         if (i % kScalarProbes == 0) r.buf = load_bits(r.stream, r.pos, r.last_off);
-        const uint32_t sym = entry_sym(next_entry<false>(r, tb, max_len));
+        const uint32_t sym = entry_sym(next_entry<kPairMode<MODE>>(r, tb, max_len));
         const float xv = __uint_as_float(static_cast<uint32_t>(t.x[col]) << 16);
         acc = fmaf(static_cast<float>(static_cast<int32_t>(sym) - z), xv, acc);
         if (++col == cols) {
@@ -1083,6 +1102,7 @@ template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<M
 template <int MODE>
 __device__ __forceinline__ bool rows_fit(const DevTensor &t) {
     if (t.chunk_symbols % Cfg<MODE>::spb != 0) return false;
+    if constexpr (kPairMode<MODE> && is_gemv(MODE)) return t.cols % 16 == 0 && t.cols >= 128;
     if constexpr (gemv_multirow(MODE)) return t.cols % 8 == 0 && t.cols >= 64;
     if constexpr (is_gemv(MODE)) return t.cols % 8 == 0 && t.cols >= t.chunk_symbols;
     return true;
@@ -1288,6 +1308,8 @@ void dispatch_mode(int mode, F f) {
         case kModeBF16P: f(std::integral_constant<int, kModeBF16P>{}); break;
         case kModeGemvF32M: f(std::integral_constant<int, kModeGemvF32M>{}); break;
         case kModeGemvBF16M: f(std::integral_constant<int, kModeGemvBF16M>{}); break;
+        case kModeGemvF32MP: f(std::integral_constant<int, kModeGemvF32MP>{}); break;
+        case kModeGemvBF16MP: f(std::integral_constant<int, kModeGemvBF16MP>{}); break;
         default: f(std::integral_constant<int, kModeGemvBF16>{}); break;
     }
 }
@@ -1303,6 +1325,7 @@ unsigned wg_of(int mode) {
 // `multirow`: GEMV with a tensor whose segments are longer than its matrix rows.
 int mode_of(entro_op op, entro_dtype d, bool pairs, bool multirow) {
     if (op == ENTRO_OP_GEMV) {
+        if (pairs) return d == ENTRO_F32 ? kModeGemvF32MP : kModeGemvBF16MP;
         if (multirow) return d == ENTRO_F32 ? kModeGemvF32M : kModeGemvBF16M;
         return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
     }

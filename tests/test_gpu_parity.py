@@ -332,6 +332,26 @@ def test_gemv_against_fp64_oracle(rows, cols, chunk, batch):
     assert np.all(np.abs(y_bf - y_ref) <= 2.0 ** -7 * np.abs(y_ref) + 1e-3 * np.sqrt(np.mean(y_ref ** 2)))
 
 
+@pytest.mark.parametrize("rows,cols,chunk", [
+    (160, 3072, 8192),       # phi3 shapes: two and two thirds rows per segment
+    (64, 8192, 8192),        # one row per segment
+    (96, 4096, 1024),        # four segments per row
+    (520, 128, 4096),        # the shortest rows the pair kernel takes
+    (33, 144, 256),          # rows and blocks out of step
+    (50, 200, 512),          # cols not a multiple of 16: element by element, with the pair tables
+])
+@pytest.mark.parametrize("batch", [False, True])
+def test_gemv_4bit_two_symbols_per_lookup(rows, cols, chunk, batch):
+    rng = np.random.default_rng(rows + cols)
+    sym = np.minimum(rng.geometric(0.45, rows * cols) - 1, 15).astype(np.uint8)
+    sym[rng.random(sym.size) < 0.01] = 15                      # some long codes
+    enc = _oracle_encoded(sym, 4, chunk, rows=rows, cols=cols, s=np.float32(0.07), z=6)
+    xb = synth.make_x_bf16(1, rows % 4, cols)
+    y_ref, _ = oracle.gemv(sym, rows, cols, enc.qp.scale, 6, xb)
+    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), y_ref)
+    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_BF16, batch), y_ref, tol=8e-3)   # y itself rounded to bf16
+
+
 def test_gemv_unit_vector_picks_a_column_exactly():
     rows, cols = 64, 4096
     rng = np.random.default_rng(1)
