@@ -486,7 +486,7 @@ def main():
     # -------------------------------------------------------------- oracle on the host cores
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
-        budget_syms = 400_000_000
+        budget_syms = 1_500_000_000      # about 15 s of one core
         t_cpu, syms = 0.0, 0
         sample = []
         for e in encs:

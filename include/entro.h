@@ -242,6 +242,56 @@ entro_status entro_decode_dequant_batch(const entro_tensor *ts, uint32_t count, 
 entro_status entro_decode_gemv_batch(const entro_tensor *ts, uint32_t count, entro_dtype y_type,
                                      void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------ device side: compression
+ * The steps before the decode path for weights that already sit in device
+ * memory: the three that touch every weight (range, Eq. 1's grid map with the
+ * symbol counts of "Huffman weight encoding", the segment-parallel writing of
+ * the stream, Fig. 3) run as kernels; the two that touch 2^bits numbers
+ * (entro_qparams_from_range, entro_codebook_from_counts) are host calls between
+ * them, on values the caller copies back.  Results are those of entro_quantize
+ * and entro_encode, bit for bit.  All calls only enqueue work on hip_stream. */
+
+/* range16 (device, 16 bytes, 16-byte aligned) receives { float min, float max,
+ * uint32 nonfinite (1 if a NaN or Inf occurs, NaNs do not enter min / max),
+ * uint32 0 } of w (device, n floats, 16-byte aligned). */
+entro_status entro_range_device(const float *w, uint64_t n, void *range16, void *hip_stream);
+
+/* Host: Eq. 1's scale and zero-point from a tensor's range (the formulas given
+ * with entro_quantize).  ENTRO_ERR_NONFINITE if `nonfinite` is set or a bound is
+ * not finite, ENTRO_ERR_RANGE for a negative minimum under the unsigned scheme
+ * or an empty range. */
+entro_status entro_qparams_from_range(float min, float max, uint32_t nonfinite, int bits, entro_scheme scheme,
+                                      entro_qparams *qp);
+
+/* q[i] = clamp(rint(w[i] / s) + z, 0, 2^bits - 1), one symbol per byte, and the
+ * histogram of the symbols.  w: device, n floats; q: device, n bytes; counts:
+ * device, 256 entries, overwritten (entries at and above 2^bits end up 0); all
+ * 16-byte aligned.  qp: host.  ENTRO_ERR_RANGE if |zero_point| > 2^24 (the
+ * decoders take no such tensor either).  A NaN weight, which entro_range_device
+ * reports, quantises to clamp(z). */
+entro_status entro_quantize_device(const float *w, uint64_t n, const entro_qparams *qp, uint8_t *q, uint64_t *counts,
+                                   void *hip_stream);
+
+/* Host: exact size in bytes (padding included) of the stream that symbols with
+ * this histogram make under this codebook; 0 if a counted symbol has no code. */
+uint64_t entro_encoded_bytes(const uint64_t *counts, const entro_codebook *cb);
+
+/* Encode q (device, n symbols one per byte) into stream (device, stream_cap
+ * bytes, a multiple of 16) and fill offsets (device, entro_num_chunks + 1
+ * entries), in the format described at the top; the padded size is
+ * entro_encoded_bytes, or follows from offsets[n_chunks].  cb: host.
+ * chunk_symbols <= 2^20.  What can only be seen on the device is reported in
+ * *status (device, 4 bytes, written by the call): 0 if the stream was written,
+ * otherwise nothing was written to `stream`; pass the value, once copied back,
+ * to entro_encode_device_status. */
+entro_status entro_encode_device(const uint8_t *q, uint64_t n, const entro_codebook *cb, uint32_t chunk_symbols, void *stream,
+                                 uint64_t stream_cap, uint64_t *offsets, uint32_t *status, void *hip_stream);
+
+/* Host: the meaning of a status word of entro_encode_device: ENTRO_OK,
+ * ENTRO_ERR_SYMBOL (a symbol without a code), ENTRO_ERR_CAPACITY (stream_cap too
+ * small), ENTRO_ERR_SIZE (the stream would reach 4 GiB). */
+entro_status entro_encode_device_status(uint32_t status_word);
+
 /* Calibration for the roofline figures, not part of the path: one kernel that reads
  * read_bytes from src and writes write_bytes to dst (device pointers, 16-byte
  * aligned, sizes multiples of 16), perfectly coalesced, reads and writes interleaved

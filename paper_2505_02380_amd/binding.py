@@ -102,6 +102,13 @@ def lib():
         "entro_decode_gemv_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_last_device_error": (C.c_char_p, []),
         "entro_stream_probe": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+        "entro_range_device": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+        "entro_qparams_from_range": (C.c_int, [C.c_float, C.c_float, C.c_uint32, C.c_int, C.c_int, C.POINTER(QParams)]),
+        "entro_quantize_device": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(QParams), C.c_void_p, C.c_void_p, C.c_void_p]),
+        "entro_encoded_bytes": (C.c_uint64, [u64p, cbp]),
+        "entro_encode_device": (C.c_int, [C.c_void_p, C.c_uint64, cbp, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]),
+        "entro_encode_device_status": (C.c_int, [C.c_uint32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -117,7 +124,8 @@ EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_count
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
-            "entro_stream_probe"]
+            "entro_stream_probe", "entro_range_device", "entro_qparams_from_range", "entro_quantize_device",
+            "entro_encoded_bytes", "entro_encode_device", "entro_encode_device_status"]
 
 
 def _ptr(a: np.ndarray, t):
@@ -260,11 +268,12 @@ def encode_tensor(w: np.ndarray, bits: int, scheme: int, chunk_symbols: int, row
 class DeviceTensor:
     """Device copies of one encoded tensor plus its output buffer (torch owns the memory)."""
 
-    def __init__(self, enc: EncodedTensor, device="cuda"):
+    def __init__(self, enc: EncodedTensor, device="cuda", stream=None, offsets=None):
         import torch
         self.enc = enc
-        self.stream = torch.from_numpy(enc.stream).to(device)
-        self.offsets = torch.from_numpy(enc.offsets.view(np.int64)).to(device)
+        # stream / offsets given: the tensor was encoded on the device and enc holds no host copy of them
+        self.stream = torch.from_numpy(enc.stream).to(device) if stream is None else stream
+        self.offsets = torch.from_numpy(enc.offsets.view(np.int64)).to(device) if offsets is None else offsets
         self.x = None
         self.out = None
 
@@ -272,7 +281,7 @@ class DeviceTensor:
         e = self.enc
         t = CTensor()
         t.stream = self.stream.data_ptr()
-        t.stream_bytes = e.stream.size
+        t.stream_bytes = self.stream.numel()
         t.offsets = self.offsets.data_ptr()
         t.n = e.n
         t.chunk_symbols = e.chunk_symbols
@@ -349,6 +358,72 @@ def entro_stream_probe(src, read_bytes: int, dst, write_bytes: int, scratch, str
     """Calibration kernel: read read_bytes of src, write write_bytes of dst (torch device tensors)."""
     _check(lib().entro_stream_probe(src.data_ptr(), int(read_bytes), dst.data_ptr(), int(write_bytes), scratch.data_ptr(),
                                     _stream_ptr(stream)), "entro_stream_probe")
+
+
+# ------------------------------------------------------- device-side compression
+def entro_range_device(w, range16, stream=None):
+    """min / max / non-finite flag of w (torch float32 device tensor) into range16 (16 bytes of device memory)."""
+    _check(lib().entro_range_device(w.data_ptr(), w.numel(), range16.data_ptr(), _stream_ptr(stream)), "entro_range_device")
+
+
+def entro_qparams_from_range(mn: float, mx: float, nonfinite: int, bits: int, scheme: int) -> QParams:
+    qp = QParams()
+    _check(lib().entro_qparams_from_range(mn, mx, nonfinite, bits, scheme, C.byref(qp)), "entro_qparams_from_range")
+    return qp
+
+
+def entro_quantize_device(w, qp: QParams, q, counts, stream=None):
+    """q (uint8 device tensor, w.numel() bytes) and counts (int64 device tensor of 256) from w and qp."""
+    _check(lib().entro_quantize_device(w.data_ptr(), w.numel(), C.byref(qp), q.data_ptr(), counts.data_ptr(),
+                                       _stream_ptr(stream)), "entro_quantize_device")
+
+
+def entro_encoded_bytes(counts: np.ndarray, cb: Codebook) -> int:
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    return int(lib().entro_encoded_bytes(_ptr(counts, C.c_uint64), C.byref(cb)))
+
+
+def entro_encode_device(q, cb: Codebook, chunk_symbols: int, stream_out, offsets, status, stream=None):
+    """Encode q (uint8 device tensor) into stream_out / offsets (device tensors); status: 4 bytes of device memory."""
+    _check(lib().entro_encode_device(q.data_ptr(), q.numel(), C.byref(cb), chunk_symbols, stream_out.data_ptr(),
+                                     stream_out.numel() * stream_out.element_size(), offsets.data_ptr(), status.data_ptr(),
+                                     _stream_ptr(stream)), "entro_encode_device")
+
+
+def entro_encode_device_status(word: int) -> int:
+    return int(lib().entro_encode_device_status(int(word) & 0xFFFFFFFF))
+
+
+def compress_on_device(w, bits: int, scheme: int, chunk_symbols: int, rows: int = 0, cols: int = 0, name: str = "",
+                       max_len: int = 0, return_q: bool = False):
+    """Range -> (s, z) -> quantise + count -> codebook -> encode for a float32 tensor that lives on the GPU.
+
+    The three passes over the weights are kernels; the two small steps between them run in the host
+    library on the 16 and 2048 bytes copied back.  Returns a DeviceTensor ready for the decode calls.
+    """
+    import torch
+    w = w.reshape(-1)
+    dev = w.device
+    small = torch.empty(4 + 1, dtype=torch.int32, device=dev)          # range (16 bytes) and the encoder's status word
+    counts = torch.empty(256, dtype=torch.int64, device=dev)
+    entro_range_device(w, small)
+    r = small[:4].cpu().numpy()
+    mn, mx = r[:2].view(np.float32)
+    qp = entro_qparams_from_range(float(mn), float(mx), int(r[2]), bits, scheme)
+    q = torch.empty(w.numel(), dtype=torch.uint8, device=dev)
+    entro_quantize_device(w, qp, q, counts)
+    cnt = counts.cpu().numpy().view(np.uint64)
+    cb = (entro_codebook_from_counts_limited(cnt[: 1 << bits], bits, max_len) if max_len
+          else entro_codebook_from_counts(cnt[: 1 << bits], bits))
+    nbytes = entro_encoded_bytes(cnt, cb)
+    stream_out = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    offsets = torch.empty(entro_num_chunks(w.numel(), chunk_symbols) + 1, dtype=torch.int64, device=dev)
+    status = small[4:]
+    entro_encode_device(q, cb, chunk_symbols, stream_out, offsets, status)
+    _check(entro_encode_device_status(int(status.cpu()[0])), "entro_encode_device (status word)")
+    enc = EncodedTensor(None, None, w.numel(), chunk_symbols, cb, qp, rows, cols, name)
+    dt = DeviceTensor(enc, dev, stream=stream_out, offsets=offsets)
+    return (dt, q) if return_q else dt
 
 
 def entro_decode_batch(ts, out_type, workspace, stream=None):

@@ -18,7 +18,7 @@ DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang"
 
 def sources():
     return [os.path.join(CSRC, "entro_host.cpp"), os.path.join(CSRC, "entro_device.hip"),
-            os.path.join(INCLUDE, "entro.h")]
+            os.path.join(CSRC, "entro_compress.hip"), os.path.join(INCLUDE, "entro.h")]
 
 
 def up_to_date() -> bool:
@@ -31,11 +31,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(BUILD, exist_ok=True)
     host_o = os.path.join(BUILD, "entro_host.o")
     dev_o = os.path.join(BUILD, "entro_device.o")
+    comp_o = os.path.join(BUILD, "entro_compress.o")
     cmds = [
         ["g++", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wextra", "-pthread",
          "-I", INCLUDE, "-c", os.path.join(CSRC, "entro_host.cpp"), "-o", host_o],
         [HIPCC, *DEVICE_FLAGS, "-I", INCLUDE, "-c", os.path.join(CSRC, "entro_device.hip"), "-o", dev_o],
-        [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, host_o, dev_o, "-pthread"],
+        [HIPCC, *DEVICE_FLAGS, "-I", INCLUDE, "-c", os.path.join(CSRC, "entro_compress.hip"), "-o", comp_o],
+        [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, host_o, dev_o, comp_o, "-pthread"],
     ]
     for c in cmds:
         if verbose:

@@ -1,0 +1,483 @@
+// Compression side of libentro on the GPU: the steps that come before the
+// decode path, for weights that already sit in device memory.
+//
+// EntroLLM's offline pipeline (Proposed Method: "Mixed Quantization Scheme",
+// Eq. 1 / Fig. 2; "Huffman weight encoding"; "Segmentation for parallel
+// Huffman decoding", Fig. 3) is range -> (s, z) -> integer grid -> symbol
+// counts -> prefix code -> segmented bit stream.  Three of those steps touch
+// every weight and run here as kernels (range, quantise + count, encode); the
+// two that touch only 256 numbers ((s, z) from the range, the code from the
+// counts) stay on the host between them.
+//
+// Encoding is segment-parallel like decoding: a first kernel adds up the code
+// lengths of every segment, a scan turns them into the bit-offset table, and a
+// third kernel has one wavefront write one segment.  Within a segment the
+// wavefront takes 256 symbols at a time (one aligned dword of four symbols per
+// lane), a prefix sum over the lanes' code lengths gives every code its bit
+// position, and the lanes OR their codes into a staging buffer in LDS, whose
+// whole dwords then go to memory in one coalesced store per 64 dwords.
+// Segments are bit-packed back to back, so the first and the last dword of a
+// segment may be shared with its neighbours: those two are OR-ed into the
+// (zeroed) stream atomically, everything between is stored plainly.
+#include "entro.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+// defined beside entro_last_device_error
+void entro_detail_note_hip_error(const char *what, int hip_error);
+
+namespace {
+
+constexpr int kWG = 256;                       // four wavefronts
+constexpr int kWaves = kWG / 64;
+constexpr int kHistCopies = 8;                 // counters per bin and wave, picked by lane: spreads the hits on the few frequent symbols
+constexpr uint32_t kFlagSymbol = 1u;           // a symbol without a code (or >= 2^bits)
+constexpr uint32_t kFlagCapacity = 2u;         // the stream does not fit stream_cap
+constexpr uint32_t kFlagSize = 4u;             // the stream would reach 4 GiB
+constexpr int kStageDwords = 264;              // 31 carried bits + 256 codes of up to 32 bits, and the dword behind them
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+bool hip_ok(hipError_t e, const char *what) {
+    if (e == hipSuccess) return true;
+    entro_detail_note_hip_error(what, static_cast<int>(e));
+    return false;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Number of workgroups for a grid-stride kernel over `items` work items of one thread each.
+unsigned grid_for(uint64_t items, unsigned per_cu) {
+    thread_local int cached_dev = -1, cached_cus = 0;
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return 0;
+    if (dev != cached_dev) {
+        int n = 0;
+        if (!hip_ok(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute")) return 0;
+        cached_dev = dev;
+        cached_cus = n;
+    }
+    const uint64_t want = (items + kWG - 1) / kWG;
+    const uint64_t cap = static_cast<uint64_t>(cached_cus) * per_cu;
+    const uint64_t g = want < cap ? want : cap;
+    return static_cast<unsigned>(g ? g : 1);
+}
+
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// floats as unsigned keys of the same order (negative values below positive ones)
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// ------------------------------------------------------------------ range
+__global__ void k_range_init(uint32_t *r) {
+    r[0] = 0xffffffffu;   // smallest key seen
+    r[1] = 0u;            // largest key seen
+    r[2] = 0u;            // NaN / Inf seen
+    r[3] = 0u;
+}
+
+__global__ __launch_bounds__(kWG) void k_range(const float *__restrict__ w, uint64_t n, uint32_t *__restrict__ r) {
+    const uint64_t n4 = n >> 2;
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWG;
+    const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x;
+    float lo = __uint_as_float(0x7f800000u), hi = __uint_as_float(0xff800000u);
+    uint32_t bad = 0;
+    auto take = [&](float v) {
+        bad |= ((__float_as_uint(v) & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
+        lo = v < lo ? v : lo;
+        hi = v > hi ? v : hi;
+    };
+    const f32x4 *w4 = reinterpret_cast<const f32x4 *>(w);
+    uint64_t i = gid;
+    for (; i + 3 * stride < n4; i += 4 * stride) {          // four loads in flight per lane
+        const f32x4 a = w4[i], b = w4[i + stride], c = w4[i + 2 * stride], d = w4[i + 3 * stride];
+        take(a.x); take(a.y); take(a.z); take(a.w);
+        take(b.x); take(b.y); take(b.z); take(b.w);
+        take(c.x); take(c.y); take(c.z); take(c.w);
+        take(d.x); take(d.y); take(d.z); take(d.w);
+    }
+    for (; i < n4; i += stride) {
+        const f32x4 a = w4[i];
+        take(a.x); take(a.y); take(a.z); take(a.w);
+    }
+    if (gid < (n & 3u)) take(w[(n4 << 2) + gid]);
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const float l2 = __shfl_xor(lo, m, 64), h2 = __shfl_xor(hi, m, 64);
+        lo = l2 < lo ? l2 : lo;
+        hi = h2 > hi ? h2 : hi;
+        bad |= __shfl_xor(bad, m, 64);
+    }
+    if ((threadIdx.x & 63u) == 0) {
+        // a lane that saw nothing still holds +Inf / -Inf, which lose against every finite value
+        atomicMin(&r[0], order_key(lo));
+        atomicMax(&r[1], order_key(hi));
+        if (bad) atomicOr(&r[2], 1u);
+    }
+}
+
+__global__ void k_range_finish(uint32_t *r) {
+    r[0] = __float_as_uint(key_value(r[0]));
+    r[1] = __float_as_uint(key_value(r[1]));
+}
+
+// ------------------------------------------------------- quantise and count
+__global__ void k_zero_counts(unsigned long long *counts) { counts[threadIdx.x] = 0ull; }
+
+// Eq. 1 on one weight: true division, round half to even, zero-point added in
+// integers, clamped to the grid.  |z| <= 2^24 (checked on the host), so
+// limiting the rounded quotient to +-2^30 first changes no result.
+__device__ __forceinline__ uint32_t quantize_one(float v, float s, int32_t z, int32_t Q) {
+    float r = __builtin_rintf(v / s);
+    r = r < -1073741824.0f ? -1073741824.0f : (r > 1073741824.0f ? 1073741824.0f : r);
+    int32_t q = static_cast<int32_t>(r) + z;
+    q = q < 0 ? 0 : (q > Q ? Q : q);
+    return static_cast<uint32_t>(q);
+}
+
+__global__ __launch_bounds__(kWG) void k_quantize(const float *__restrict__ w, uint64_t n, float s, int32_t z, int32_t Q,
+                                                  uint8_t *__restrict__ q, unsigned long long *__restrict__ counts) {
+    // hist[wave][bin][copy]: the copies of a bin lie in neighbouring banks
+    __shared__ uint32_t hist[kWaves * 256 * kHistCopies];
+    for (int i = threadIdx.x; i < kWaves * 256 * kHistCopies; i += kWG) hist[i] = 0;
+    __syncthreads();
+    uint32_t *mine = hist + (threadIdx.x >> 6) * (256 * kHistCopies) + (threadIdx.x & (kHistCopies - 1));
+    const uint64_t n4 = n >> 2;
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWG;
+    const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x;
+    const f32x4 *w4 = reinterpret_cast<const f32x4 *>(w);
+    uint32_t *q4 = reinterpret_cast<uint32_t *>(q);
+    auto four = [&](const f32x4 v) {
+        const uint32_t a = quantize_one(v.x, s, z, Q), b = quantize_one(v.y, s, z, Q), c = quantize_one(v.z, s, z, Q),
+                       d = quantize_one(v.w, s, z, Q);
+        atomicAdd(&mine[a * kHistCopies], 1u);
+        atomicAdd(&mine[b * kHistCopies], 1u);
+        atomicAdd(&mine[c * kHistCopies], 1u);
+        atomicAdd(&mine[d * kHistCopies], 1u);
+        return a | (b << 8) | (c << 16) | (d << 24);
+    };
+    uint64_t i = gid;
+    for (; i + stride < n4; i += 2 * stride) {               // two loads in flight per lane
+        const f32x4 a = w4[i], b = w4[i + stride];
+        q4[i] = four(a);
+        q4[i + stride] = four(b);
+    }
+    for (; i < n4; i += stride) q4[i] = four(w4[i]);
+    if (gid < (n & 3u)) {
+        const uint32_t a = quantize_one(w[(n4 << 2) + gid], s, z, Q);
+        q[(n4 << 2) + gid] = static_cast<uint8_t>(a);
+        atomicAdd(&mine[a * kHistCopies], 1u);
+    }
+    __syncthreads();
+    // thread t owns bin t
+    uint32_t sum = 0;
+    for (int wv = 0; wv < kWaves; ++wv)
+        for (int c = 0; c < kHistCopies; ++c) sum += hist[wv * (256 * kHistCopies) + threadIdx.x * kHistCopies + c];
+    if (sum) atomicAdd(&counts[threadIdx.x], static_cast<unsigned long long>(sum));
+}
+
+// ------------------------------------------------------------------ encode
+struct EncTable {
+    uint32_t rev[256];    // the code's bits in stream order: first code bit in bit 0
+    uint8_t len[256];     // 0: no code
+};
+
+__global__ void k_encode_init(uint32_t *status) { *status = 0u; }
+
+// Bits of every segment, into offsets[k + 1]; one wavefront per segment.
+__global__ __launch_bounds__(kWG) void k_segment_bits(const uint8_t *__restrict__ q, uint64_t n, uint32_t chunk_symbols,
+                                                      uint32_t n_chunks, const EncTable tab, uint64_t *__restrict__ offsets,
+                                                      uint32_t *__restrict__ status) {
+    __shared__ uint8_t len[256];
+    len[threadIdx.x] = tab.len[threadIdx.x];
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t *q32 = reinterpret_cast<const uint32_t *>(q);
+    for (uint64_t k = static_cast<uint64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6); k < n_chunks;
+         k += static_cast<uint64_t>(gridDim.x) * kWaves) {
+        const uint64_t b0 = k * chunk_symbols;
+        const uint64_t b1 = b0 + chunk_symbols < n ? b0 + chunk_symbols : n;
+        // the aligned dwords that hold the segment's bytes; bytes of a dword outside [b0, b1) are skipped
+        // (a dword with one byte inside the buffer lies inside the buffer's pages as a whole)
+        const uint64_t d1 = (b1 + 3) >> 2;
+        uint32_t sum = 0, miss = 0;
+        for (uint64_t d = (b0 >> 2) + lane; d < d1; d += 64) {
+            const uint32_t word = q32[d];
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) {
+                const uint64_t idx = (d << 2) + j;
+                if (idx >= b0 && idx < b1) {
+                    const uint32_t l = len[(word >> (8 * j)) & 0xffu];
+                    sum += l;
+                    miss |= l == 0 ? 1u : 0u;
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            sum += __shfl_xor(sum, m, 64);
+            miss |= __shfl_xor(miss, m, 64);
+        }
+        if (lane == 0) {
+            offsets[k + 1] = sum;
+            if (miss) atomicOr(status, kFlagSymbol);
+        }
+    }
+}
+
+__device__ __forceinline__ uint64_t padded_bytes(uint64_t total_bits) {
+    uint64_t b = (total_bits + 7) / 8;
+    b = (b + 15) / 16 * 16;
+    return b + 16;
+}
+
+// offsets[k + 1] holds segment k's bits on entry and the stream bit behind segment k on exit.
+// One workgroup walks the table in tiles of four entries per thread.
+constexpr int kScanWG = 1024;
+__global__ __launch_bounds__(kScanWG) void k_scan_offsets(uint64_t *__restrict__ offsets, uint32_t n_chunks, uint64_t stream_cap,
+                                                          uint32_t *__restrict__ status) {
+    __shared__ uint64_t wave_sum[kScanWG / 64];
+    __shared__ uint64_t carry_s;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) {
+        offsets[0] = 0;
+        carry_s = 0;
+    }
+    __syncthreads();
+    for (uint64_t base = 0; base < n_chunks; base += 4 * kScanWG) {
+        const uint64_t at = base + 4ull * threadIdx.x;
+        uint64_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = at + j < n_chunks ? offsets[at + j + 1] : 0;
+        v[1] += v[0];
+        v[2] += v[1];
+        v[3] += v[2];
+        uint64_t x = v[3];
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            const uint64_t y = __shfl_up(x, m, 64);
+            if (lane >= static_cast<uint32_t>(m)) x += y;
+        }
+        if (lane == 63) wave_sum[wave] = x;
+        __syncthreads();
+        uint64_t before = carry_s;
+        for (uint32_t wv = 0; wv < wave; ++wv) before += wave_sum[wv];
+        before += x - v[3];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (at + j < n_chunks) offsets[at + j + 1] = before + v[j];
+        __syncthreads();
+        if (threadIdx.x == kScanWG - 1) carry_s = before + v[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const uint64_t need = padded_bytes(carry_s);
+        if (need > stream_cap) atomicOr(status, kFlagCapacity);
+        if (need >= (1ull << 32)) atomicOr(status, kFlagSize);
+    }
+}
+
+// Zero the bytes the stream will occupy (the padding included), and no more than stream_cap.
+__global__ __launch_bounds__(kWG) void k_zero_stream(u32x4 *__restrict__ stream, uint64_t stream_cap,
+                                                     const uint64_t *__restrict__ offsets, uint32_t n_chunks,
+                                                     const uint32_t *__restrict__ status) {
+    if (*status != 0u) return;
+    uint64_t need = padded_bytes(offsets[n_chunks]);
+    need = need < stream_cap ? need : (stream_cap & ~15ull);
+    const uint64_t blocks = need >> 4;
+    const u32x4 zero = {0, 0, 0, 0};
+    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x; i < blocks;
+         i += static_cast<uint64_t>(gridDim.x) * kWG)
+        stream[i] = zero;
+}
+
+// One wavefront writes one segment.
+__global__ __launch_bounds__(kWG) void k_write_segments(const uint8_t *__restrict__ q, uint64_t n, uint32_t chunk_symbols,
+                                                        uint32_t n_chunks, const EncTable tab,
+                                                        const uint64_t *__restrict__ offsets, uint32_t *__restrict__ stream,
+                                                        uint64_t stream_dwords, const uint32_t *__restrict__ status) {
+    __shared__ uint64_t entry[256];                      // rev | len << 32
+    __shared__ uint32_t stage_all[kWaves][kStageDwords];
+    entry[threadIdx.x] = tab.rev[threadIdx.x] | (static_cast<uint64_t>(tab.len[threadIdx.x]) << 32);
+    for (int i = threadIdx.x; i < kWaves * kStageDwords; i += kWG) (&stage_all[0][0])[i] = 0;
+    __syncthreads();
+    if (*status != 0u) return;                           // a symbol without a code, or no room: nothing is written
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t *stage = stage_all[threadIdx.x >> 6];
+    const uint32_t *q32 = reinterpret_cast<const uint32_t *>(q);
+    for (uint64_t k = static_cast<uint64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6); k < n_chunks;
+         k += static_cast<uint64_t>(gridDim.x) * kWaves) {
+        const uint64_t b0 = k * chunk_symbols;
+        const uint64_t b1 = b0 + chunk_symbols < n ? b0 + chunk_symbols : n;
+        const uint64_t d1 = (b1 + 3) >> 2;
+        const uint64_t start = offsets[k];
+        const uint64_t first_g = start >> 5;             // the stream dword the segment starts in
+        uint64_t g = first_g;                            // where stage[0] goes
+        uint32_t fill = static_cast<uint32_t>(start & 31u);   // bits in the stage, counted from bit 0 of stage[0]
+        for (uint64_t d0 = b0 >> 2; d0 < d1; d0 += 64) {
+            const uint64_t d = d0 + lane;
+            const uint32_t word = d < d1 ? q32[d] : 0u;
+            uint32_t rev[4], len[4], tot = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) {
+                const uint64_t idx = (d << 2) + j;
+                const uint64_t e = entry[(word >> (8 * j)) & 0xffu];
+                const bool in = d < d1 && idx >= b0 && idx < b1;
+                rev[j] = static_cast<uint32_t>(e);
+                len[j] = in ? static_cast<uint32_t>(e >> 32) : 0u;
+                tot += len[j];
+            }
+            uint32_t x = tot;                            // inclusive prefix sum over the lanes
+#pragma unroll
+            for (int m = 1; m < 64; m <<= 1) {
+                const uint32_t y = __shfl_up(x, m, 64);
+                if (lane >= static_cast<uint32_t>(m)) x += y;
+            }
+            const uint32_t round_bits = __shfl(x, 63, 64);
+            uint32_t p = fill + x - tot;
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) {
+                if (len[j]) {
+                    const uint32_t sh = p & 31u;
+                    const uint64_t v = static_cast<uint64_t>(rev[j]) << sh;
+                    atomicOr(&stage[p >> 5], static_cast<uint32_t>(v));
+                    if (sh + len[j] > 32u) atomicOr(&stage[(p >> 5) + 1], static_cast<uint32_t>(v >> 32));
+                    p += len[j];
+                }
+            }
+            fill += round_bits;
+            wave_sync_lds();
+            // the whole dwords go out; the segment's first dword may hold the end of the segment before
+            const uint32_t full = fill >> 5;
+            for (uint32_t i = lane; i < full; i += 64) {
+                const uint32_t v = stage[i];
+                stage[i] = 0;
+                if (g + i < stream_dwords) {
+                    if (g + i == first_g) atomicOr(&stream[g + i], v);
+                    else stream[g + i] = v;
+                }
+            }
+            wave_sync_lds();
+            if (full && lane == 0) {
+                const uint32_t c = stage[full];
+                stage[full] = 0;
+                stage[0] = c;
+            }
+            wave_sync_lds();
+            g += full;
+            fill &= 31u;
+        }
+        // what is left is shared with the next segment
+        if (lane == 0 && fill) {
+            const uint32_t c = stage[0];
+            stage[0] = 0;
+            if (g < stream_dwords) atomicOr(&stream[g], c);
+        }
+        wave_sync_lds();
+    }
+}
+
+EncTable make_table(const entro_codebook *cb) {
+    EncTable t;
+    std::memset(&t, 0, sizeof(t));
+    for (int s = 0; s < (1 << cb->bits); ++s) {
+        const uint32_t l = cb->len[s];
+        if (!l) continue;
+        uint32_t r = 0;
+        for (uint32_t b = 0; b < l; ++b) r |= ((cb->code[s] >> (l - 1 - b)) & 1u) << b;
+        t.rev[s] = r;
+        t.len[s] = static_cast<uint8_t>(l);
+    }
+    return t;
+}
+
+}  // namespace
+
+extern "C" {
+
+entro_status entro_range_device(const float *w, uint64_t n, void *range16, void *hip_stream) {
+    if (!w || !range16) return ENTRO_ERR_NULL;
+    if (n == 0) return ENTRO_ERR_SIZE;
+    if (!aligned16(w) || !aligned16(range16)) return ENTRO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const unsigned grid = grid_for((n + 3) / 4, 8);
+    if (!grid) return ENTRO_ERR_DEVICE;
+    uint32_t *r = static_cast<uint32_t *>(range16);
+    hipLaunchKernelGGL(k_range_init, dim3(1), dim3(1), 0, st, r);
+    hipLaunchKernelGGL(k_range, dim3(grid), dim3(kWG), 0, st, w, n, r);
+    hipLaunchKernelGGL(k_range_finish, dim3(1), dim3(1), 0, st, r);
+    return hip_ok(hipGetLastError(), "entro_range_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;
+}
+
+entro_status entro_quantize_device(const float *w, uint64_t n, const entro_qparams *qp, uint8_t *q, uint64_t *counts,
+                                   void *hip_stream) {
+    if (!w || !qp || !q || !counts) return ENTRO_ERR_NULL;
+    if (qp->bits != 4 && qp->bits != 8) return ENTRO_ERR_BITS;
+    if (qp->scheme != ENTRO_UNSIGNED && qp->scheme != ENTRO_ASYMMETRIC) return ENTRO_ERR_SCHEME;
+    if (n == 0) return ENTRO_ERR_SIZE;
+    if (!(qp->scale > 0.0f) || qp->scale > 3.0e38f) return ENTRO_ERR_RANGE;
+    if (qp->zero_point > (1 << 24) || qp->zero_point < -(1 << 24)) return ENTRO_ERR_RANGE;
+    if (!aligned16(w) || !aligned16(q) || !aligned16(counts)) return ENTRO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const unsigned grid = grid_for((n + 3) / 4, 4);
+    if (!grid) return ENTRO_ERR_DEVICE;
+    unsigned long long *c = reinterpret_cast<unsigned long long *>(counts);
+    hipLaunchKernelGGL(k_zero_counts, dim3(1), dim3(256), 0, st, c);
+    hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kWG), 0, st, w, n, qp->scale, qp->zero_point, (1 << qp->bits) - 1, q, c);
+    return hip_ok(hipGetLastError(), "entro_quantize_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;
+}
+
+entro_status entro_encode_device(const uint8_t *q, uint64_t n, const entro_codebook *cb, uint32_t chunk_symbols, void *stream,
+                                 uint64_t stream_cap, uint64_t *offsets, uint32_t *status, void *hip_stream) {
+    if (!q || !cb || !stream || !offsets || !status) return ENTRO_ERR_NULL;
+    if (cb->bits != 4 && cb->bits != 8) return ENTRO_ERR_BITS;
+    if (n == 0 || chunk_symbols == 0 || chunk_symbols > (1u << 20)) return ENTRO_ERR_SIZE;
+    if (cb->max_len < 1 || cb->max_len > ENTRO_MAX_CODE_LEN) return ENTRO_ERR_CORRUPT;
+    for (int s = 0; s < ENTRO_MAX_SYMBOLS; ++s)
+        if (cb->len[s] > cb->max_len || (s >= (1 << cb->bits) && cb->len[s])) return ENTRO_ERR_CORRUPT;
+    {
+        // the codes must be the canonical ones of the lengths: that is what every decoder rebuilds
+        entro_codebook ref;
+        if (entro_codebook_from_lengths(cb->len, cb->bits, &ref) != ENTRO_OK) return ENTRO_ERR_CORRUPT;
+        for (int s = 0; s < (1 << cb->bits); ++s)
+            if (ref.code[s] != cb->code[s]) return ENTRO_ERR_CORRUPT;
+    }
+    const uint64_t n_chunks = entro_num_chunks(n, chunk_symbols);
+    if (n_chunks >= (uint64_t{1} << 32) - 1024) return ENTRO_ERR_SIZE;
+    if (stream_cap < 32 || (stream_cap & 15u)) return ENTRO_ERR_CAPACITY;
+    if (!aligned16(q) || !aligned16(stream) || !aligned16(offsets) || (reinterpret_cast<uintptr_t>(status) & 3u)) return ENTRO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const EncTable tab = make_table(cb);
+    const unsigned grid = grid_for(n_chunks * 64, 8);
+    const unsigned zgrid = grid_for(stream_cap / 16, 8);
+    if (!grid || !zgrid) return ENTRO_ERR_DEVICE;
+    const uint32_t nc = static_cast<uint32_t>(n_chunks);
+    hipLaunchKernelGGL(k_encode_init, dim3(1), dim3(1), 0, st, status);
+    hipLaunchKernelGGL(k_segment_bits, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets, status);
+    hipLaunchKernelGGL(k_scan_offsets, dim3(1), dim3(kScanWG), 0, st, offsets, nc, stream_cap, status);
+    hipLaunchKernelGGL(k_zero_stream, dim3(zgrid), dim3(kWG), 0, st, static_cast<u32x4 *>(stream), stream_cap, offsets, nc, status);
+    hipLaunchKernelGGL(k_write_segments, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets,
+                       static_cast<uint32_t *>(stream), stream_cap / 4, status);
+    return hip_ok(hipGetLastError(), "entro_encode_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;
+}
+
+entro_status entro_encode_device_status(uint32_t status_word) {
+    if (status_word & kFlagSymbol) return ENTRO_ERR_SYMBOL;
+    if (status_word & kFlagCapacity) return ENTRO_ERR_CAPACITY;
+    if (status_word & kFlagSize) return ENTRO_ERR_SIZE;
+    return status_word ? ENTRO_ERR_CORRUPT : ENTRO_OK;
+}
+
+}  // extern "C"

@@ -1435,6 +1435,11 @@ __global__ __launch_bounds__(1024) void k_stream_probe(const u32x4 *__restrict__
     if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u) *sink = acc.z;     // keeps the reads alive
 }
 
+// for the library's other device source: record a failed HIP call for entro_last_device_error
+void entro_detail_note_hip_error(const char *what, int hip_error) {
+    hip_ok(static_cast<hipError_t>(hip_error), what);
+}
+
 extern "C" {
 
 const char *entro_last_device_error(void) { return g_last_error.c_str(); }

@@ -254,13 +254,39 @@ uint64_t padded_bytes(uint64_t total_bits) {
 
 extern "C" {
 
+entro_status entro_qparams_from_range(float min, float max, uint32_t nonfinite, int bits, entro_scheme scheme,
+                                      entro_qparams *qp) {
+    if (!qp) return ENTRO_ERR_NULL;
+    if (!bits_ok(bits)) return ENTRO_ERR_BITS;
+    if (scheme != ENTRO_UNSIGNED && scheme != ENTRO_ASYMMETRIC) return ENTRO_ERR_SCHEME;
+    if (nonfinite || !std::isfinite(min) || !std::isfinite(max)) return ENTRO_ERR_NONFINITE;
+    const float Q = static_cast<float>((1 << bits) - 1);
+    float s;
+    int32_t z;
+    if (scheme == ENTRO_UNSIGNED) {
+        if (min < 0.0f || !(max > 0.0f)) return ENTRO_ERR_RANGE;
+        s = max / Q;
+        z = 0;
+    } else {
+        if (!(max > min)) return ENTRO_ERR_RANGE;
+        s = (max - min) / Q;
+        if (!(s > 0.0f) || !std::isfinite(s)) return ENTRO_ERR_RANGE;
+        z = static_cast<int32_t>(std::nearbyintf(-min / s));
+    }
+    if (!(s > 0.0f) || !std::isfinite(s)) return ENTRO_ERR_RANGE;
+    qp->scale = s;
+    qp->zero_point = z;
+    qp->bits = bits;
+    qp->scheme = scheme;
+    return ENTRO_OK;
+}
+
 entro_status entro_quantize(const float *w, uint64_t n, int bits, entro_scheme scheme, uint8_t *q,
                             entro_qparams *qp) {
     if (!w || !q || !qp) return ENTRO_ERR_NULL;
     if (!bits_ok(bits)) return ENTRO_ERR_BITS;
     if (scheme != ENTRO_UNSIGNED && scheme != ENTRO_ASYMMETRIC) return ENTRO_ERR_SCHEME;
     if (n == 0) return ENTRO_ERR_SIZE;
-    const float Q = static_cast<float>((1 << bits) - 1);
 
     const unsigned parts = worker_count(n, 1u << 20);
     std::vector<float> lo(parts, w[0]), hi(parts, w[0]);
@@ -284,19 +310,10 @@ entro_status entro_quantize(const float *w, uint64_t n, int bits, entro_scheme s
         mn = std::min(mn, lo[p]);
         mx = std::max(mx, hi[p]);
     }
-    float s;
-    int32_t z;
-    if (scheme == ENTRO_UNSIGNED) {
-        if (mn < 0.0f || !(mx > 0.0f)) return ENTRO_ERR_RANGE;
-        s = mx / Q;
-        z = 0;
-    } else {
-        if (!(mx > mn)) return ENTRO_ERR_RANGE;
-        s = (mx - mn) / Q;
-        if (!(s > 0.0f) || !std::isfinite(s)) return ENTRO_ERR_RANGE;
-        z = static_cast<int32_t>(std::nearbyintf(-mn / s));
-    }
-    if (!(s > 0.0f) || !std::isfinite(s)) return ENTRO_ERR_RANGE;
+    entro_status st = entro_qparams_from_range(mn, mx, 0, bits, scheme, qp);
+    if (st != ENTRO_OK) return st;
+    const float s = qp->scale;
+    const int32_t z = qp->zero_point;
     const int32_t Qi = (1 << bits) - 1;
     parallel_ranges(n, 1u << 20, [&](unsigned, uint64_t b, uint64_t e) {
         for (uint64_t i = b; i < e; ++i) {
@@ -306,10 +323,6 @@ entro_status entro_quantize(const float *w, uint64_t n, int bits, entro_scheme s
             q[i] = static_cast<uint8_t>(v);
         }
     });
-    qp->scale = s;
-    qp->zero_point = z;
-    qp->bits = bits;
-    qp->scheme = scheme;
     return ENTRO_OK;
 }
 
@@ -397,6 +410,16 @@ uint64_t entro_num_chunks(uint64_t n, uint32_t chunk_symbols) {
 uint64_t entro_encode_bound(uint64_t n, const entro_codebook *cb) {
     if (!cb || n == 0 || cb->max_len < 1 || cb->max_len > ENTRO_MAX_CODE_LEN) return 0;
     return padded_bytes(n * static_cast<uint64_t>(cb->max_len));
+}
+
+uint64_t entro_encoded_bytes(const uint64_t *counts, const entro_codebook *cb) {
+    if (!counts || !cb || !bits_ok(cb->bits)) return 0;
+    uint64_t bits = 0;
+    for (int s = 0; s < (1 << cb->bits); ++s) {
+        if (counts[s] && !cb->len[s]) return 0;
+        bits += counts[s] * cb->len[s];
+    }
+    return padded_bytes(bits);
 }
 
 entro_status entro_encode(const uint8_t *q, uint64_t n, const entro_codebook *cb,

@@ -1,0 +1,209 @@
+"""GPU parity of the compression kernels (range, quantise + count, encode), called
+through the C ABI, against the CPU oracle.
+
+Bars: everything here is integer or bit work and must be identical: the range as
+numbers, the symbols byte for byte, the counts, the offset table and every byte
+of the stream including its padding.  The oracle quantises, counts and encodes
+the same seeded inputs; codebooks come from the oracle's lengths (canonical
+codes are a function of the lengths), never from the device."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+import paper_2505_02380_amd as E
+from paper_2505_02380_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _codebook(ln, bits):
+    full = np.zeros(1 << bits, np.uint8)
+    full[: len(ln)] = ln
+    return E.entro_codebook_from_lengths(full, bits)
+
+
+def _gpu_encode(sym, cb, chunk, cap=None, guard=64):
+    """-> (stream bytes incl. guard, offsets, status word)."""
+    q = torch.from_numpy(sym).to(DEV)
+    cnt = np.bincount(sym, minlength=256).astype(np.uint64)
+    need = E.entro_encoded_bytes(cnt, cb)
+    cap = need if cap is None else cap
+    buf = torch.full((cap + guard,), 0xAB, dtype=torch.uint8, device=DEV)
+    offsets = torch.full((E.entro_num_chunks(sym.size, chunk) + 1 + 2,), -1, dtype=torch.int64, device=DEV)
+    status = torch.full((4,), 77, dtype=torch.int32, device=DEV)
+    E.entro_encode_device(q, cb, chunk, buf[:cap], offsets, status)
+    torch.cuda.synchronize()
+    assert torch.all(offsets[-2:] == -1), "wrote past the end of the offset table"
+    assert torch.all(status[1:] == 77)
+    return buf.cpu().numpy(), offsets[:-2].cpu().numpy().view(np.uint64), int(status[0].item()) & 0xFFFFFFFF, cap
+
+
+def _assert_same_stream(sym, ln, bits, chunk):
+    code = oracle.canonical_codes(ln)
+    ref_stream, ref_off = oracle.encode(sym, ln, code, chunk)
+    cb = _codebook(ln, bits)
+    got, off, status, cap = _gpu_encode(sym, cb, chunk)
+    assert status == 0
+    assert cap == ref_stream.size, "entro_encoded_bytes disagrees with the oracle's stream size"
+    assert np.array_equal(off, ref_off)
+    assert np.array_equal(got[:cap], ref_stream)
+    assert np.all(got[cap:] == 0xAB), "wrote past the end of the stream"
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4096, 100003])
+def test_range_matches_numpy(n):
+    rng = np.random.default_rng(n)
+    w = (rng.standard_t(4, n) * 0.02).astype(np.float32)
+    d = torch.from_numpy(w).to(DEV)
+    out = torch.full((8,), 5, dtype=torch.int32, device=DEV)
+    E.entro_range_device(d, out)
+    torch.cuda.synchronize()
+    r = out.cpu().numpy()
+    mn, mx = r[:2].view(np.float32)
+    assert mn == w.min() and mx == w.max()
+    assert r[2] == 0 and r[3] == 0 and np.all(r[4:] == 5)
+
+
+def test_range_reports_nan_and_inf_and_signed_zero():
+    w = np.linspace(-1, 2, 5000).astype(np.float32)
+    for bad in (np.nan, np.inf, -np.inf):
+        v = w.copy()
+        v[1234] = bad
+        out = torch.zeros(4, dtype=torch.int32, device=DEV)
+        E.entro_range_device(torch.from_numpy(v).to(DEV), out)
+        assert out.cpu().numpy()[2] == 1
+    # all values >= 0 with a negative zero among them: the range is [0, max] whichever zero is kept
+    v = np.abs(w)
+    v[7] = -0.0
+    out = torch.zeros(4, dtype=torch.int32, device=DEV)
+    E.entro_range_device(torch.from_numpy(v).to(DEV), out)
+    r = out.cpu().numpy()
+    assert r[:2].view(np.float32)[0] == 0.0 and r[2] == 0
+
+
+@pytest.mark.parametrize("bits,scheme", [(8, 1), (4, 1), (8, 0), (4, 0)])
+@pytest.mark.parametrize("n", [7, 4096, 1_000_003])
+def test_quantize_and_counts_match_the_oracle(bits, scheme, n):
+    rng = np.random.default_rng(100 * bits + scheme + n)
+    w = (rng.standard_t(4, n) * 0.02).astype(np.float32)
+    if scheme == 0:
+        w = np.abs(w)
+    q_ref, s_ref, z_ref = oracle.quantize(w, bits, scheme)
+    d = torch.from_numpy(w).to(DEV)
+    r = torch.zeros(4, dtype=torch.int32, device=DEV)
+    E.entro_range_device(d, r)
+    rr = r.cpu().numpy()
+    mn, mx = rr[:2].view(np.float32)
+    qp = E.entro_qparams_from_range(float(mn), float(mx), int(rr[2]), bits, scheme)
+    assert np.float32(qp.scale) == s_ref and qp.zero_point == z_ref
+    q = torch.full((n + 64,), 0xAB, dtype=torch.uint8, device=DEV)
+    counts = torch.full((256 + 2,), -1, dtype=torch.int64, device=DEV)
+    E.entro_quantize_device(d, qp, q[:n], counts)
+    torch.cuda.synchronize()
+    got = q.cpu().numpy()
+    assert np.array_equal(got[:n], q_ref)
+    assert np.all(got[n:] == 0xAB), "wrote past the end of q"
+    c = counts.cpu().numpy()
+    assert np.all(c[256:] == -1)
+    ref = np.zeros(256, np.int64)
+    ref[: 1 << bits] = oracle.histogram(q_ref, bits).astype(np.int64)
+    assert np.array_equal(c[:256], ref)
+
+
+def test_quantize_ties_round_to_even_and_clamp():
+    # s = 1 (range 0..255 unsigned): halves must go to the even neighbour; an off-grid zero-point clamps
+    w = np.array([0.5, 1.5, 2.5, 3.5, 254.5, 255.0, 0.0, 126.5, 127.5, 17.49999, 17.50001], np.float32)
+    q_ref, s, z = oracle.quantize(w, 8, 0)
+    assert s == 1.0 and list(q_ref[:4]) == [0, 2, 2, 4]
+    d = torch.from_numpy(w).to(DEV)
+    q = torch.zeros(w.size, dtype=torch.uint8, device=DEV)
+    counts = torch.zeros(256, dtype=torch.int64, device=DEV)
+    E.entro_quantize_device(d, B.QParams(np.float32(s), z, 8, 0), q, counts)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    # zero-point far outside the grid: everything clamps to one end, as in the definition
+    for zp, expect in ((-1000, 0), (1000, 255)):
+        E.entro_quantize_device(d, B.QParams(np.float32(1.0), zp, 8, 1), q, counts)
+        assert np.all(q.cpu().numpy() == expect)
+        assert int(counts[expect].item()) == w.size
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_encode_adversarial_streams_identical(bits):
+    for name, sym, chunk in synth.adversarial_symbol_cases(bits):
+        ln, code, _ = oracle.codebook_from_symbols(sym, bits)
+        _assert_same_stream(sym, ln, bits, chunk)
+
+
+@pytest.mark.parametrize("chunk", [1, 2, 3, 5, 63, 64, 255, 257, 1000, 4096, 8192, 1 << 20])
+def test_encode_segment_sizes_and_unaligned_starts(chunk):
+    rng = np.random.default_rng(chunk)
+    n = 50000 if chunk < 64 else 300001
+    sym = np.minimum(rng.geometric(0.3, n) - 1, 255).astype(np.uint8)
+    ln, code, _ = oracle.codebook_from_symbols(sym, 8)
+    _assert_same_stream(sym, ln, 8, chunk)
+
+
+def test_encode_codes_of_every_length_up_to_32():
+    # lengths 1..31, 32, 32 with all symbols equally frequent: 256 codes of a round fill the staging buffer
+    ln = np.zeros(256, np.uint8)
+    ln[:33] = list(range(1, 32)) + [32, 32]
+    rng = np.random.default_rng(32)
+    sym = rng.integers(0, 33, 70001).astype(np.uint8)
+    _assert_same_stream(sym, ln, 8, 4096)
+    # the longest codes only: every round writes 256 * 32 bits
+    sym = rng.integers(31, 33, 20000).astype(np.uint8)
+    _assert_same_stream(sym, ln, 8, 777)
+
+
+def test_encode_reports_missing_code_and_small_capacity_and_writes_nothing():
+    rng = np.random.default_rng(5)
+    sym = rng.integers(0, 16, 100000).astype(np.uint8)
+    ln, code, _ = oracle.codebook_from_symbols(sym, 8)
+    cb = _codebook(ln, 8)
+    bad = sym.copy()
+    bad[77777] = 200                                   # no code for 200
+    cnt = np.bincount(sym, minlength=256).astype(np.uint64)
+    need = E.entro_encoded_bytes(cnt, cb)
+    assert E.entro_encoded_bytes(np.bincount(bad, minlength=256).astype(np.uint64), cb) == 0
+    q = torch.from_numpy(bad).to(DEV)
+    buf = torch.full((need + 64,), 0xAB, dtype=torch.uint8, device=DEV)
+    offsets = torch.zeros(E.entro_num_chunks(sym.size, 4096) + 1, dtype=torch.int64, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    E.entro_encode_device(q, cb, 4096, buf[:need], offsets, status)
+    assert E.entro_encode_device_status(int(status.item())) == B.ENTRO_ERR_SYMBOL
+    assert torch.all(buf == 0xAB)
+    # capacity 16 bytes short
+    got, off, st, cap = _gpu_encode(sym, cb, 4096, cap=need - 16)
+    assert E.entro_encode_device_status(st) == B.ENTRO_ERR_CAPACITY
+    assert np.all(got[cap:] == 0xAB)
+    # generous capacity is fine and leaves the bytes behind the stream alone
+    got, off, st, cap = _gpu_encode(sym, cb, 4096, cap=need + 4096)
+    ref_stream, ref_off = oracle.encode(sym, ln, code, 4096)
+    assert st == 0 and np.array_equal(got[:need], ref_stream) and np.array_equal(off, ref_off)
+    assert np.all(got[need:] == 0xAB)
+
+
+@pytest.mark.parametrize("bits,scheme,max_len", [(8, 1, 0), (4, 1, 0), (8, 1, 12)])
+def test_compress_then_decode_on_the_device(bits, scheme, max_len):
+    # the whole chain on the GPU, checked link by link against the oracle's chain on the same weights
+    spec = synth.config_tensors(1)[0]
+    w = synth.make_tensor(spec).ravel()[: 1_500_000 + 37]
+    q_ref, s_ref, z_ref = oracle.quantize(w, bits, scheme)
+    dt, q = E.compress_on_device(torch.from_numpy(w).to(DEV), bits, scheme, 4096, max_len=max_len, return_q=True)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    cb, qp = dt.enc.cb, dt.enc.qp
+    assert np.float32(qp.scale) == s_ref and qp.zero_point == z_ref
+    ln = cb.lengths()[: 1 << bits]
+    cnt = oracle.histogram(q_ref, bits)
+    ref_ln = oracle.limited_lengths(cnt, max_len)[0] if max_len else oracle.huffman_lengths(cnt)
+    assert int(np.sum(cnt * ln.astype(np.uint64))) == int(np.sum(cnt * ref_ln.astype(np.uint64)))   # optimal cost
+    assert not max_len or ln.max() <= max_len
+    ref_stream, ref_off = oracle.encode(q_ref, ln, oracle.canonical_codes(ln), 4096)
+    assert np.array_equal(dt.stream.cpu().numpy(), ref_stream)
+    assert np.array_equal(dt.offsets.cpu().numpy().view(np.uint64), ref_off)
+    out = torch.zeros(w.size, dtype=torch.float32, device=DEV)
+    E.entro_decode_dequant(dt.ctensor(out), E.ENTRO_F32)
+    assert np.array_equal(out.cpu().numpy(), oracle.dequant_f32(q_ref, s_ref, z_ref))

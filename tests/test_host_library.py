@@ -292,3 +292,62 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert L.entro_plan_init(C.byref(plan), C.byref(t), 1, E.ENTRO_OP_DECODE, E.ENTRO_U8, 4096, 16, None) \
         == B.ENTRO_ERR_CAPACITY
     assert L.entro_plan_run(C.byref(B.Plan()), None) == B.ENTRO_ERR_NULL
+
+
+@pytest.mark.parametrize("bits,scheme", [(8, 1), (8, 0), (4, 1), (4, 0)])
+def test_qparams_from_range_is_the_quantizer_s_first_half(bits, scheme):
+    rng = np.random.default_rng(7 + bits + scheme)
+    w = (rng.standard_t(4, 20001) * 0.02).astype(np.float32)
+    if scheme == 0:
+        w = np.abs(w)
+    _, s, z = oracle.quantize(w, bits, scheme)
+    qp = E.entro_qparams_from_range(float(w.min()), float(w.max()), 0, bits, scheme)
+    assert np.float32(qp.scale) == s and qp.zero_point == z and qp.bits == bits and qp.scheme == scheme
+    for args, status in [
+        ((0.0, 1.0, 1, bits, scheme), B.ENTRO_ERR_NONFINITE),
+        ((0.0, float("inf"), 0, bits, scheme), B.ENTRO_ERR_NONFINITE),
+        ((2.0, 2.0, 0, bits, 1), B.ENTRO_ERR_RANGE),
+        ((-1.0, 1.0, 0, bits, 0), B.ENTRO_ERR_RANGE),
+        ((0.0, 1.0, 0, 5, scheme), B.ENTRO_ERR_BITS),
+        ((0.0, 1.0, 0, bits, 9), B.ENTRO_ERR_SCHEME),
+    ]:
+        with pytest.raises(E.EntroError) as e:
+            E.entro_qparams_from_range(*args)
+        assert e.value.status == status
+
+
+def test_encoded_bytes_is_the_encoder_s_stream_size():
+    for name, sym, chunk in synth.adversarial_symbol_cases(8):
+        ln, code, cnt = oracle.codebook_from_symbols(sym, 8)
+        cb = E.entro_codebook_from_lengths(ln, 8)
+        stream, off = oracle.encode(sym, ln, code, chunk)
+        assert E.entro_encoded_bytes(cnt, cb) == stream.size == oracle.stream_bytes(int(off[-1])), name
+    cnt = np.zeros(256, np.uint64)
+    cnt[255] = 1                                                     # a counted symbol without a code
+    ln, _, _ = oracle.codebook_from_symbols(np.array([0, 1, 1], np.uint8), 8)
+    assert E.entro_encoded_bytes(cnt, E.entro_codebook_from_lengths(ln, 8)) == 0
+
+
+def test_device_compression_calls_validate_before_touching_the_gpu():
+    L = E.lib()
+    qp = B.QParams(1.0, 0, 8, 1)
+    assert L.entro_range_device(None, 4, 4096, None) == B.ENTRO_ERR_NULL
+    assert L.entro_range_device(4096, 0, 8192, None) == B.ENTRO_ERR_SIZE
+    assert L.entro_range_device(4100, 4, 8192, None) == B.ENTRO_ERR_ALIGN
+    assert L.entro_quantize_device(4096, 4, C.byref(qp), 8192, None, None) == B.ENTRO_ERR_NULL
+    assert L.entro_quantize_device(4096, 4, C.byref(B.QParams(1.0, 0, 5, 1)), 8192, 12288, None) == B.ENTRO_ERR_BITS
+    assert L.entro_quantize_device(4096, 4, C.byref(B.QParams(0.0, 0, 8, 1)), 8192, 12288, None) == B.ENTRO_ERR_RANGE
+    assert L.entro_quantize_device(4096, 4, C.byref(B.QParams(1.0, 1 << 25, 8, 1)), 8192, 12288, None) == B.ENTRO_ERR_RANGE
+    assert L.entro_quantize_device(4096, 4, C.byref(qp), 8193, 12288, None) == B.ENTRO_ERR_ALIGN
+    sym = np.arange(16, dtype=np.uint8).repeat(4)
+    cb = E.entro_build_codebook(sym, 4)
+    assert L.entro_encode_device(4096, 64, C.byref(cb), 32, 8192, 64, 12288, None, None) == B.ENTRO_ERR_NULL
+    assert L.entro_encode_device(4096, 64, C.byref(cb), 0, 8192, 64, 12288, 16384, None) == B.ENTRO_ERR_SIZE
+    assert L.entro_encode_device(4096, 64, C.byref(cb), (1 << 20) + 1, 8192, 64, 12288, 16384, None) == B.ENTRO_ERR_SIZE
+    assert L.entro_encode_device(4096, 64, C.byref(cb), 32, 8192, 40, 12288, 16384, None) == B.ENTRO_ERR_CAPACITY
+    assert L.entro_encode_device(4096, 64, C.byref(cb), 32, 8200, 64, 12288, 16384, None) == B.ENTRO_ERR_ALIGN
+    bad = B.Codebook.from_buffer_copy(cb)
+    bad.code[3] ^= 1
+    assert L.entro_encode_device(4096, 64, C.byref(bad), 32, 8192, 64, 12288, 16384, None) == B.ENTRO_ERR_CORRUPT
+    assert [E.entro_encode_device_status(v) for v in (0, 1, 2, 4, 3)] == \
+        [B.ENTRO_OK, B.ENTRO_ERR_SYMBOL, B.ENTRO_ERR_CAPACITY, B.ENTRO_ERR_SIZE, B.ENTRO_ERR_SYMBOL]
