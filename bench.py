@@ -476,6 +476,53 @@ def main():
             del enc_c, dts_c, out_c, v_c, ts_c, plan_c
         result["other_configs"] = others
 
+    # ------------------------------------------------ the steps before the path, on the GPU
+    if not args.no_extras:
+        log("timing the compression kernels on layer 0's fp32 weights")
+        specs0 = synth.config_tensors(4, layers=1)
+        comp = {"workload": "layer 0 of the mistral-7B-shaped set, fp32 weights resident in HBM: range, quantise + count, "
+                            "encode (kernels; the (s, z) and codebook steps between them run on the host and are not timed)",
+                "tensors": {}}
+        k_total, n_total = 0.0, 0
+        for spec, e in zip(specs0, encs):
+            assert e.name == f"L{spec.layer}.{spec.name}" and e.n == spec.rows * spec.cols
+            w = torch.from_numpy(synth.make_tensor(spec).ravel()).to(dev)
+            small = torch.empty(8, dtype=torch.int32, device=dev)
+            counts = torch.empty(256, dtype=torch.int64, device=dev)
+            qd = torch.empty(w.numel(), dtype=torch.uint8, device=dev)
+            _, k_r = timed(lambda: E.entro_range_device(w, small), 5, 1)
+            r = small[:4].cpu().numpy()
+            mn, mx = r[:2].view(np.float32)
+            qp = E.entro_qparams_from_range(float(mn), float(mx), int(r[2]), 8, E.ENTRO_ASYMMETRIC)
+            _, k_q = timed(lambda: E.entro_quantize_device(w, qp, qd, counts), 5, 1)
+            cnt = counts.cpu().numpy().view(np.uint64)
+            cb = E.entro_codebook_from_counts(cnt, 8)
+            st_d = torch.empty(E.entro_encoded_bytes(cnt, cb), dtype=torch.uint8, device=dev)
+            off_d = torch.empty(E.entro_num_chunks(w.numel(), e.chunk_symbols) + 1, dtype=torch.int64, device=dev)
+            status = small[4:5]
+            _, k_e = timed(lambda: E.entro_encode_device(qd, cb, e.chunk_symbols, st_d, off_d, status), 5, 1)
+            # the host library encoded the same weights for the decode legs: the two streams must be identical
+            same = (int(status.item()) == 0 and np.float32(qp.scale) == np.float32(e.qp.scale)
+                    and qp.zero_point == e.qp.zero_point and np.array_equal(st_d.cpu().numpy(), e.stream)
+                    and np.array_equal(off_d.cpu().numpy().view(np.uint64), e.offsets))
+            if not same:
+                print(f"bench.py: device-side compression of {e.name} differs from the host library's", file=sys.stderr)
+                sys.exit(1)
+            nn = w.numel()
+            comp["tensors"][e.name] = {"symbols": nn, "range_us": round(k_r * 1e3, 1), "quantize_us": round(k_q * 1e3, 1),
+                                       "encode_us": round(k_e * 1e3, 1)}
+            k_total += k_r + k_q + k_e
+            n_total += nn
+            del w, qd, st_d, off_d
+        # algorithmic bytes: 4 (range) + 4 + 1 (quantise) + 1 + 1 + stream + offsets (encode: two passes over the symbols)
+        comp_bytes = n_total * 11 + sum(e.stream.size + e.offsets.size * 8 for e in encs[: len(specs0)])
+        comp.update({"kernel_ms_per_layer": round(k_total, 4), "symbols_per_s": round(n_total / (k_total * 1e-3), 0),
+                     "algorithmic_GBps": round(comp_bytes / (k_total * 1e-3) / 1e9, 1),
+                     "hbm_frac": round(comp_bytes / (k_total * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "identical_to_host_encoder": True})
+        result["compress_device"] = comp
+        log(f"compression kernels: {k_total:.3f} ms per layer, {n_total / (k_total * 1e-3) / 1e9:.0f} G symbols/s")
+
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)

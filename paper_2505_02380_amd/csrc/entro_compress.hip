@@ -17,8 +17,8 @@
 // position, and the lanes OR their codes into a staging buffer in LDS, whose
 // whole dwords then go to memory in one coalesced store per 64 dwords.
 // Segments are bit-packed back to back, so the first and the last dword of a
-// segment may be shared with its neighbours: those two are OR-ed into the
-// (zeroed) stream atomically, everything between is stored plainly.
+// segment may be shared with its neighbours: those two are zeroed beforehand
+// and OR-ed into atomically, everything between is stored plainly.
 #include "entro.h"
 
 #include <hip/hip_runtime.h>
@@ -32,11 +32,16 @@ namespace {
 
 constexpr int kWG = 256;                       // four wavefronts
 constexpr int kWaves = kWG / 64;
+// The two streaming kernels run one large workgroup per compute unit with many loads in flight per lane:
+// what a workgroup finds goes into a few words of memory by atomics, and those queue up, so the fewer
+// workgroups the better.
+constexpr int kBigWG = 1024;
+constexpr int kBigWaves = kBigWG / 64;
 constexpr int kHistCopies = 8;                 // counters per bin and wave, picked by lane: spreads the hits on the few frequent symbols
+constexpr int kPrefetch = 8;                   // dwords of symbols a lane requests together
 constexpr uint32_t kFlagSymbol = 1u;           // a symbol without a code (or >= 2^bits)
 constexpr uint32_t kFlagCapacity = 2u;         // the stream does not fit stream_cap
 constexpr uint32_t kFlagSize = 4u;             // the stream would reach 4 GiB
-constexpr int kStageDwords = 264;              // 31 carried bits + 256 codes of up to 32 bits, and the dword behind them
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -50,7 +55,7 @@ bool hip_ok(hipError_t e, const char *what) {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Number of workgroups for a grid-stride kernel over `items` work items of one thread each.
-unsigned grid_for(uint64_t items, unsigned per_cu) {
+unsigned grid_for(uint64_t items, unsigned per_cu, unsigned wg = kWG) {
     thread_local int cached_dev = -1, cached_cus = 0;
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return 0;
@@ -60,7 +65,7 @@ unsigned grid_for(uint64_t items, unsigned per_cu) {
         cached_dev = dev;
         cached_cus = n;
     }
-    const uint64_t want = (items + kWG - 1) / kWG;
+    const uint64_t want = (items + wg - 1) / wg;
     const uint64_t cap = static_cast<uint64_t>(cached_cus) * per_cu;
     const uint64_t g = want < cap ? want : cap;
     return static_cast<unsigned>(g ? g : 1);
@@ -88,10 +93,11 @@ __global__ void k_range_init(uint32_t *r) {
     r[3] = 0u;
 }
 
-__global__ __launch_bounds__(kWG) void k_range(const float *__restrict__ w, uint64_t n, uint32_t *__restrict__ r) {
+__global__ __launch_bounds__(kBigWG) void k_range(const float *__restrict__ w, uint64_t n, uint32_t *__restrict__ r) {
+    constexpr int kLoads = 8;                            // loads in flight per lane
     const uint64_t n4 = n >> 2;
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWG;
-    const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x;
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kBigWG;
+    const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * kBigWG + threadIdx.x;
     float lo = __uint_as_float(0x7f800000u), hi = __uint_as_float(0xff800000u);
     uint32_t bad = 0;
     auto take = [&](float v) {
@@ -101,12 +107,14 @@ __global__ __launch_bounds__(kWG) void k_range(const float *__restrict__ w, uint
     };
     const f32x4 *w4 = reinterpret_cast<const f32x4 *>(w);
     uint64_t i = gid;
-    for (; i + 3 * stride < n4; i += 4 * stride) {          // four loads in flight per lane
-        const f32x4 a = w4[i], b = w4[i + stride], c = w4[i + 2 * stride], d = w4[i + 3 * stride];
-        take(a.x); take(a.y); take(a.z); take(a.w);
-        take(b.x); take(b.y); take(b.z); take(b.w);
-        take(c.x); take(c.y); take(c.z); take(c.w);
-        take(d.x); take(d.y); take(d.z); take(d.w);
+    for (; i + (kLoads - 1) * stride < n4; i += kLoads * stride) {
+        f32x4 v[kLoads];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) v[j] = w4[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            take(v[j].x); take(v[j].y); take(v[j].z); take(v[j].w);
+        }
     }
     for (; i < n4; i += stride) {
         const f32x4 a = w4[i];
@@ -120,10 +128,26 @@ __global__ __launch_bounds__(kWG) void k_range(const float *__restrict__ w, uint
         hi = h2 > hi ? h2 : hi;
         bad |= __shfl_xor(bad, m, 64);
     }
+    __shared__ float wlo[kBigWaves], whi[kBigWaves];
+    __shared__ uint32_t wbad[kBigWaves];
     if ((threadIdx.x & 63u) == 0) {
-        // a lane that saw nothing still holds +Inf / -Inf, which lose against every finite value
-        atomicMin(&r[0], order_key(lo));
-        atomicMax(&r[1], order_key(hi));
+        wlo[threadIdx.x >> 6] = lo;
+        whi[threadIdx.x >> 6] = hi;
+        wbad[threadIdx.x >> 6] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int wv = 1; wv < kBigWaves; ++wv) {
+            lo = wlo[wv] < lo ? wlo[wv] : lo;
+            hi = whi[wv] > hi ? whi[wv] : hi;
+            bad |= wbad[wv];
+        }
+        // a workgroup that saw nothing still holds +Inf / -Inf, which lose against every finite value;
+        // only a workgroup that improves on what is there already (the values only ever move one way)
+        // sends an atomic
+        const uint32_t klo = order_key(lo), khi = order_key(hi);
+        if (klo < __hip_atomic_load(&r[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(&r[0], klo);
+        if (khi > __hip_atomic_load(&r[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(&r[1], khi);
         if (bad) atomicOr(&r[2], 1u);
     }
 }
@@ -147,16 +171,18 @@ __device__ __forceinline__ uint32_t quantize_one(float v, float s, int32_t z, in
     return static_cast<uint32_t>(q);
 }
 
-__global__ __launch_bounds__(kWG) void k_quantize(const float *__restrict__ w, uint64_t n, float s, int32_t z, int32_t Q,
-                                                  uint8_t *__restrict__ q, unsigned long long *__restrict__ counts) {
-    // hist[wave][bin][copy]: the copies of a bin lie in neighbouring banks
-    __shared__ uint32_t hist[kWaves * 256 * kHistCopies];
-    for (int i = threadIdx.x; i < kWaves * 256 * kHistCopies; i += kWG) hist[i] = 0;
+constexpr int kHistSets = 4;                     // histograms per workgroup, picked by wave
+__global__ __launch_bounds__(kBigWG) void k_quantize(const float *__restrict__ w, uint64_t n, float s, int32_t z, int32_t Q,
+                                                     uint8_t *__restrict__ q, unsigned long long *__restrict__ counts) {
+    constexpr int kLoads = 4;                            // loads in flight per lane
+    // hist[set][bin][copy]: the copies of a bin lie in neighbouring banks
+    __shared__ uint32_t hist[kHistSets * 256 * kHistCopies];
+    for (int i = threadIdx.x; i < kHistSets * 256 * kHistCopies; i += kBigWG) hist[i] = 0;
     __syncthreads();
-    uint32_t *mine = hist + (threadIdx.x >> 6) * (256 * kHistCopies) + (threadIdx.x & (kHistCopies - 1));
+    uint32_t *mine = hist + ((threadIdx.x >> 6) & (kHistSets - 1)) * (256 * kHistCopies) + (threadIdx.x & (kHistCopies - 1));
     const uint64_t n4 = n >> 2;
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWG;
-    const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x;
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kBigWG;
+    const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * kBigWG + threadIdx.x;
     const f32x4 *w4 = reinterpret_cast<const f32x4 *>(w);
     uint32_t *q4 = reinterpret_cast<uint32_t *>(q);
     auto four = [&](const f32x4 v) {
@@ -169,10 +195,12 @@ __global__ __launch_bounds__(kWG) void k_quantize(const float *__restrict__ w, u
         return a | (b << 8) | (c << 16) | (d << 24);
     };
     uint64_t i = gid;
-    for (; i + stride < n4; i += 2 * stride) {               // two loads in flight per lane
-        const f32x4 a = w4[i], b = w4[i + stride];
-        q4[i] = four(a);
-        q4[i + stride] = four(b);
+    for (; i + (kLoads - 1) * stride < n4; i += kLoads * stride) {
+        f32x4 v[kLoads];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) v[j] = w4[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) q4[i + j * stride] = four(v[j]);
     }
     for (; i < n4; i += stride) q4[i] = four(w4[i]);
     if (gid < (n & 3u)) {
@@ -181,11 +209,12 @@ __global__ __launch_bounds__(kWG) void k_quantize(const float *__restrict__ w, u
         atomicAdd(&mine[a * kHistCopies], 1u);
     }
     __syncthreads();
-    // thread t owns bin t
-    uint32_t sum = 0;
-    for (int wv = 0; wv < kWaves; ++wv)
-        for (int c = 0; c < kHistCopies; ++c) sum += hist[wv * (256 * kHistCopies) + threadIdx.x * kHistCopies + c];
-    if (sum) atomicAdd(&counts[threadIdx.x], static_cast<unsigned long long>(sum));
+    if (threadIdx.x < 256) {                             // thread t owns bin t
+        unsigned long long sum = 0;                      // a counter stays below 2^32 for tensors of up to 2^44 symbols
+        for (int st = 0; st < kHistSets; ++st)
+            for (int c = 0; c < kHistCopies; ++c) sum += hist[st * (256 * kHistCopies) + threadIdx.x * kHistCopies + c];
+        if (sum) atomicAdd(&counts[threadIdx.x], sum);
+    }
 }
 
 // ------------------------------------------------------------------ encode
@@ -211,17 +240,27 @@ __global__ __launch_bounds__(kWG) void k_segment_bits(const uint8_t *__restrict_
         const uint64_t b1 = b0 + chunk_symbols < n ? b0 + chunk_symbols : n;
         // the aligned dwords that hold the segment's bytes; bytes of a dword outside [b0, b1) are skipped
         // (a dword with one byte inside the buffer lies inside the buffer's pages as a whole)
-        const uint64_t d1 = (b1 + 3) >> 2;
+        const uint32_t skew = static_cast<uint32_t>(b0 & 3u);       // bytes of the first dword that are not the segment's
+        const uint32_t nsym = static_cast<uint32_t>(b1 - b0);
+        const uint32_t nd = (skew + nsym + 3u) >> 2;
+        const uint32_t *src = q32 + (b0 >> 2);
         uint32_t sum = 0, miss = 0;
-        for (uint64_t d = (b0 >> 2) + lane; d < d1; d += 64) {
-            const uint32_t word = q32[d];
+        for (uint32_t dd = 0; dd < nd; dd += 64 * kPrefetch) {
+            uint32_t words[kPrefetch];
 #pragma unroll
-            for (uint32_t j = 0; j < 4; ++j) {
-                const uint64_t idx = (d << 2) + j;
-                if (idx >= b0 && idx < b1) {
-                    const uint32_t l = len[(word >> (8 * j)) & 0xffu];
-                    sum += l;
-                    miss |= l == 0 ? 1u : 0u;
+            for (int r = 0; r < kPrefetch; ++r) {
+                const uint32_t ld = dd + 64u * r + lane;
+                words[r] = ld < nd ? src[ld] : 0u;
+            }
+#pragma unroll
+            for (int r = 0; r < kPrefetch; ++r) {
+                const uint32_t rel = 4u * (dd + 64u * r + lane) - skew;   // wraps for the skipped bytes: not < nsym
+#pragma unroll
+                for (uint32_t j = 0; j < 4; ++j) {
+                    const uint32_t l = len[(words[r] >> (8 * j)) & 0xffu];
+                    const bool in = rel + j < nsym;
+                    sum += in ? l : 0u;
+                    miss |= (in && l == 0) ? 1u : 0u;
                 }
             }
         }
@@ -289,29 +328,35 @@ __global__ __launch_bounds__(kScanWG) void k_scan_offsets(uint64_t *__restrict__
     }
 }
 
-// Zero the bytes the stream will occupy (the padding included), and no more than stream_cap.
-__global__ __launch_bounds__(kWG) void k_zero_stream(u32x4 *__restrict__ stream, uint64_t stream_cap,
-                                                     const uint64_t *__restrict__ offsets, uint32_t n_chunks,
-                                                     const uint32_t *__restrict__ status) {
+// The stream dwords that are OR-ed into rather than stored: the one every segment starts in (which is
+// also the one the segment before ends in, and for k = n_chunks the stream's last, partial one), and
+// the padding behind the last code.  Everything else is overwritten as whole dwords.
+__global__ __launch_bounds__(kWG) void k_zero_shared_dwords(uint32_t *__restrict__ stream, uint64_t stream_dwords,
+                                                            const uint64_t *__restrict__ offsets, uint32_t n_chunks,
+                                                            const uint32_t *__restrict__ status) {
     if (*status != 0u) return;
-    uint64_t need = padded_bytes(offsets[n_chunks]);
-    need = need < stream_cap ? need : (stream_cap & ~15ull);
-    const uint64_t blocks = need >> 4;
-    const u32x4 zero = {0, 0, 0, 0};
-    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x; i < blocks;
-         i += static_cast<uint64_t>(gridDim.x) * kWG)
-        stream[i] = zero;
+    const uint64_t total = offsets[n_chunks];
+    const uint64_t pad0 = total >> 5, pad1 = padded_bytes(total) >> 2;       // the last partial dword and the padding
+    const uint64_t items = static_cast<uint64_t>(n_chunks) + (pad1 - pad0);
+    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x; i < items;
+         i += static_cast<uint64_t>(gridDim.x) * kWG) {
+        const uint64_t g = i < n_chunks ? offsets[i] >> 5 : pad0 + (i - n_chunks);
+        if (g < stream_dwords) stream[g] = 0u;
+    }
 }
 
-// One wavefront writes one segment.
+// One wavefront writes one segment.  The stage is a ring of dwords addressed by the bit position
+// counted from the start of the stream dword the segment begins in; a round adds at most 256 codes
+// of 32 bits and every round's whole dwords leave at once, so 512 dwords never wrap onto live ones.
+constexpr int kStageRing = 512;
 __global__ __launch_bounds__(kWG) void k_write_segments(const uint8_t *__restrict__ q, uint64_t n, uint32_t chunk_symbols,
                                                         uint32_t n_chunks, const EncTable tab,
                                                         const uint64_t *__restrict__ offsets, uint32_t *__restrict__ stream,
                                                         uint64_t stream_dwords, const uint32_t *__restrict__ status) {
     __shared__ uint64_t entry[256];                      // rev | len << 32
-    __shared__ uint32_t stage_all[kWaves][kStageDwords];
+    __shared__ uint32_t stage_all[kWaves][kStageRing];
     entry[threadIdx.x] = tab.rev[threadIdx.x] | (static_cast<uint64_t>(tab.len[threadIdx.x]) << 32);
-    for (int i = threadIdx.x; i < kWaves * kStageDwords; i += kWG) (&stage_all[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < kWaves * kStageRing; i += kWG) (&stage_all[0][0])[i] = 0;
     __syncthreads();
     if (*status != 0u) return;                           // a symbol without a code, or no room: nothing is written
     const uint32_t lane = threadIdx.x & 63u;
@@ -321,69 +366,96 @@ __global__ __launch_bounds__(kWG) void k_write_segments(const uint8_t *__restric
          k += static_cast<uint64_t>(gridDim.x) * kWaves) {
         const uint64_t b0 = k * chunk_symbols;
         const uint64_t b1 = b0 + chunk_symbols < n ? b0 + chunk_symbols : n;
-        const uint64_t d1 = (b1 + 3) >> 2;
+        const uint32_t skew = static_cast<uint32_t>(b0 & 3u);       // bytes of the first dword that are not the segment's
+        const uint32_t nsym = static_cast<uint32_t>(b1 - b0);
+        const uint32_t nd = (skew + nsym + 3u) >> 2;
+        const uint32_t *src = q32 + (b0 >> 2);
         const uint64_t start = offsets[k];
-        const uint64_t first_g = start >> 5;             // the stream dword the segment starts in
-        uint64_t g = first_g;                            // where stage[0] goes
-        uint32_t fill = static_cast<uint32_t>(start & 31u);   // bits in the stage, counted from bit 0 of stage[0]
-        for (uint64_t d0 = b0 >> 2; d0 < d1; d0 += 64) {
-            const uint64_t d = d0 + lane;
-            const uint32_t word = d < d1 ? q32[d] : 0u;
-            uint32_t rev[4], len[4], tot = 0;
-#pragma unroll
-            for (uint32_t j = 0; j < 4; ++j) {
-                const uint64_t idx = (d << 2) + j;
-                const uint64_t e = entry[(word >> (8 * j)) & 0xffu];
-                const bool in = d < d1 && idx >= b0 && idx < b1;
-                rev[j] = static_cast<uint32_t>(e);
-                len[j] = in ? static_cast<uint32_t>(e >> 32) : 0u;
-                tot += len[j];
+        uint32_t *const out = stream + (start >> 5);     // the stream dword the segment starts in
+        const uint64_t room = stream_dwords > (start >> 5) ? stream_dwords - (start >> 5) : 0;   // dwords up to the end of the buffer
+        uint32_t fill = static_cast<uint32_t>(start & 31u);   // bits written, counted from bit 0 of that dword
+        uint32_t done = 0;                               // dwords that have left the stage
+        // dword i of the segment leaves the stage; the first one may hold the end of the segment before
+        auto emit = [&](uint32_t i) {
+            const uint32_t v = stage[i & (kStageRing - 1)];
+            stage[i & (kStageRing - 1)] = 0;
+            if (i < room) {
+                if (i == 0) atomicOr(out, v);
+                else out[i] = v;
             }
-            uint32_t x = tot;                            // inclusive prefix sum over the lanes
+        };
+        for (uint32_t dd = 0; dd < nd; dd += 64 * kPrefetch) {
+            uint32_t words[kPrefetch];
 #pragma unroll
-            for (int m = 1; m < 64; m <<= 1) {
-                const uint32_t y = __shfl_up(x, m, 64);
-                if (lane >= static_cast<uint32_t>(m)) x += y;
+            for (int r = 0; r < kPrefetch; ++r) {
+                const uint32_t ld = dd + 64u * r + lane;
+                words[r] = ld < nd ? src[ld] : 0u;
             }
-            const uint32_t round_bits = __shfl(x, 63, 64);
-            uint32_t p = fill + x - tot;
 #pragma unroll
-            for (uint32_t j = 0; j < 4; ++j) {
-                if (len[j]) {
-                    const uint32_t sh = p & 31u;
-                    const uint64_t v = static_cast<uint64_t>(rev[j]) << sh;
-                    atomicOr(&stage[p >> 5], static_cast<uint32_t>(v));
-                    if (sh + len[j] > 32u) atomicOr(&stage[(p >> 5) + 1], static_cast<uint32_t>(v >> 32));
-                    p += len[j];
+            for (int r = 0; r < kPrefetch; ++r) {
+                if (dd + 64u * r >= nd) break;           // the same for all lanes
+                const uint32_t word = words[r];
+                const uint32_t rel = 4u * (dd + 64u * r + lane) - skew;   // wraps for the skipped bytes: not < nsym
+                // the lane's four codes, strung together in stream order: up to 128 bits in c[0..3];
+                // a symbol that is not this segment's counts as no bits
+                uint64_t pair[2];
+                uint32_t plen[2];
+#pragma unroll
+                for (uint32_t h = 0; h < 2; ++h) {
+                    const uint64_t e0 = entry[(word >> (16 * h)) & 0xffu], e1 = entry[(word >> (16 * h + 8)) & 0xffu];
+                    const bool in0 = rel + 2 * h < nsym, in1 = rel + 2 * h + 1 < nsym;
+                    const uint32_t l0 = in0 ? static_cast<uint32_t>(e0 >> 32) : 0u, l1 = in1 ? static_cast<uint32_t>(e1 >> 32) : 0u;
+                    const uint32_t r0 = in0 ? static_cast<uint32_t>(e0) : 0u, r1 = in1 ? static_cast<uint32_t>(e1) : 0u;
+                    pair[h] = r0 | (static_cast<uint64_t>(r1) << l0);          // l0 <= 32
+                    plen[h] = l0 + l1;
                 }
+                const uint32_t tot = plen[0] + plen[1];
+                const uint64_t lo = pair[0] | (plen[0] == 64u ? 0ull : pair[1] << (plen[0] & 63u));
+                const uint64_t hi = plen[0] ? pair[1] >> ((64u - plen[0]) & 63u) : 0ull;
+                const uint32_t c[4] = {static_cast<uint32_t>(lo), static_cast<uint32_t>(lo >> 32), static_cast<uint32_t>(hi),
+                                       static_cast<uint32_t>(hi >> 32)};
+                // inclusive prefix sum of the lanes' bit counts: within rows of 16 lanes by DPP shifts (a lane
+                // without a source adds 0), then the three row totals in front of a row are added
+                uint32_t x = tot;
+                x += __builtin_amdgcn_update_dpp(0u, x, 0x111, 0xf, 0xf, true);    // row_shr:1
+                x += __builtin_amdgcn_update_dpp(0u, x, 0x112, 0xf, 0xf, true);    // row_shr:2
+                x += __builtin_amdgcn_update_dpp(0u, x, 0x114, 0xf, 0xf, true);    // row_shr:4
+                x += __builtin_amdgcn_update_dpp(0u, x, 0x118, 0xf, 0xf, true);    // row_shr:8
+                const uint32_t t0 = __builtin_amdgcn_readlane(x, 15), t1 = __builtin_amdgcn_readlane(x, 31),
+                               t2 = __builtin_amdgcn_readlane(x, 47), t3 = __builtin_amdgcn_readlane(x, 63);
+                x += (lane >= 16 ? t0 : 0u) + (lane >= 32 ? t1 : 0u) + (lane >= 48 ? t2 : 0u);
+                const uint32_t round_bits = t0 + t1 + t2 + t3;
+                // shifted to its place in the stage the string covers up to five dwords; the first two are
+                // OR-ed in by every lane (zeros do no harm), the others only where a lane reaches them
+                const uint32_t p = fill + x - tot;
+                const uint32_t sh = p & 31u, at = p >> 5;
+#pragma unroll
+                for (uint32_t i = 0; i < 5; ++i) {
+                    const uint32_t up = i < 4 ? c[i < 4 ? i : 0] : 0u, down = i ? c[i ? i - 1 : 0] : 0u;
+                    // ({up, down} << sh) >> 32
+                    const uint32_t v = sh ? __builtin_amdgcn_alignbit(up, down, 32u - sh) : up;
+                    if (i < 2 || sh + tot > 32u * i) atomicOr(&stage[(at + i) & (kStageRing - 1)], v);
+                }
+                fill += round_bits;
+                wave_sync_lds();
+                // whole dwords leave 64 at a time
+                while ((fill >> 5) - done >= 64u) {
+                    emit(done + lane);
+                    done += 64u;
+                }
+                wave_sync_lds();
             }
-            fill += round_bits;
-            wave_sync_lds();
-            // the whole dwords go out; the segment's first dword may hold the end of the segment before
+        }
+        {
             const uint32_t full = fill >> 5;
-            for (uint32_t i = lane; i < full; i += 64) {
-                const uint32_t v = stage[i];
-                stage[i] = 0;
-                if (g + i < stream_dwords) {
-                    if (g + i == first_g) atomicOr(&stream[g + i], v);
-                    else stream[g + i] = v;
-                }
-            }
-            wave_sync_lds();
-            if (full && lane == 0) {
-                const uint32_t c = stage[full];
-                stage[full] = 0;
-                stage[0] = c;
-            }
-            wave_sync_lds();
-            g += full;
-            fill &= 31u;
+            if (done + lane < full) emit(done + lane);
+            done = full;
         }
         // what is left is shared with the next segment
-        if (lane == 0 && fill) {
-            const uint32_t c = stage[0];
-            stage[0] = 0;
-            if (g < stream_dwords) atomicOr(&stream[g], c);
+        if (lane == 0 && (fill & 31u)) {
+            const uint32_t c = stage[done & (kStageRing - 1)];
+            stage[done & (kStageRing - 1)] = 0;
+            if (done < room) atomicOr(out + done, c);
         }
         wave_sync_lds();
     }
@@ -412,11 +484,11 @@ entro_status entro_range_device(const float *w, uint64_t n, void *range16, void 
     if (n == 0) return ENTRO_ERR_SIZE;
     if (!aligned16(w) || !aligned16(range16)) return ENTRO_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const unsigned grid = grid_for((n + 3) / 4, 8);
+    const unsigned grid = grid_for((n + 3) / 4, 1, kBigWG);
     if (!grid) return ENTRO_ERR_DEVICE;
     uint32_t *r = static_cast<uint32_t *>(range16);
     hipLaunchKernelGGL(k_range_init, dim3(1), dim3(1), 0, st, r);
-    hipLaunchKernelGGL(k_range, dim3(grid), dim3(kWG), 0, st, w, n, r);
+    hipLaunchKernelGGL(k_range, dim3(grid), dim3(kBigWG), 0, st, w, n, r);
     hipLaunchKernelGGL(k_range_finish, dim3(1), dim3(1), 0, st, r);
     return hip_ok(hipGetLastError(), "entro_range_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;
 }
@@ -431,11 +503,11 @@ entro_status entro_quantize_device(const float *w, uint64_t n, const entro_qpara
     if (qp->zero_point > (1 << 24) || qp->zero_point < -(1 << 24)) return ENTRO_ERR_RANGE;
     if (!aligned16(w) || !aligned16(q) || !aligned16(counts)) return ENTRO_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const unsigned grid = grid_for((n + 3) / 4, 4);
+    const unsigned grid = grid_for((n + 3) / 4, 1, kBigWG);
     if (!grid) return ENTRO_ERR_DEVICE;
     unsigned long long *c = reinterpret_cast<unsigned long long *>(counts);
     hipLaunchKernelGGL(k_zero_counts, dim3(1), dim3(256), 0, st, c);
-    hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kWG), 0, st, w, n, qp->scale, qp->zero_point, (1 << qp->bits) - 1, q, c);
+    hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kBigWG), 0, st, w, n, qp->scale, qp->zero_point, (1 << qp->bits) - 1, q, c);
     return hip_ok(hipGetLastError(), "entro_quantize_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;
 }
 
@@ -461,13 +533,14 @@ entro_status entro_encode_device(const uint8_t *q, uint64_t n, const entro_codeb
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const EncTable tab = make_table(cb);
     const unsigned grid = grid_for(n_chunks * 64, 8);
-    const unsigned zgrid = grid_for(stream_cap / 16, 8);
+    const unsigned zgrid = grid_for(n_chunks + 16, 8);
     if (!grid || !zgrid) return ENTRO_ERR_DEVICE;
     const uint32_t nc = static_cast<uint32_t>(n_chunks);
     hipLaunchKernelGGL(k_encode_init, dim3(1), dim3(1), 0, st, status);
     hipLaunchKernelGGL(k_segment_bits, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets, status);
     hipLaunchKernelGGL(k_scan_offsets, dim3(1), dim3(kScanWG), 0, st, offsets, nc, stream_cap, status);
-    hipLaunchKernelGGL(k_zero_stream, dim3(zgrid), dim3(kWG), 0, st, static_cast<u32x4 *>(stream), stream_cap, offsets, nc, status);
+    hipLaunchKernelGGL(k_zero_shared_dwords, dim3(zgrid), dim3(kWG), 0, st, static_cast<uint32_t *>(stream), stream_cap / 4, offsets,
+                       nc, status);
     hipLaunchKernelGGL(k_write_segments, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets,
                        static_cast<uint32_t *>(stream), stream_cap / 4, status);
     return hip_ok(hipGetLastError(), "entro_encode_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;
