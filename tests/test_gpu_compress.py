@@ -207,3 +207,19 @@ def test_compress_then_decode_on_the_device(bits, scheme, max_len):
     out = torch.zeros(w.size, dtype=torch.float32, device=DEV)
     E.entro_decode_dequant(dt.ctensor(out), E.ENTRO_F32)
     assert np.array_equal(out.cpu().numpy(), oracle.dequant_f32(q_ref, s_ref, z_ref))
+
+
+def test_compress_a_full_size_tensor_of_the_headline_set():
+    # L0.q of the mistral-7B-shaped set (4096 x 4096, 4096 segments): every byte against the oracle's chain
+    spec = synth.config_tensors(4, layers=1)[0]
+    w = synth.make_tensor(spec).ravel()
+    q_ref, s_ref, z_ref = oracle.quantize(w, 8, 1)
+    dt, q = E.compress_on_device(torch.from_numpy(w).to(DEV), 8, E.ENTRO_ASYMMETRIC, 4096, return_q=True)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.float32(dt.enc.qp.scale) == s_ref and dt.enc.qp.zero_point == z_ref
+    ln = dt.enc.cb.lengths()
+    cnt = oracle.histogram(q_ref, 8)
+    assert int(np.sum(cnt * ln.astype(np.uint64))) == int(np.sum(cnt * oracle.huffman_lengths(cnt).astype(np.uint64)))
+    ref_stream, ref_off = oracle.encode(q_ref, ln, oracle.canonical_codes(ln), 4096)
+    assert np.array_equal(dt.offsets.cpu().numpy().view(np.uint64), ref_off)
+    assert np.array_equal(dt.stream.cpu().numpy(), ref_stream)
