@@ -263,6 +263,13 @@ entro_status entro_range_device(const float *w, uint64_t n, void *range16, void 
 entro_status entro_qparams_from_range(float min, float max, uint32_t nonfinite, int bits, entro_scheme scheme,
                                       entro_qparams *qp);
 
+/* Host: which of the two grids of Fig. 2 a tensor with this range gets under the
+ * mixed scheme ("either unsigned or asymmetric per layer, based on its weight
+ * distribution"; the paper states no rule): the unsigned grid, which has no
+ * zero-point, exactly when it can represent the tensor, i.e. when no weight is
+ * negative (norm gains, for instance); the asymmetric grid otherwise. */
+entro_scheme entro_scheme_for_range(float min, float max);
+
 /* q[i] = clamp(rint(w[i] / s) + z, 0, 2^bits - 1), one symbol per byte, and the
  * histogram of the symbols.  w: device, n floats; q: device, n bytes; counts:
  * device, 256 entries, overwritten (entries at and above 2^bits end up 0); all

@@ -104,6 +104,7 @@ def lib():
         "entro_stream_probe": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
         "entro_range_device": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
         "entro_qparams_from_range": (C.c_int, [C.c_float, C.c_float, C.c_uint32, C.c_int, C.c_int, C.POINTER(QParams)]),
+        "entro_scheme_for_range": (C.c_int, [C.c_float, C.c_float]),
         "entro_quantize_device": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(QParams), C.c_void_p, C.c_void_p, C.c_void_p]),
         "entro_encoded_bytes": (C.c_uint64, [u64p, cbp]),
         "entro_encode_device": (C.c_int, [C.c_void_p, C.c_uint64, cbp, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
@@ -124,7 +125,7 @@ EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_count
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
-            "entro_stream_probe", "entro_range_device", "entro_qparams_from_range", "entro_quantize_device",
+            "entro_stream_probe", "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
             "entro_encoded_bytes", "entro_encode_device", "entro_encode_device_status"]
 
 
@@ -372,6 +373,10 @@ def entro_qparams_from_range(mn: float, mx: float, nonfinite: int, bits: int, sc
     return qp
 
 
+def entro_scheme_for_range(mn: float, mx: float) -> int:
+    return int(lib().entro_scheme_for_range(mn, mx))
+
+
 def entro_quantize_device(w, qp: QParams, q, counts, stream=None):
     """q (uint8 device tensor, w.numel() bytes) and counts (int64 device tensor of 256) from w and qp."""
     _check(lib().entro_quantize_device(w.data_ptr(), w.numel(), C.byref(qp), q.data_ptr(), counts.data_ptr(),
@@ -394,12 +399,13 @@ def entro_encode_device_status(word: int) -> int:
     return int(lib().entro_encode_device_status(int(word) & 0xFFFFFFFF))
 
 
-def compress_on_device(w, bits: int, scheme: int, chunk_symbols: int, rows: int = 0, cols: int = 0, name: str = "",
+def compress_on_device(w, bits: int, scheme: Optional[int], chunk_symbols: int, rows: int = 0, cols: int = 0, name: str = "",
                        max_len: int = 0, return_q: bool = False):
     """Range -> (s, z) -> quantise + count -> codebook -> encode for a float32 tensor that lives on the GPU.
 
     The three passes over the weights are kernels; the two small steps between them run in the host
-    library on the 16 and 2048 bytes copied back.  Returns a DeviceTensor ready for the decode calls.
+    library on the 16 and 2048 bytes copied back.  scheme None: entro_scheme_for_range picks the grid.
+    Returns a DeviceTensor ready for the decode calls.
     """
     import torch
     w = w.reshape(-1)
@@ -409,6 +415,8 @@ def compress_on_device(w, bits: int, scheme: int, chunk_symbols: int, rows: int 
     entro_range_device(w, small)
     r = small[:4].cpu().numpy()
     mn, mx = r[:2].view(np.float32)
+    if scheme is None:
+        scheme = entro_scheme_for_range(float(mn), float(mx))
     qp = entro_qparams_from_range(float(mn), float(mx), int(r[2]), bits, scheme)
     q = torch.empty(w.numel(), dtype=torch.uint8, device=dev)
     entro_quantize_device(w, qp, q, counts)

@@ -39,6 +39,7 @@ constexpr int kBigWG = 1024;
 constexpr int kBigWaves = kBigWG / 64;
 constexpr int kHistCopies = 8;                 // counters per bin and wave, picked by lane: spreads the hits on the few frequent symbols
 constexpr int kPrefetch = 8;                   // dwords of symbols a lane requests together
+constexpr uint64_t kMissBit = 1ull << 63;       // in a segment's bit count: it holds a symbol without a code
 constexpr uint32_t kFlagSymbol = 1u;           // a symbol without a code (or >= 2^bits)
 constexpr uint32_t kFlagCapacity = 2u;         // the stream does not fit stream_cap
 constexpr uint32_t kFlagSize = 4u;             // the stream would reach 4 GiB
@@ -223,12 +224,9 @@ struct EncTable {
     uint8_t len[256];     // 0: no code
 };
 
-__global__ void k_encode_init(uint32_t *status) { *status = 0u; }
-
 // Bits of every segment, into offsets[k + 1]; one wavefront per segment.
 __global__ __launch_bounds__(kWG) void k_segment_bits(const uint8_t *__restrict__ q, uint64_t n, uint32_t chunk_symbols,
-                                                      uint32_t n_chunks, const EncTable tab, uint64_t *__restrict__ offsets,
-                                                      uint32_t *__restrict__ status) {
+                                                      uint32_t n_chunks, const EncTable tab, uint64_t *__restrict__ offsets) {
     __shared__ uint8_t len[256];
     len[threadIdx.x] = tab.len[threadIdx.x];
     __syncthreads();
@@ -269,10 +267,7 @@ __global__ __launch_bounds__(kWG) void k_segment_bits(const uint8_t *__restrict_
             sum += __shfl_xor(sum, m, 64);
             miss |= __shfl_xor(miss, m, 64);
         }
-        if (lane == 0) {
-            offsets[k + 1] = sum;
-            if (miss) atomicOr(status, kFlagSymbol);
-        }
+        if (lane == 0) offsets[k + 1] = sum | (miss ? kMissBit : 0ull);
     }
 }
 
@@ -282,28 +277,41 @@ __device__ __forceinline__ uint64_t padded_bytes(uint64_t total_bits) {
     return b + 16;
 }
 
-// offsets[k + 1] holds segment k's bits on entry and the stream bit behind segment k on exit.
-// One workgroup walks the table in tiles of four entries per thread.
+// offsets[k + 1] holds segment k's bits on entry (bit 63 set: it has a symbol without a code) and the
+// stream bit behind segment k on exit.  One workgroup walks the table in tiles of eight entries per
+// thread, sets the status word, and, if all is well, clears the stream dwords that are OR-ed into
+// rather than stored: the one every segment starts in (which is also the one the segment before ends
+// in, and for k = n_chunks the stream's last, partial one) and the padding behind the last code.
+// Everything else is overwritten as whole dwords.  (zero_here false: the table is long, and a kernel
+// of many workgroups clears them instead; one workgroup's scattered stores take too long then.)
 constexpr int kScanWG = 1024;
-__global__ __launch_bounds__(kScanWG) void k_scan_offsets(uint64_t *__restrict__ offsets, uint32_t n_chunks, uint64_t stream_cap,
-                                                          uint32_t *__restrict__ status) {
+constexpr int kScanPer = 8;                  // table entries per thread and tile
+__global__ __launch_bounds__(kScanWG) void k_scan_offsets(uint64_t *__restrict__ offsets, uint32_t n_chunks,
+                                                          uint32_t *__restrict__ stream, uint64_t stream_cap,
+                                                          uint32_t *__restrict__ status, bool zero_here) {
     __shared__ uint64_t wave_sum[kScanWG / 64];
     __shared__ uint64_t carry_s;
+    __shared__ uint32_t flags_s;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) {
         offsets[0] = 0;
         carry_s = 0;
+        flags_s = 0;
     }
     __syncthreads();
-    for (uint64_t base = 0; base < n_chunks; base += 4 * kScanWG) {
-        const uint64_t at = base + 4ull * threadIdx.x;
-        uint64_t v[4];
+    bool miss = false;
+    for (uint64_t base = 0; base < n_chunks; base += kScanPer * kScanWG) {
+        const uint64_t at = base + static_cast<uint64_t>(kScanPer) * threadIdx.x;
+        uint64_t v[kScanPer];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = at + j < n_chunks ? offsets[at + j + 1] : 0;
-        v[1] += v[0];
-        v[2] += v[1];
-        v[3] += v[2];
-        uint64_t x = v[3];
+        for (int j = 0; j < kScanPer; ++j) {
+            v[j] = at + j < n_chunks ? offsets[at + j + 1] : 0;
+            miss |= (v[j] & kMissBit) != 0;
+            v[j] &= ~kMissBit;
+        }
+#pragma unroll
+        for (int j = 1; j < kScanPer; ++j) v[j] += v[j - 1];
+        uint64_t x = v[kScanPer - 1];
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) {
             const uint64_t y = __shfl_up(x, m, 64);
@@ -313,36 +321,47 @@ __global__ __launch_bounds__(kScanWG) void k_scan_offsets(uint64_t *__restrict__
         __syncthreads();
         uint64_t before = carry_s;
         for (uint32_t wv = 0; wv < wave; ++wv) before += wave_sum[wv];
-        before += x - v[3];
+        before += x - v[kScanPer - 1];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kScanPer; ++j)
             if (at + j < n_chunks) offsets[at + j + 1] = before + v[j];
         __syncthreads();
-        if (threadIdx.x == kScanWG - 1) carry_s = before + v[3];
+        if (threadIdx.x == kScanWG - 1) carry_s = before + v[kScanPer - 1];
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        const uint64_t need = padded_bytes(carry_s);
-        if (need > stream_cap) atomicOr(status, kFlagCapacity);
-        if (need >= (1ull << 32)) atomicOr(status, kFlagSize);
+    if (miss) atomicOr(&flags_s, kFlagSymbol);
+    __syncthreads();                                     // also: the offsets written above are visible to the whole workgroup
+    const uint64_t total = carry_s;
+    const uint64_t need = padded_bytes(total);
+    uint32_t flags = flags_s;
+    if (need > stream_cap) flags |= kFlagCapacity;
+    if (need >= (1ull << 32)) flags |= kFlagSize;
+    if (threadIdx.x == 0) *status = flags;
+    if (flags || !zero_here) return;
+    const uint64_t pad0 = total >> 5, pad1 = need >> 2;  // the last partial dword and the padding
+    const uint64_t items = static_cast<uint64_t>(n_chunks) + (pad1 - pad0);
+    for (uint64_t base = 0; base < items; base += 8 * kScanWG) {      // eight independent loads per thread and trip
+        uint64_t g[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint64_t i = base + static_cast<uint64_t>(j) * kScanWG + threadIdx.x;
+            g[j] = i < n_chunks ? offsets[i] >> 5 : pad0 + (i - n_chunks);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (base + static_cast<uint64_t>(j) * kScanWG + threadIdx.x < items) stream[g[j]] = 0u;   // g < need / 4 <= stream_cap / 4
     }
 }
 
-// The stream dwords that are OR-ed into rather than stored: the one every segment starts in (which is
-// also the one the segment before ends in, and for k = n_chunks the stream's last, partial one), and
-// the padding behind the last code.  Everything else is overwritten as whole dwords.
-__global__ __launch_bounds__(kWG) void k_zero_shared_dwords(uint32_t *__restrict__ stream, uint64_t stream_dwords,
-                                                            const uint64_t *__restrict__ offsets, uint32_t n_chunks,
-                                                            const uint32_t *__restrict__ status) {
+__global__ __launch_bounds__(kWG) void k_zero_shared_dwords(uint32_t *__restrict__ stream, const uint64_t *__restrict__ offsets,
+                                                            uint32_t n_chunks, const uint32_t *__restrict__ status) {
     if (*status != 0u) return;
     const uint64_t total = offsets[n_chunks];
-    const uint64_t pad0 = total >> 5, pad1 = padded_bytes(total) >> 2;       // the last partial dword and the padding
+    const uint64_t pad0 = total >> 5, pad1 = padded_bytes(total) >> 2;
     const uint64_t items = static_cast<uint64_t>(n_chunks) + (pad1 - pad0);
     for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kWG + threadIdx.x; i < items;
-         i += static_cast<uint64_t>(gridDim.x) * kWG) {
-        const uint64_t g = i < n_chunks ? offsets[i] >> 5 : pad0 + (i - n_chunks);
-        if (g < stream_dwords) stream[g] = 0u;
-    }
+         i += static_cast<uint64_t>(gridDim.x) * kWG)
+        stream[i < n_chunks ? offsets[i] >> 5 : pad0 + (i - n_chunks)] = 0u;     // inside the stream: status 0 says it fits
 }
 
 // One wavefront writes one segment.  The stage is a ring of dwords addressed by the bit position
@@ -533,14 +552,15 @@ entro_status entro_encode_device(const uint8_t *q, uint64_t n, const entro_codeb
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const EncTable tab = make_table(cb);
     const unsigned grid = grid_for(n_chunks * 64, 8);
-    const unsigned zgrid = grid_for(n_chunks + 16, 8);
-    if (!grid || !zgrid) return ENTRO_ERR_DEVICE;
+    if (!grid) return ENTRO_ERR_DEVICE;
     const uint32_t nc = static_cast<uint32_t>(n_chunks);
-    hipLaunchKernelGGL(k_encode_init, dim3(1), dim3(1), 0, st, status);
-    hipLaunchKernelGGL(k_segment_bits, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets, status);
-    hipLaunchKernelGGL(k_scan_offsets, dim3(1), dim3(kScanWG), 0, st, offsets, nc, stream_cap, status);
-    hipLaunchKernelGGL(k_zero_shared_dwords, dim3(zgrid), dim3(kWG), 0, st, static_cast<uint32_t *>(stream), stream_cap / 4, offsets,
-                       nc, status);
+    hipLaunchKernelGGL(k_segment_bits, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets);
+    const bool zero_here = n_chunks <= 2048;
+    hipLaunchKernelGGL(k_scan_offsets, dim3(1), dim3(kScanWG), 0, st, offsets, nc, static_cast<uint32_t *>(stream), stream_cap, status,
+                       zero_here);
+    if (!zero_here)
+        hipLaunchKernelGGL(k_zero_shared_dwords, dim3(grid_for(n_chunks + 16, 8)), dim3(kWG), 0, st, static_cast<uint32_t *>(stream),
+                           offsets, nc, status);
     hipLaunchKernelGGL(k_write_segments, dim3(grid), dim3(kWG), 0, st, q, n, chunk_symbols, nc, tab, offsets,
                        static_cast<uint32_t *>(stream), stream_cap / 4, status);
     return hip_ok(hipGetLastError(), "entro_encode_device") ? ENTRO_OK : ENTRO_ERR_DEVICE;

@@ -254,6 +254,10 @@ uint64_t padded_bytes(uint64_t total_bits) {
 
 extern "C" {
 
+entro_scheme entro_scheme_for_range(float min, float max) {
+    return (min >= 0.0f && max > 0.0f) ? ENTRO_UNSIGNED : ENTRO_ASYMMETRIC;
+}
+
 entro_status entro_qparams_from_range(float min, float max, uint32_t nonfinite, int bits, entro_scheme scheme,
                                       entro_qparams *qp) {
     if (!qp) return ENTRO_ERR_NULL;

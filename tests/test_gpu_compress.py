@@ -223,3 +223,16 @@ def test_compress_a_full_size_tensor_of_the_headline_set():
     ref_stream, ref_off = oracle.encode(q_ref, ln, oracle.canonical_codes(ln), 4096)
     assert np.array_equal(dt.offsets.cpu().numpy().view(np.uint64), ref_off)
     assert np.array_equal(dt.stream.cpu().numpy(), ref_stream)
+
+
+def test_mixed_scheme_picks_the_grid_from_the_range():
+    spec = [t for t in synth.config_tensors(2, layers=1) if t.name == "norm_attn"][0]
+    g = synth.make_tensor(spec).ravel()                   # norm gains in (0.8, 1.2): unsigned grid
+    dt, q = E.compress_on_device(torch.from_numpy(g).to(DEV), 8, None, 4096, return_q=True)
+    assert dt.enc.qp.scheme == E.ENTRO_UNSIGNED and dt.enc.qp.zero_point == 0
+    q_ref, s_ref, _ = oracle.quantize(g, 8, 0)
+    assert np.array_equal(q.cpu().numpy(), q_ref) and np.float32(dt.enc.qp.scale) == s_ref
+    w = synth.make_tensor(synth.config_tensors(1)[0]).ravel()[:100000]
+    dt, q = E.compress_on_device(torch.from_numpy(w).to(DEV), 8, None, 4096, return_q=True)
+    assert dt.enc.qp.scheme == E.ENTRO_ASYMMETRIC
+    assert np.array_equal(q.cpu().numpy(), oracle.quantize(w, 8, 1)[0])

@@ -351,3 +351,17 @@ def test_device_compression_calls_validate_before_touching_the_gpu():
     assert L.entro_encode_device(4096, 64, C.byref(bad), 32, 8192, 64, 12288, 16384, None) == B.ENTRO_ERR_CORRUPT
     assert [E.entro_encode_device_status(v) for v in (0, 1, 2, 4, 3)] == \
         [B.ENTRO_OK, B.ENTRO_ERR_SYMBOL, B.ENTRO_ERR_CAPACITY, B.ENTRO_ERR_SIZE, B.ENTRO_ERR_SYMBOL]
+
+
+def test_scheme_for_range_takes_the_unsigned_grid_only_where_it_can_hold_the_tensor():
+    assert E.entro_scheme_for_range(0.8, 1.2) == E.ENTRO_UNSIGNED          # norm gains
+    assert E.entro_scheme_for_range(0.0, 1.0) == E.ENTRO_UNSIGNED
+    assert E.entro_scheme_for_range(-0.0, 1.0) == E.ENTRO_UNSIGNED
+    assert E.entro_scheme_for_range(-1e-30, 1.0) == E.ENTRO_ASYMMETRIC
+    assert E.entro_scheme_for_range(-3.0, -1.0) == E.ENTRO_ASYMMETRIC
+    # whatever it picks, the quantizer accepts the tensor
+    for w in (np.array([0.8, 1.0, 1.2], np.float32), np.array([-1, 0.5, 2], np.float32)):
+        sch = E.entro_scheme_for_range(float(w.min()), float(w.max()))
+        q, qp = E.entro_quantize(w, 8, sch)
+        qo, s, z = oracle.quantize(w, 8, sch)
+        assert np.array_equal(q, qo) and qp.scheme == sch
