@@ -6,6 +6,8 @@ numbers, the symbols byte for byte, the counts, the offset table and every byte
 of the stream including its padding.  The oracle quantises, counts and encodes
 the same seeded inputs; codebooks come from the oracle's lengths (canonical
 codes are a function of the lengths), never from the device."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -236,3 +238,42 @@ def test_mixed_scheme_picks_the_grid_from_the_range():
     dt, q = E.compress_on_device(torch.from_numpy(w).to(DEV), 8, None, 4096, return_q=True)
     assert dt.enc.qp.scheme == E.ENTRO_ASYMMETRIC
     assert np.array_equal(q.cpu().numpy(), oracle.quantize(w, 8, 1)[0])
+
+
+def test_random_tensors_compress_identically():
+    """Seeded sweep over sizes, segment lengths, value distributions, widths, schemes and code-length
+    limits: range, symbols, counts, offsets and stream of the device chain against the oracle's."""
+    # ENTRO_SWEEP_SEED / ENTRO_SWEEP_CASES widen the sweep for a soak run
+    rng = np.random.default_rng(int(os.environ.get("ENTRO_SWEEP_SEED", "77")))
+    for case in range(int(os.environ.get("ENTRO_SWEEP_CASES", "120"))):
+        bits = 4 if case % 3 == 0 else 8
+        chunk = int(rng.choice([1, 7, 64, 100, 256, 1000, 1023, 4096, 8192, 65536]))
+        n = int(rng.integers(1, 60 * min(chunk, 4096) + 2))
+        kind = case % 4
+        if kind == 0:
+            w = rng.standard_t(rng.uniform(2.5, 8), n) * 0.02
+        elif kind == 1:
+            w = rng.laplace(0, 0.015, n)
+        elif kind == 2:
+            w = rng.uniform(0.8, 1.2, n)
+        else:
+            w = rng.normal(0, 1, n)
+            w[rng.integers(0, n, max(1, n // 1000))] *= 100          # a few huge values: a very spiky histogram
+        w = w.astype(np.float32)
+        if n == 1 or w.max() == w.min():
+            w = np.concatenate([w, w[:1] + np.float32(1)])
+            n = w.size
+        scheme = 0 if w.min() >= 0 and case % 2 else 1
+        max_len = int(rng.choice([0, 0, 9, 12, 16])) if bits == 8 else int(rng.choice([0, 5, 8]))
+        tag = (case, bits, chunk, n, kind, scheme, max_len)
+        q_ref, s_ref, z_ref = oracle.quantize(w, bits, scheme)
+        dt, q = E.compress_on_device(torch.from_numpy(w).to(DEV), bits, scheme, chunk, max_len=max_len, return_q=True)
+        assert np.array_equal(q.cpu().numpy(), q_ref), tag
+        assert np.float32(dt.enc.qp.scale) == s_ref and dt.enc.qp.zero_point == z_ref, tag
+        ln = dt.enc.cb.lengths()[: 1 << bits]
+        cnt = oracle.histogram(q_ref, bits)
+        ref_ln = oracle.limited_lengths(cnt, max_len)[0] if max_len else oracle.huffman_lengths(cnt)
+        assert int(np.sum(cnt * ln.astype(np.uint64))) == int(np.sum(cnt * ref_ln.astype(np.uint64))), tag
+        ref_stream, ref_off = oracle.encode(q_ref, ln, oracle.canonical_codes(ln), chunk)
+        assert np.array_equal(dt.offsets.cpu().numpy().view(np.uint64), ref_off), tag
+        assert np.array_equal(dt.stream.cpu().numpy(), ref_stream), tag
