@@ -85,6 +85,9 @@ enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 
 constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32M || mode == kModeGemvF32MP; }
 constexpr bool is_gemv(int mode) { return gemv_f32(mode) || mode == kModeGemvBF16 || mode == kModeGemvBF16M || mode == kModeGemvBF16MP; }
 constexpr bool gemv_multirow(int mode) { return is_gemv(mode) && mode != kModeGemvF32 && mode != kModeGemvBF16; }
+// the GEMV whose segments lie within matrix rows: every lane multiplies its own symbols into x as it
+// decodes them, there is no tile
+constexpr bool gemv_direct_mode(int mode) { return mode == kModeGemvF32 || mode == kModeGemvBF16; }
 // the output format of a mode
 constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
@@ -98,8 +101,8 @@ template <> struct Cfg<kModeU8> { static constexpr int spb = 64, row = 64, waves
 template <> struct Cfg<kModeU4> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 256; };
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
-template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
 // eight waves: the row bookkeeping needs more registers than ten waves leave
 template <> struct Cfg<kModeGemvF32M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
@@ -1093,8 +1096,97 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     }
 }
 
+// GEMV for segments that lie within matrix rows (chunk_symbols <= cols): the lane that decodes a
+// segment also multiplies it into x, four symbols per group, as they come out of the table.  All
+// lanes are at the same place of their segments, so where segments and rows coincide the lanes of
+// a wave ask for the same piece of x (one request); elsewhere they ask for a handful of different
+// ones.  The 64 activations of a block are requested a block ahead, before the stream lines that
+// ring_topup asks for: loads return in order, and a wait for x must not become a wait for the stream.
+// A segment touches one row, or the end of one and the start of the next: `first` holds the sum
+// up to the row end, `acc` what follows.
+template <int MODE>
+__device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb, uint32_t *ring_mem, uint32_t wave_first) {
+    constexpr int GPB = 64 / kGroup;                       // groups per block of 64 symbols
+    const uint32_t lane = threadIdx.x & 63u;
+    if (wave_first >= t.n_chunks) return;
+    const uint32_t C = t.chunk_symbols;
+    const uint32_t k = wave_first + lane;
+    uint32_t nsym = 0;
+    if (k < t.n_chunks) {
+        const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
+        nsym = left < C ? static_cast<uint32_t>(left) : C;
+    }
+    const bool fast = nsym == C;                           // a shorter last segment takes the element-by-element path
+    RingReader<4> r;
+    r.stream = t.stream;
+    r.last_blk = t.stream_bytes - 16u;
+    r.ring = (lds_v32)(ring_mem + lane);
+    // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
+    ring_load(r, fast ? t.offsets[k] : 0);
+    const uint32_t cols = t.cols;
+    const uint16_t *xvec = t.x;
+    const uint32_t max_len = t.max_len;
+    const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
+    uint32_t col = fast ? static_cast<uint32_t>((static_cast<uint64_t>(k) * C) % cols) : 0u;   // column of the block's first symbol
+    float acc = 0.0f, first = 0.0f;
+    bool crossed = false;
+    // eight activations per piece; a piece never straddles a row end (cols % 8 == 0, segments start at multiples of 64)
+    u32x4 xb[8];
+    auto ask_x = [&](uint32_t c0) {
+#pragma unroll
+        for (uint32_t p = 0; p < 8; ++p) {
+            uint32_t c = c0 + 8u * p;
+            c -= c >= cols ? cols : 0u;
+            xb[p] = *(global_u4_ptr)(xvec + c);
+        }
+    };
+    ask_x(col);
+    const uint32_t blocks = C / 64u;
+    for (uint32_t bs = 0; bs < blocks; ++bs) {
+#pragma unroll
+        for (int g = 0; g < GPB; ++g) {
+            if (g % kTripGroups == 0)
+                if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
+            const uint32_t s4 = ring_group<false>(r, tb, max_len);
+            const u32x4 xv = xb[g / 2];
+            const uint32_t xa = (g & 1) ? xv.z : xv.x, xc = (g & 1) ? xv.w : xv.y;
+            acc = fmaf(static_cast<float>(s4 & 0xffu) - zf, __uint_as_float(xa << 16), acc);
+            acc = fmaf(static_cast<float>((s4 >> 8) & 0xffu) - zf, __uint_as_float(xa & 0xffff0000u), acc);
+            acc = fmaf(static_cast<float>((s4 >> 16) & 0xffu) - zf, __uint_as_float(xc << 16), acc);
+            acc = fmaf(static_cast<float>(s4 >> 24) - zf, __uint_as_float(xc & 0xffff0000u), acc);
+            if (g & 1) {
+                // the piece ended a row: what has been summed belongs to it
+                const bool row_end = col + 8u * (g / 2) + 8u == cols || col + 8u * (g / 2) + 8u == 2u * cols;
+                first = row_end ? acc : first;
+                acc = row_end ? 0.0f : acc;
+                crossed |= row_end;
+            }
+        }
+        col += 64u;
+        col -= col >= cols ? cols : 0u;
+        if (bs + 1 < blocks) ask_x(col);
+        ring_topup(r);
+    }
+    if (fast) {
+        // a: the part in the first row the segment touches, b: the part in the next one
+        const float a = crossed ? first : acc, b = crossed ? acc : 0.0f;
+        if (t.need_fix) {                                   // row fragments: summed by the second stage
+            t.partials[2 * static_cast<uint64_t>(k)] = a;
+            t.partials[2 * static_cast<uint64_t>(k) + 1] = b;
+        } else {                                            // segment == row
+            const float y = a * t.scale;
+            if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[k] = y;
+            else reinterpret_cast<uint16_t *>(t.out)[k] = static_cast<uint16_t>(bf16_bits(y));
+        }
+    } else if (nsym) {
+        gemv_segment<MODE>(t, tb, k);
+    }
+}
+
 // The GEMV kernels need the tables and the scratch table only.
-template <int MODE> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
+struct alignas(256) RingMem { uint32_t ring[kRingDwords * 64]; };
+template <int MODE, bool DIRECT = gemv_direct_mode(MODE)> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor<MODE, true> { Tables tb; RingMem wm[Cfg<MODE>::waves]; };
 
 // Does the tensor go through decode_rows?  Segments must tile into blocks; for the
 // GEMV, pieces of eight must not straddle a matrix row and a segment must touch at
@@ -1135,7 +1227,10 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTenso
     const uint32_t first = blockIdx.x * wg_units * kUnit;
     if (rows_fit<MODE>(t)) {
         const uint32_t wave = threadIdx.x >> 6;
-        if (wave < wg_units) decode_rows<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
+        if (wave < wg_units) {
+            if constexpr (gemv_direct_mode(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
+            else decode_rows<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
+        }
     } else {
         const uint32_t end = first + wg_units * kUnit;
         scalar_chunks<MODE>(t, sm.tb, first, end < t.n_chunks ? end : t.n_chunks);
@@ -1178,7 +1273,8 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor
                 if ((threadIdx.x & 63u) == 0) u = atomicAdd(&next_unit, 1u);
                 u = __builtin_amdgcn_readfirstlane(u);
                 if (u >= n_units) break;
-                decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
+                if constexpr (gemv_direct_mode(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
+                else decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
             }
         } else {
             const uint32_t end = it.first + n_units * kUnit;
