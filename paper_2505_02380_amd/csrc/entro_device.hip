@@ -87,7 +87,7 @@ constexpr bool is_gemv(int mode) { return gemv_f32(mode) || mode == kModeGemvBF1
 constexpr bool gemv_multirow(int mode) { return is_gemv(mode) && mode != kModeGemvF32 && mode != kModeGemvBF16; }
 // the GEMV whose segments lie within matrix rows: every lane multiplies its own symbols into x as it
 // decodes them, there is no tile
-constexpr bool gemv_direct_mode(int mode) { return mode == kModeGemvF32 || mode == kModeGemvBF16; }
+constexpr bool gemv_direct_mode(int mode) { return is_gemv(mode); }
 // the output format of a mode
 constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
@@ -106,8 +106,8 @@ template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64,
 // eight waves: the row bookkeeping needs more registers than ten waves leave
 template <> struct Cfg<kModeGemvF32M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvF32MP> { static constexpr int spb = 128, row = 64, waves = 8, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16MP> { static constexpr int spb = 128, row = 64, waves = 8, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32MP> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16MP> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 128; };
 template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 512; };
 template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 256; };
@@ -1096,17 +1096,23 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     }
 }
 
-// GEMV for segments that lie within matrix rows (chunk_symbols <= cols): the lane that decodes a
-// segment also multiplies it into x, four symbols per group, as they come out of the table.  All
-// lanes are at the same place of their segments, so where segments and rows coincide the lanes of
-// a wave ask for the same piece of x (one request); elsewhere they ask for a handful of different
-// ones.  The 64 activations of a block are requested a block ahead, before the stream lines that
-// ring_topup asks for: loads return in order, and a wait for x must not become a wait for the stream.
-// A segment touches one row, or the end of one and the start of the next: `first` holds the sum
-// up to the row end, `acc` what follows.
+// GEMV: the lane that decodes a segment also multiplies it into x, a group of symbols at a time as
+// they come out of the table; there is no tile and no flush, which leaves LDS for 14 wavefronts.
+// All lanes are at the same place of their segments, so where segments and rows coincide the lanes
+// of a wave ask for the same piece of x (one request); elsewhere they ask for a handful of
+// different ones.  The 64 activations of a half block are requested one half block ahead, before
+// the stream lines that ring_topup asks for: loads return in order, and a wait for x must not
+// become a wait for the stream.
+// A segment may begin and end anywhere in a row and hold any number of row ends (cols >= 64, so a
+// half block holds at most one): the sum up to the first row end is the head fragment (or a whole
+// row, if the segment starts one), every further row end completes a whole row, which the lane
+// stores itself, and what is left at the end is the tail fragment; the fragments go to the
+// segment's two partial sums, which the second stage adds up per row.
 template <int MODE>
 __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb, uint32_t *ring_mem, uint32_t wave_first) {
-    constexpr int GPB = 64 / kGroup;                       // groups per block of 64 symbols
+    constexpr bool PAIR = kPairMode<MODE>;                 // two 4-bit symbols per table lookup
+    constexpr int SPG = PAIR ? 8 : 4;                      // symbols per group
+    constexpr int GPH = 64 / SPG;                          // groups per half block of 64 symbols
     const uint32_t lane = threadIdx.x & 63u;
     if (wave_first >= t.n_chunks) return;
     const uint32_t C = t.chunk_symbols;
@@ -1127,9 +1133,14 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
     const uint16_t *xvec = t.x;
     const uint32_t max_len = t.max_len;
     const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
-    uint32_t col = fast ? static_cast<uint32_t>((static_cast<uint64_t>(k) * C) % cols) : 0u;   // column of the block's first symbol
-    float acc = 0.0f, first = 0.0f;
-    bool crossed = false;
+    const float scale = t.scale;
+    const uint64_t flat0 = static_cast<uint64_t>(k) * C;
+    uint32_t col = fast ? static_cast<uint32_t>(flat0 % cols) : 0u;    // column of the half block's first symbol
+    uint32_t row = fast ? static_cast<uint32_t>(flat0 / cols) : 0u;    // the row the lane is in
+    const bool starts_row = col == 0;
+    float acc = 0.0f, first = 0.0f, end_sum = 0.0f;
+    bool crossed = false;                                  // a row end has been passed
+    bool ended = false;                                    // a row ended in this half block: end_sum holds its sum
     // eight activations per piece; a piece never straddles a row end (cols % 8 == 0, segments start at multiples of 64)
     u32x4 xb[8];
     auto ask_x = [&](uint32_t c0) {
@@ -1140,43 +1151,64 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
             xb[p] = *(global_u4_ptr)(xvec + c);
         }
     };
+    auto mul4 = [&](uint32_t s4, uint32_t xa, uint32_t xc) {
+        acc = fmaf(static_cast<float>(s4 & 0xffu) - zf, __uint_as_float(xa << 16), acc);
+        acc = fmaf(static_cast<float>((s4 >> 8) & 0xffu) - zf, __uint_as_float(xa & 0xffff0000u), acc);
+        acc = fmaf(static_cast<float>((s4 >> 16) & 0xffu) - zf, __uint_as_float(xc << 16), acc);
+        acc = fmaf(static_cast<float>(s4 >> 24) - zf, __uint_as_float(xc & 0xffff0000u), acc);
+    };
     ask_x(col);
-    const uint32_t blocks = C / 64u;
-    for (uint32_t bs = 0; bs < blocks; ++bs) {
+    const uint32_t halves = C / 64u;
+    for (uint32_t h = 0; h < halves; ++h) {
 #pragma unroll
-        for (int g = 0; g < GPB; ++g) {
+        for (int g = 0; g < GPH; ++g) {
             if (g % kTripGroups == 0)
                 if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
-            const uint32_t s4 = ring_group<false>(r, tb, max_len);
-            const u32x4 xv = xb[g / 2];
-            const uint32_t xa = (g & 1) ? xv.z : xv.x, xc = (g & 1) ? xv.w : xv.y;
-            acc = fmaf(static_cast<float>(s4 & 0xffu) - zf, __uint_as_float(xa << 16), acc);
-            acc = fmaf(static_cast<float>((s4 >> 8) & 0xffu) - zf, __uint_as_float(xa & 0xffff0000u), acc);
-            acc = fmaf(static_cast<float>((s4 >> 16) & 0xffu) - zf, __uint_as_float(xc << 16), acc);
-            acc = fmaf(static_cast<float>(s4 >> 24) - zf, __uint_as_float(xc & 0xffff0000u), acc);
-            if (g & 1) {
-                // the piece ended a row: what has been summed belongs to it
-                const bool row_end = col + 8u * (g / 2) + 8u == cols || col + 8u * (g / 2) + 8u == 2u * cols;
-                first = row_end ? acc : first;
+            const uint32_t s4 = ring_group<PAIR>(r, tb, max_len);
+            if constexpr (PAIR) {
+                uint32_t lo, hi;
+                unpack_nibbles(s4, lo, hi);
+                mul4(lo, xb[g].x, xb[g].y);
+                mul4(hi, xb[g].z, xb[g].w);
+            } else {
+                const u32x4 xv = xb[g / 2];
+                mul4(s4, (g & 1) ? xv.z : xv.x, (g & 1) ? xv.w : xv.y);
+            }
+            if (PAIR || (g & 1)) {
+                // a row ends behind this piece (at most once per half block: cols >= 64): its sum is set
+                // aside without a branch, so that the groups of the half block stay one stretch of code
+                const uint32_t piece = PAIR ? g : g / 2;
+                const bool row_end = col + 8u * piece + 8u == cols;
+                end_sum = row_end ? acc : end_sum;
                 acc = row_end ? 0.0f : acc;
-                crossed |= row_end;
+                ended |= row_end;
+            }
+        }
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(ended) != 0, 0)) {
+            if (ended) {
+                if (!crossed && !starts_row) {
+                    first = end_sum;                       // the head fragment
+                } else if (fast) {                         // a whole row
+                    const float y = end_sum * scale;
+                    if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
+                    else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
+                }
+                crossed = true;
+                row += 1u;
+                ended = false;
             }
         }
         col += 64u;
         col -= col >= cols ? cols : 0u;
-        if (bs + 1 < blocks) ask_x(col);
-        ring_topup(r);
+        if (h + 1 < halves) ask_x(col);
+        if (!PAIR || (h & 1u)) ring_topup(r);              // once per block of 16 groups
     }
     if (fast) {
-        // a: the part in the first row the segment touches, b: the part in the next one
-        const float a = crossed ? first : acc, b = crossed ? acc : 0.0f;
-        if (t.need_fix) {                                   // row fragments: summed by the second stage
-            t.partials[2 * static_cast<uint64_t>(k)] = a;
-            t.partials[2 * static_cast<uint64_t>(k) + 1] = b;
-        } else {                                            // segment == row
-            const float y = a * t.scale;
-            if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[k] = y;
-            else reinterpret_cast<uint16_t *>(t.out)[k] = static_cast<uint16_t>(bf16_bits(y));
+        if (!crossed) {
+            t.partials[2 * static_cast<uint64_t>(k)] = acc;              // the segment lies inside one row
+        } else {
+            if (!starts_row) t.partials[2 * static_cast<uint64_t>(k)] = first;
+            if (col != 0) t.partials[2 * static_cast<uint64_t>(k) + 1] = acc;   // the segment ends inside a row
         }
     } else if (nsym) {
         gemv_segment<MODE>(t, tb, k);
@@ -1194,9 +1226,7 @@ template <int MODE> struct SmemFor<MODE, true> { Tables tb; RingMem wm[Cfg<MODE>
 template <int MODE>
 __device__ __forceinline__ bool rows_fit(const DevTensor &t) {
     if (t.chunk_symbols % Cfg<MODE>::spb != 0) return false;
-    if constexpr (kPairMode<MODE> && is_gemv(MODE)) return t.cols % 16 == 0 && t.cols >= 128;
-    if constexpr (gemv_multirow(MODE)) return t.cols % 8 == 0 && t.cols >= 64;
-    if constexpr (is_gemv(MODE)) return t.cols % 8 == 0 && t.cols >= t.chunk_symbols;
+    if constexpr (is_gemv(MODE)) return t.cols % 8 == 0 && t.cols >= 64;
     return true;
 }
 
@@ -1421,8 +1451,8 @@ unsigned wg_of(int mode) {
 // `multirow`: GEMV with a tensor whose segments are longer than its matrix rows.
 int mode_of(entro_op op, entro_dtype d, bool pairs, bool multirow) {
     if (op == ENTRO_OP_GEMV) {
+        (void)multirow;                                     // one kernel serves segments within rows and longer ones
         if (pairs) return d == ENTRO_F32 ? kModeGemvF32MP : kModeGemvBF16MP;
-        if (multirow) return d == ENTRO_F32 ? kModeGemvF32M : kModeGemvBF16M;
         return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
     }
     switch (d) {
