@@ -76,18 +76,12 @@ struct WorkItem {
     uint32_t first;             // first segment (main kernels) or first row (second-stage sum)
 };
 
-// The P modes are the byte, fp32 and bf16 outputs of launches whose tensors all hold 4-bit symbols:
-// they decode two symbols per lookup, like the packed output.
-// The M modes are the GEMV of launches with a tensor whose segments are longer than its matrix rows.
+// The P modes are the byte, fp32 and bf16 outputs and the GEMV of launches whose tensors all hold
+// 4-bit symbols: they decode two symbols per lookup, like the packed output.
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5,
-            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32M = 9, kModeGemvBF16M = 10,
-            kModeGemvF32MP = 11, kModeGemvBF16MP = 12 };       // MP: the M kernel with two 4-bit symbols per lookup
-constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32M || mode == kModeGemvF32MP; }
-constexpr bool is_gemv(int mode) { return gemv_f32(mode) || mode == kModeGemvBF16 || mode == kModeGemvBF16M || mode == kModeGemvBF16MP; }
-constexpr bool gemv_multirow(int mode) { return is_gemv(mode) && mode != kModeGemvF32 && mode != kModeGemvBF16; }
-// the GEMV whose segments lie within matrix rows: every lane multiplies its own symbols into x as it
-// decodes them, there is no tile
-constexpr bool gemv_direct_mode(int mode) { return is_gemv(mode); }
+            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32P = 9, kModeGemvBF16P = 10 };
+constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32P; }
+constexpr bool is_gemv(int mode) { return gemv_f32(mode) || mode == kModeGemvBF16 || mode == kModeGemvBF16P; }
 // the output format of a mode
 constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
@@ -95,7 +89,8 @@ constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == 
 // (one per table lookup: a symbol, or two 4-bit symbols already packed), waves
 // per workgroup (what fits into the 160 KB of LDS), tile bytes one lane consumes
 // per flush pass (a 16-byte store for all but fp32) and bytes that a row becomes
-// in memory.  The host glue sizes its launches with the same numbers.
+// in memory.  The host glue sizes its launches with the same numbers.  The GEMV
+// has no tile (only spb, the symbols between two ring refills, and waves count).
 template <int MODE> struct Cfg;
 template <> struct Cfg<kModeU8> { static constexpr int spb = 64, row = 64, waves = 10, piece = 16, out_row = 64; };
 template <> struct Cfg<kModeU4> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 64; };
@@ -103,17 +98,14 @@ template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, wave
 template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
 template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
-// eight waves: the row bookkeeping needs more registers than ten waves leave
-template <> struct Cfg<kModeGemvF32M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16M> { static constexpr int spb = 64, row = 64, waves = 8, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvF32MP> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeGemvBF16MP> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 128; };
 template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 512; };
 template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 256; };
 // Packed 4-bit output decodes two symbols per lookup, and so do the P modes.
 template <int MODE> constexpr bool kPairMode = MODE == kModeU4 || MODE == kModeU8P || MODE == kModeF32P || MODE == kModeBF16P ||
-                                               MODE == kModeGemvF32MP || MODE == kModeGemvBF16MP;
+                                               MODE == kModeGemvF32P || MODE == kModeGemvBF16P;
 
 // Lookup tables of one workgroup (LDS).
 // Entry (16 bits): bits 0..5 the code's length, bits 8..15 its symbol, so that an
@@ -192,19 +184,6 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
 __device__ __forceinline__ uint32_t pack_entry(uint32_t sym, uint32_t len) { return len | (sym << 8); }
 __device__ __forceinline__ uint32_t entry_len(uint32_t e) { return e & 0x3fu; }
 __device__ __forceinline__ uint32_t entry_sym(uint32_t e) { return e >> 8; }
-
-// sum over eight symbols (one per byte of d0, d1) of (q - z) * x, x being eight bf16 values.
-__device__ __forceinline__ float dot8(uint32_t d0, uint32_t d1, const u32x4 xv, float zf, float part) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t xa = j < 2 ? xv.x : xv.y, xb = j < 2 ? xv.z : xv.w;
-        const float x0 = __uint_as_float((j & 1) ? (xa & 0xffff0000u) : (xa << 16));
-        const float x1 = __uint_as_float((j & 1) ? (xb & 0xffff0000u) : (xb << 16));
-        part = fmaf(static_cast<float>((d0 >> (8 * j)) & 0xffu) - zf, x0, part);
-        part = fmaf(static_cast<float>((d1 >> (8 * j)) & 0xffu) - zf, x1, part);
-    }
-    return part;
-}
 
 // The eight 4-bit symbols of four pair bytes, one per byte, in order.
 __device__ __forceinline__ void unpack_nibbles(uint32_t d, uint32_t &lo, uint32_t &hi) {
@@ -738,13 +717,11 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
 // SPB symbols per lane at a time into the wave's
 // LDS tile (one row of symbol bytes per lane; all lanes move in step, four
 // symbols per group), then consume the tile row-wise: write it out in the output
-// type, so that every store instruction covers whole rows, or (GEMV) multiply it
-// into the activation vector.
+// type, so that every store instruction covers whole rows.
 template <int MODE>
 __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb, WaveMem<Cfg<MODE>::row> *wms,
                                             uint32_t wave_first) {
-    constexpr bool GEMV = is_gemv(MODE);
-    constexpr bool MROW = gemv_multirow(MODE);           // GEMV whose segments may hold whole matrix rows
+    static_assert(!is_gemv(MODE), "the GEMV has a kernel of its own");
     constexpr bool PAIR = kPairMode<MODE>;
     constexpr int SPB = Cfg<MODE>::spb;                   // symbols of a lane per block
     constexpr int ROW = Cfg<MODE>::row;                   // bytes they make in the tile
@@ -752,11 +729,10 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     constexpr uint32_t PIECE = Cfg<MODE>::piece;          // tile bytes one lane consumes per pass
     constexpr uint32_t LPR = ROW / PIECE;                 // lanes that consume one row
     constexpr uint32_t RPI = 64 / LPR;                    // rows per pass
-    constexpr uint32_t EBITS = GEMV ? 0 : OutTraits<GEMV ? kModeU8 : MODE>::ebits;
+    constexpr uint32_t EBITS = OutTraits<MODE>::ebits;
     constexpr int TRIPS = ROW / (kGroup * kTripGroups);
     static_assert(ROW % (kGroup * kTripGroups) == 0, "a row is a whole number of trips");
     static_assert(SPB == (PAIR ? 2 : 1) * ROW, "one tile byte per lookup");
-    constexpr uint32_t SYM_PIECE = PIECE * (PAIR ? 2u : 1u);   // symbols of a lane's piece
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     WaveMem<ROW> &wm = wms[wave];
@@ -770,14 +746,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
         nsym = left < C ? static_cast<uint32_t>(left) : C;
     }
     // A shorter last segment takes the row path for its whole blocks and the scalar path for the
-    // rest (GEMV: the scalar path as a whole).  The lane moves on with the others past its own end;
-    // what it decodes there is not stored.
-    const bool fast = GEMV ? nsym == C : nsym != 0;
+    // rest.  The lane moves on with the others past its own end; what it decodes there is not stored.
+    const bool fast = nsym != 0;
     const uint32_t my_blocks = nsym / SPB;
     uint64_t tail_pos = fast ? t.offsets[k] : 0;          // where the symbols behind the lane's last whole block start
-    // memory serves a scattered 128-byte request far better than two of 64 bytes at different times;
-    // the GEMV, which writes nothing, does better with the smaller line and the registers it saves
-    RingReader<GEMV ? 4 : 8> r;
+    // memory serves a scattered 128-byte request far better than two of 64 bytes at different times
+    RingReader<8> r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(wm.ring + lane);
@@ -785,8 +759,8 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     ring_load(r, fast ? t.offsets[k] : 0);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
     const uint32_t n_full = static_cast<uint32_t>(t.n / C);          // segments of full length
-    // whole blocks of the shorter last segment, if there is one (GEMV stores nothing of it here)
-    const uint32_t tail_blocks = GEMV ? 0u : static_cast<uint32_t>((t.n - static_cast<uint64_t>(n_full) * C) / SPB);
+    // whole blocks of the shorter last segment, if there is one
+    const uint32_t tail_blocks = static_cast<uint32_t>((t.n - static_cast<uint64_t>(n_full) * C) / SPB);
     // a wave that holds only the shorter last segment stops after its blocks
     const uint32_t wave_blocks = wave_first < n_full ? blocks_total : tail_blocks;
     // where the first row this lane serves in a flush pass begins; the passes are RPI rows apart
@@ -796,55 +770,11 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const float scale = t.scale;
     lds_v32 tile = (lds_v32)wm.tile;
 
-    // GEMV: the lane sums, for the eight rows it serves, its eight-symbol piece of every block.
-    // A segment is at most as long as a matrix row here, so it touches one row (acc_a) or the
-    // end of one and the start of the next (acc_b).
-    const uint32_t cols = t.cols;
-    const uint16_t *xvec = t.x;
-    float acc_a[64 / RPI], acc_b[64 / RPI];
-    uint32_t col0[64 / RPI];
-    // Segments longer than matrix rows (MROW): acc_a is the first row the segment touches, acc_b the
-    // row it is in after that, acc_c what a block adds to the row after that one; col0 then is the
-    // column of the current block's first symbol and moves along.
-    float acc_c[MROW ? 64 / RPI : 1];
-    uint32_t row_first[MROW ? 64 / RPI : 1], rows_done[MROW ? 64 / RPI : 1];   // the segment's first row; row ends passed
-    uint32_t in_first = 0xffu;               // MROW, bit it: still in the first row
-    uint32_t starts_row = 0;                 // MROW, bit it: the segment starts at column 0
-    if constexpr (GEMV) {
-#pragma unroll
-        for (uint32_t it = 0; it < 64 / RPI; ++it) {
-            const uint32_t kk = wave_first + it * RPI + lane / LPR;
-            acc_a[it] = 0.0f;
-            acc_b[it] = 0.0f;
-            col0[it] = static_cast<uint32_t>((static_cast<uint64_t>(kk) * C) % cols);
-            if constexpr (MROW) {
-                acc_c[it] = 0.0f;
-                starts_row |= (col0[it] == 0 ? 1u : 0u) << it;
-                row_first[it] = static_cast<uint32_t>((static_cast<uint64_t>(kk) * C) / cols);
-                rows_done[it] = 0;
-            }
-        }
-    }
-
     // integer outputs whose blocks make 64 bytes per row: the even block's pieces, kept for the odd block's flush
-    constexpr bool HOLD = !GEMV && OUT_ROW == 64;
+    constexpr bool HOLD = OUT_ROW == 64;
     u32x4 held[HOLD ? 64 / RPI : 1];
     bool held_full[HOLD ? 64 / RPI : 1];
     for (uint32_t bs = 0; bs < wave_blocks; ++bs) {
-        // GEMV: ask for the block's activations now, so that they arrive while the symbols are decoded
-        // (eight bf16 per pass; always inside x: columns come in pieces of eight and cols % 8 == 0)
-        u32x4 xblk[GEMV ? 64 / RPI : 1][PAIR ? 2 : 1];
-        bool xsecond[GEMV ? 64 / RPI : 1];
-        if constexpr (GEMV) {
-#pragma unroll
-            for (uint32_t it = 0; it < 64 / RPI; ++it) {
-                uint32_t col = col0[it] + (MROW ? 0u : bs * SPB) + (lane % LPR) * SYM_PIECE;
-                xsecond[it] = col >= cols;                            // past the row end: next row, from column 0
-                col -= xsecond[it] ? cols : 0u;
-                xblk[it][0] = *(global_u4_ptr)(xvec + col);
-                if constexpr (PAIR) xblk[it][1] = *(global_u4_ptr)(xvec + col + 8u);
-            }
-        }
 #pragma unroll 1
         for (int trip = 0; trip < TRIPS; ++trip) {
             if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
@@ -852,7 +782,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             for (int g = 0; g < kTripGroups; ++g)
                 tile[WaveMem<ROW>::tile_at(lane, trip * kTripGroups + g)] = ring_group<PAIR>(r, tb, max_len);
         }
-        if (!GEMV && bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
+        if (bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
         ring_topup(r);
         wave_sync_lds();
 #pragma unroll
@@ -863,184 +793,89 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             // the row has this block: always in a full segment, up to tail_blocks in the shorter last one
             const bool full = kk < n_full || (kk == n_full && bs < tail_blocks);
             uint8_t *dst = row0 + static_cast<uint64_t>(it) * (RPI * bytes_per_chunk) + static_cast<uint64_t>(bs) * OUT_ROW;
-            if constexpr (GEMV) {
-                // the lane's eight symbols of the row
-                const uint32_t d0 = tile[WaveMem<ROW>::tile_at(rr, piece * 2u)], d1 = tile[WaveMem<ROW>::tile_at(rr, piece * 2u + 1u)];
-                if (full) {
-                    const bool second = xsecond[it];
-                    float part;
-                    if constexpr (PAIR) {
-                        // eight pair bytes: sixteen symbols against sixteen activations
-                        uint32_t a0, a1, b0, b1;
-                        unpack_nibbles(d0, a0, a1);
-                        unpack_nibbles(d1, b0, b1);
-                        part = dot8(a0, a1, xblk[it][0], zf, 0.0f);
-                        part = dot8(b0, b1, xblk[it][1], zf, part);
-                    } else {
-                        part = dot8(d0, d1, xblk[it][0], zf, 0.0f);
-                    }
-                    if constexpr (!MROW) {
-                        acc_a[it] += second ? 0.0f : part;
-                        acc_b[it] += second ? part : 0.0f;
-                    } else {
-                        const bool first = (in_first >> it) & 1u;
-                        acc_a[it] += first && !second ? part : 0.0f;
-                        acc_b[it] += first == second ? part : 0.0f;          // first row's successor, or the current row
-                        acc_c[it] += !first && second ? part : 0.0f;
-                    }
-                }
-                if constexpr (MROW) {
-                    // a matrix row ends inside this block (at most one does: cols >= 64)
-                    if (col0[it] + SPB >= cols) {
-                        if (!((in_first >> it) & 1u)) {
-                            // a whole row that lies inside the segment: its eight lanes add up and store it
-                            float a = acc_b[it];
+            // Store k of the pass writes the bytes [k * LPR * 16, (k + 1) * LPR * 16) of the row's
+            // piece of this block, 16 per lane, so that every store instruction covers whole
+            // stretches of memory; the lane fetches the tile bytes that become its 16 bytes.
+            constexpr int OUT = base_mode(MODE);
+            constexpr uint32_t SYMS = OUT == kModeF32 ? 4u : OUT == kModeBF16 ? 8u : OUT == kModeU8 ? 16u : 32u;   // per 16 bytes
+            constexpr uint32_t TB = PAIR && OUT != kModeU4 ? SYMS / 2u : OUT == kModeU4 ? 16u : SYMS;   // tile bytes for them
+            constexpr uint32_t NST = ROW / (LPR * TB);
+            static_assert(NST * LPR * TB == ROW && NST * LPR * 16u == static_cast<uint32_t>(OUT_ROW), "the stores tile the row");
 #pragma unroll
-                            for (uint32_t m = 1; m < LPR; m <<= 1) a += __shfl_xor(a, m, 64);
-                            if (full && piece == 0) {
-                                const uint32_t row = row_first[it] + rows_done[it];
-                                const float y = a * scale;
-                                if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
-                                else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
-                            }
-                            acc_b[it] = acc_c[it];
-                            acc_c[it] = 0.0f;
-                        }
-                        in_first &= ~(1u << it);
-                        rows_done[it] += 1u;
-                        col0[it] = col0[it] + SPB - cols;
+            for (uint32_t k = 0; k < NST; ++k) {
+                const uint32_t tb0 = (k * LPR + piece) * TB;        // first tile byte of this lane's share
+                uint32_t raw[TB >= 4 ? TB / 4 : 1];
+#pragma unroll
+                for (uint32_t j = 0; j < (TB >= 4 ? TB / 4 : 1); ++j) raw[j] = tile[WaveMem<ROW>::tile_at(rr, tb0 / 4 + j)];
+                if (TB < 4) raw[0] = (raw[0] >> (8u * (tb0 & 3u))) & 0xffffu;    // two pair bytes out of a dword
+                uint8_t *const at = dst + k * (LPR * 16u) + piece * 16u;
+                if constexpr (OUT == kModeU8 || OUT == kModeU4) {
+                    u32x4 v;
+                    if constexpr (PAIR && OUT == kModeU8) {
+                        // 8 pair bytes -> 16 symbol bytes
+                        uint32_t u[4];
+                        unpack_nibbles(raw[0], u[0], u[1]);
+                        unpack_nibbles(raw[1], u[2], u[3]);
+                        v = u32x4{u[0], u[1], u[2], u[3]};
                     } else {
-                        col0[it] += SPB;
+                        // the tile bytes are the output bytes (4-bit pairs come packed out of the table)
+                        v = u32x4{raw[0], raw[1], raw[2], raw[3]};
                     }
-                }
-            } else {
-                // Store k of the pass writes the bytes [k * LPR * 16, (k + 1) * LPR * 16) of the row's
-                // piece of this block, 16 per lane, so that every store instruction covers whole
-                // stretches of memory; the lane fetches the tile bytes that become its 16 bytes.
-                constexpr int OUT = base_mode(MODE);
-                constexpr uint32_t SYMS = OUT == kModeF32 ? 4u : OUT == kModeBF16 ? 8u : OUT == kModeU8 ? 16u : 32u;   // per 16 bytes
-                constexpr uint32_t TB = PAIR && OUT != kModeU4 ? SYMS / 2u : OUT == kModeU4 ? 16u : SYMS;   // tile bytes for them
-                constexpr uint32_t NST = ROW / (LPR * TB);
-                static_assert(NST * LPR * TB == ROW && NST * LPR * 16u == static_cast<uint32_t>(OUT_ROW), "the stores tile the row");
-#pragma unroll
-                for (uint32_t k = 0; k < NST; ++k) {
-                    const uint32_t tb0 = (k * LPR + piece) * TB;        // first tile byte of this lane's share
-                    uint32_t raw[TB >= 4 ? TB / 4 : 1];
-#pragma unroll
-                    for (uint32_t j = 0; j < (TB >= 4 ? TB / 4 : 1); ++j) raw[j] = tile[WaveMem<ROW>::tile_at(rr, tb0 / 4 + j)];
-                    if (TB < 4) raw[0] = (raw[0] >> (8u * (tb0 & 3u))) & 0xffffu;    // two pair bytes out of a dword
-                    uint8_t *const at = dst + k * (LPR * 16u) + piece * 16u;
-                    if constexpr (OUT == kModeU8 || OUT == kModeU4) {
-                        u32x4 v;
-                        if constexpr (PAIR && OUT == kModeU8) {
-                            // 8 pair bytes -> 16 symbol bytes
-                            uint32_t u[4];
-                            unpack_nibbles(raw[0], u[0], u[1]);
-                            unpack_nibbles(raw[1], u[2], u[3]);
-                            v = u32x4{u[0], u[1], u[2], u[3]};
+                    if constexpr (HOLD) {
+                        // a block makes only 64 bytes per row: the even block's piece waits for the odd
+                        // block's, and the two go out in neighbouring store instructions, which the L2
+                        // merges into whole 128-byte lines (64 bytes at a time reach memory at 2.8 TB/s,
+                        // the merged lines at 4.8)
+                        if ((bs & 1u) == 0 && bs + 1 < wave_blocks) {
+                            held[it] = v;
+                            held_full[it] = full;
                         } else {
-                            // the tile bytes are the output bytes (4-bit pairs come packed out of the table)
-                            v = u32x4{raw[0], raw[1], raw[2], raw[3]};
-                        }
-                        if constexpr (HOLD) {
-                            // a block makes only 64 bytes per row: the even block's piece waits for the odd
-                            // block's, and the two go out in neighbouring store instructions, which the L2
-                            // merges into whole 128-byte lines (64 bytes at a time reach memory at 2.8 TB/s,
-                            // the merged lines at 4.8)
-                            if ((bs & 1u) == 0 && bs + 1 < wave_blocks) {
-                                held[it] = v;
-                                held_full[it] = full;
-                            } else {
-                                if ((bs & 1u) && held_full[it]) *(global_u4_wptr)(at - OUT_ROW) = held[it];
-                                if (full) *(global_u4_wptr)at = v;
-                            }
-                        } else {
+                            if ((bs & 1u) && held_full[it]) *(global_u4_wptr)(at - OUT_ROW) = held[it];
                             if (full) *(global_u4_wptr)at = v;
                         }
                     } else {
-                        // w = (q - z) * s: exact difference, one fp32 multiply
-                        uint32_t sym4[SYMS / 4];                         // one symbol per byte
-                        if constexpr (PAIR) {
-                            if constexpr (SYMS == 8) {
-                                unpack_nibbles(raw[0], sym4[0], sym4[1]);
-                            } else {
-                                uint32_t unused;
-                                unpack_nibbles(raw[0], sym4[0], unused);
-                            }
+                        if (full) *(global_u4_wptr)at = v;
+                    }
+                } else {
+                    // w = (q - z) * s: exact difference, one fp32 multiply
+                    uint32_t sym4[SYMS / 4];                         // one symbol per byte
+                    if constexpr (PAIR) {
+                        if constexpr (SYMS == 8) {
+                            unpack_nibbles(raw[0], sym4[0], sym4[1]);
                         } else {
-#pragma unroll
-                            for (uint32_t j = 0; j < SYMS / 4; ++j) sym4[j] = raw[j];
+                            uint32_t unused;
+                            unpack_nibbles(raw[0], sym4[0], unused);
                         }
-                        float f[SYMS];
+                    } else {
 #pragma unroll
-                        for (uint32_t j = 0; j < SYMS; ++j)
-                            f[j] = (static_cast<float>((sym4[j / 4] >> (8 * (j % 4))) & 0xffu) - zf) * scale;
-                        u32x4 v;
-                        if constexpr (OUT == kModeF32) {
-                            v = u32x4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
-                        } else {
+                        for (uint32_t j = 0; j < SYMS / 4; ++j) sym4[j] = raw[j];
+                    }
+                    float f[SYMS];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const f32x2 pr = {f[2 * j], f[2 * j + 1]};
-                                const bf16x2 b = __builtin_convertvector(pr, bf16x2);   // round to nearest even
-                                v[j] = __builtin_bit_cast(uint32_t, b);
-                            }
+                    for (uint32_t j = 0; j < SYMS; ++j)
+                        f[j] = (static_cast<float>((sym4[j / 4] >> (8 * (j % 4))) & 0xffu) - zf) * scale;
+                    u32x4 v;
+                    if constexpr (OUT == kModeF32) {
+                        v = u32x4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const f32x2 pr = {f[2 * j], f[2 * j + 1]};
+                            const bf16x2 b = __builtin_convertvector(pr, bf16x2);   // round to nearest even
+                            v[j] = __builtin_bit_cast(uint32_t, b);
                         }
-                        if (full) {
-                            if constexpr (OUT == kModeF32) *(global_u4_wptr)at = v;
-                            else __builtin_nontemporal_store(v, (global_u4_wptr)at);
-                        }
+                    }
+                    if (full) {
+                        if constexpr (OUT == kModeF32) *(global_u4_wptr)at = v;
+                        else __builtin_nontemporal_store(v, (global_u4_wptr)at);
                     }
                 }
             }
         }
         wave_sync_lds();
     }
-    if constexpr (GEMV) {
-        // the eight lanes of a row add up their pieces; the first of them publishes the result
-#pragma unroll
-        for (uint32_t it = 0; it < 64 / RPI; ++it) {
-            float a = acc_a[it], b = acc_b[it];
-#pragma unroll
-            for (uint32_t m = 1; m < LPR; m <<= 1) {
-                a += __shfl_xor(a, m, 64);
-                b += __shfl_xor(b, m, 64);
-            }
-            const uint32_t kk = wave_first + it * RPI + lane / LPR;
-            const bool full = kk < n_full;
-            if constexpr (MROW) {
-                if (full && (lane % LPR) == 0) {
-                    // the first row: whole if the segment starts at column 0 and holds its end, else the head
-                    // fragment; what is left of the last row (if it goes on in the next segment): the tail
-                    const bool first = (in_first >> it) & 1u;
-                    if (((starts_row >> it) & 1u) && !first) {
-                        const float y = a * scale;
-                        if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row_first[it]] = y;
-                        else reinterpret_cast<uint16_t *>(t.out)[row_first[it]] = static_cast<uint16_t>(bf16_bits(y));
-                    } else {
-                        t.partials[2 * static_cast<uint64_t>(kk)] = a;
-                    }
-                    if (!first && col0[it] != 0) t.partials[2 * static_cast<uint64_t>(kk) + 1] = b;
-                }
-                continue;
-            }
-            if (full && (lane % LPR) == 0) {
-                if (t.need_fix) {                                   // row fragments: summed by the second stage
-                    t.partials[2 * static_cast<uint64_t>(kk)] = a;
-                    t.partials[2 * static_cast<uint64_t>(kk) + 1] = b;
-                } else {                                            // segment == row
-                    const float y = a * scale;
-                    if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[kk] = y;
-                    else reinterpret_cast<uint16_t *>(t.out)[kk] = static_cast<uint16_t>(bf16_bits(y));
-                }
-            }
-        }
-        if (!fast && nsym) gemv_segment<MODE>(t, tb, k);
-    } else {
-        const uint32_t rest = nsym - my_blocks * SPB;
-        if (rest)
-            decode_scalar_from<(GEMV ? kModeU8 : MODE)>(t, tb, tail_pos, static_cast<uint64_t>(k) * C + my_blocks * SPB, rest);
-    }
+    const uint32_t rest = nsym - my_blocks * SPB;
+    if (rest) decode_scalar_from<MODE>(t, tb, tail_pos, static_cast<uint64_t>(k) * C + my_blocks * SPB, rest);
 }
 
 // Decode one segment straight into dot products with x.  A segment covers one
@@ -1217,7 +1052,7 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
 
 // The GEMV kernels need the tables and the scratch table only.
 struct alignas(256) RingMem { uint32_t ring[kRingDwords * 64]; };
-template <int MODE, bool DIRECT = gemv_direct_mode(MODE)> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
+template <int MODE, bool GEMV = is_gemv(MODE)> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
 template <int MODE> struct SmemFor<MODE, true> { Tables tb; RingMem wm[Cfg<MODE>::waves]; };
 
 // Does the tensor go through decode_rows?  Segments must tile into blocks; for the
@@ -1258,7 +1093,7 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTenso
     if (rows_fit<MODE>(t)) {
         const uint32_t wave = threadIdx.x >> 6;
         if (wave < wg_units) {
-            if constexpr (gemv_direct_mode(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
+            if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
             else decode_rows<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
         }
     } else {
@@ -1303,7 +1138,7 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor
                 if ((threadIdx.x & 63u) == 0) u = atomicAdd(&next_unit, 1u);
                 u = __builtin_amdgcn_readfirstlane(u);
                 if (u >= n_units) break;
-                if constexpr (gemv_direct_mode(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
+                if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
                 else decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
             }
         } else {
@@ -1432,10 +1267,8 @@ void dispatch_mode(int mode, F f) {
         case kModeU8P: f(std::integral_constant<int, kModeU8P>{}); break;
         case kModeF32P: f(std::integral_constant<int, kModeF32P>{}); break;
         case kModeBF16P: f(std::integral_constant<int, kModeBF16P>{}); break;
-        case kModeGemvF32M: f(std::integral_constant<int, kModeGemvF32M>{}); break;
-        case kModeGemvBF16M: f(std::integral_constant<int, kModeGemvBF16M>{}); break;
-        case kModeGemvF32MP: f(std::integral_constant<int, kModeGemvF32MP>{}); break;
-        case kModeGemvBF16MP: f(std::integral_constant<int, kModeGemvBF16MP>{}); break;
+        case kModeGemvF32P: f(std::integral_constant<int, kModeGemvF32P>{}); break;
+        case kModeGemvBF16P: f(std::integral_constant<int, kModeGemvBF16P>{}); break;
         default: f(std::integral_constant<int, kModeGemvBF16>{}); break;
     }
 }
@@ -1448,11 +1281,9 @@ unsigned wg_of(int mode) {
 }
 
 // `pairs`: every tensor of the launch holds 4-bit symbols, so the tables can hold two codes per entry.
-// `multirow`: GEMV with a tensor whose segments are longer than its matrix rows.
-int mode_of(entro_op op, entro_dtype d, bool pairs, bool multirow) {
+int mode_of(entro_op op, entro_dtype d, bool pairs) {
     if (op == ENTRO_OP_GEMV) {
-        (void)multirow;                                     // one kernel serves segments within rows and longer ones
-        if (pairs) return d == ENTRO_F32 ? kModeGemvF32MP : kModeGemvBF16MP;
+        if (pairs) return d == ENTRO_F32 ? kModeGemvF32P : kModeGemvBF16P;
         return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
     }
     switch (d) {
@@ -1490,7 +1321,7 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     if (st != ENTRO_OK) return st;
     dt.partials = partials;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int mode = mode_of(op, d, dt.bits == 4, dt.cols < dt.chunk_symbols);
+    const int mode = mode_of(op, d, dt.bits == 4);
     const unsigned wg = wg_of(mode);
     // a unit per wavefront when the tensor is large; fewer units per workgroup, down to one, when
     // that would leave compute units without a workgroup
@@ -1651,7 +1482,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     }
     // A work item is what a workgroup takes in one round when the launch is large (a unit per
     // wavefront), and less when the launch would not give every compute unit an item otherwise.
-    const int mode = mode_of(op, out_type, pairs, multirow);
+    const int mode = mode_of(op, out_type, pairs);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const uint64_t waves = wg_of(mode) / 64u;
@@ -1688,8 +1519,7 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const DevTensor *dts = reinterpret_cast<const DevTensor *>(ws + plan->off_tensors);
     const WorkItem *items = reinterpret_cast<const WorkItem *>(ws + plan->off_items);
     const WorkItem *fix = reinterpret_cast<const WorkItem *>(ws + plan->off_fix);
-    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0,
-                             plan->gemv_multirow != 0);
+    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const unsigned grid = plan->n_items < slots ? plan->n_items : slots;
