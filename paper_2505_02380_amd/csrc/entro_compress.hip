@@ -37,7 +37,7 @@ constexpr int kWaves = kWG / 64;
 // workgroups the better.
 constexpr int kBigWG = 1024;
 constexpr int kBigWaves = kBigWG / 64;
-constexpr int kHistCopies = 8;                 // counters per bin and wave, picked by lane: spreads the hits on the few frequent symbols
+constexpr int kHistCopies = 8;                 // counters per bin and set of waves, picked by lane: spreads the hits on the few frequent symbols
 constexpr int kPrefetch = 8;                   // dwords of symbols a lane requests together
 constexpr uint64_t kMissBit = 1ull << 63;       // in a segment's bit count: it holds a symbol without a code
 constexpr uint32_t kFlagSymbol = 1u;           // a symbol without a code (or >= 2^bits)

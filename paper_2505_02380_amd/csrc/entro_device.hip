@@ -8,12 +8,13 @@
 // segments of one tensor with one shared set of lookup tables in LDS.
 //
 // Data flow of the decode / dequant kernels, per lane:
-//   HBM --64-byte lines--> registers --between output blocks--> 128-byte ring in LDS
+//   HBM --128-byte lines (GEMV: 64)--> registers --between output blocks--> 128-byte ring in LDS
 //   ring --three dwords--> 63-bit window --14 bits--> first-level table (LDS,
 //   16-bit entries: length | symbol) --shift by the entry--> next code ...
 //   four symbols --one aligned dword--> the lane's row of the wave's LDS tile
 //   tile rows --dequantise / pack, row-wise--> HBM,
-// so that every global store instruction of a wave covers whole rows.  All 64
+// so that every global store instruction of a wave covers whole rows (the GEMV
+// has no tile: a lane multiplies its four symbols into x as they come).  All 64
 // lanes of a wave decode in step, four symbols per window: no lane waits for
 // another, nothing is written to LDS at an odd address, and a flush happens
 // after a fixed number of groups.  The symbol loop has no branch per lookup; a
