@@ -318,8 +318,11 @@ def test_dequant_ragged_and_unsigned_and_offgrid_zero_point():
     (512, 128, 1024),        # eight whole rows per segment
     (300, 192, 1024),        # five and a third rows per segment
     (160, 3072, 8192),       # the phi3 shapes: two and two thirds rows per segment
-    (4096 + 11, 64, 4096),   # the shortest rows the row path takes: one per block; ragged last segment
+    (4096 + 11, 64, 4096),   # the shortest rows the kernel takes: one per block; ragged last segment
     (100, 72, 512),          # a block may hold the end of one row and the start of the next
+    (64, 4096, 64),          # the shortest segments: sixty-four per row
+    (7, 1000, 4096),         # rows of 125 pieces of eight, segments of four rows and a bit
+    (31, 60, 128),           # rows shorter than a block: element by element
 ])
 @pytest.mark.parametrize("batch", [False, True])
 def test_gemv_against_fp64_oracle(rows, cols, chunk, batch):
@@ -338,9 +341,13 @@ def test_gemv_against_fp64_oracle(rows, cols, chunk, batch):
     (160, 3072, 8192),       # phi3 shapes: two and two thirds rows per segment
     (64, 8192, 8192),        # one row per segment
     (96, 4096, 1024),        # four segments per row
-    (520, 128, 4096),        # the shortest rows the pair kernel takes
+    (520, 128, 4096),        # thirty-two rows per segment
     (33, 144, 256),          # rows and blocks out of step
-    (50, 200, 512),          # cols not a multiple of 16: element by element, with the pair tables
+    (50, 200, 512),          # cols a multiple of 8 but not of 16
+    (300, 64, 256),          # the shortest rows the kernel takes: one per half block
+    (90, 72, 128),           # a half block may hold the end of one row and the start of the next
+    (40, 100, 256),          # cols not a multiple of 8: element by element, with the pair tables
+    (3, 8192, 256),          # a few long rows of many segments
 ])
 @pytest.mark.parametrize("batch", [False, True])
 def test_gemv_4bit_two_symbols_per_lookup(rows, cols, chunk, batch):
