@@ -68,6 +68,9 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if not os.path.exists(E.library_path()):                # the library is used as built; none at all: build it
+        from paper_2505_02380_amd import build as lib_build
+        lib_build.build(force=True)
     E.lib()
 
     # ------------------------------------------------------------------ inputs

@@ -12,6 +12,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    """The tests load the library as built; only where none is there at all is it built first."""
+    from paper_2505_02380_amd import binding, build
+    if not os.path.exists(binding.library_path()):
+        build.build(force=True)
+
+
 def _have_gpu() -> bool:
     try:
         import torch
