@@ -529,3 +529,56 @@ def test_mistral_layer_launch_shape_sampled_against_oracle():
         y_ref, _ = oracle.gemv(sub, len(rows), e.cols, e.qp.scale, e.qp.zero_point, xb)
         rms = np.sqrt(np.mean(yh ** 2))
         assert np.max(np.abs(yh[rows] - y_ref) / np.maximum(np.abs(y_ref), rms)) <= 1e-3, e.name
+
+
+def test_prepared_launches_replay_in_a_hip_graph():
+    """entro_plan_run only enqueues kernels (no allocation, no copies, no memset), so it can be captured:
+    every replay of the graph must give the eager result, with eager work and synchronisation between
+    the replays."""
+    rng = np.random.default_rng(4242)
+    encs, refs_q = [], []
+    for rows, cols, chunk in [(96, 4096, 4096), (40, 1024, 4096), (33, 3072, 1024)]:
+        sym = np.minimum(rng.geometric(0.3, rows * cols) - 1, 255).astype(np.uint8)
+        encs.append(_oracle_encoded(sym, 8, chunk, rows=rows, cols=cols, s=np.float32(0.01), z=3))
+        refs_q.append(sym)
+    dts = [E.to_device(e, DEV) for e in encs]
+    # dequant -> bf16
+    outs = [torch.zeros(e.n, dtype=torch.bfloat16, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=DEV)
+    plan = E.entro_plan_init(ts, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws)
+    # GEMV -> fp32 (the third tensor's rows straddle segments: two kernels per launch)
+    xs = [torch.from_numpy(synth.make_x_bf16(7, i, e.cols).view(np.int16)).to(DEV).view(torch.bfloat16) for i, e in enumerate(encs)]
+    ys = [torch.zeros(e.rows, dtype=torch.float32, device=DEV) for e in encs]
+    dts_g = [E.to_device(e, DEV) for e in encs]
+    tg = [d.ctensor(y, x) for d, y, x in zip(dts_g, ys, xs)]
+    wsg = torch.zeros(max(256, E.entro_workspace_bytes(tg, E.ENTRO_OP_GEMV)), dtype=torch.uint8, device=DEV)
+    plan_g = E.entro_plan_init(tg, E.ENTRO_OP_GEMV, E.ENTRO_F32, wsg)
+    torch.cuda.synchronize()
+    E.entro_plan_run(plan)
+    E.entro_plan_run(plan_g)
+    torch.cuda.synchronize()
+    eager_o = [o.clone() for o in outs]
+    eager_y = [y.clone() for y in ys]
+    for e, q, o in zip(encs, refs_q, eager_o):
+        assert _bf16_ulp_diff(o.view(torch.int16).cpu().numpy().view(np.uint16),
+                              oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)).max() <= 1
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            E.entro_plan_run(plan)
+            E.entro_plan_run(plan_g)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(1.0)                                   # eager work between the replays
+        for y in ys:
+            y.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, ref in zip(outs, eager_o):
+            assert torch.equal(o.view(torch.int16), ref.view(torch.int16)), rep
+        for y, ref in zip(ys, eager_y):
+            assert torch.equal(y, ref), rep                # the row sums are taken in a fixed order: bit-identical
