@@ -202,7 +202,38 @@ def main():
         result["decode_u8"] = {"ms_per_step": round(w8, 4), "kernel_ms": round(k8, 4),
                                "symbols_per_s": round(n_sym / (w8 * 1e-3), 0),
                                "hbm_frac": round((stream_bytes + offset_bytes + n_sym) / (k8 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
-        del out_u8, v8, ts8, plan8
+        # the product on those plain bytes: the uint8 model that the entropy-coded one is compared with
+        log("timing the plain uint8 GEMV on the decoded bytes (comparison)")
+        xs_p = {c: torch.from_numpy(synth.make_x_bf16(0, c % 7, c).view(np.int16)).to(dev).view(torch.bfloat16)
+                for c in sorted({e.cols for e in encs})}
+        ys_p = [torch.zeros(e.rows, dtype=torch.float32, device=dev) for e in encs]
+
+        def plain_token():
+            for e, v, y in zip(encs, v8, ys_p):
+                E.entro_gemv_u8_plain(v, e.rows, e.cols, e.qp, xs_p[e.cols], y)
+
+        wpl, kpl = timed(plain_token, max(3, args.steps // 2), 1)
+        rngp = np.random.default_rng(99)
+        for _ in range(4):
+            i = int(rngp.integers(0, len(encs)))
+            e = encs[i]
+            r = int(rngp.integers(0, e.rows))
+            k0, k1 = (r * e.cols) // e.chunk_symbols, ((r + 1) * e.cols - 1) // e.chunk_symbols
+            q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k0, k1 - k0 + 1)
+            xh = xs_p[e.cols].view(torch.int16).cpu().numpy().view(np.uint16)
+            y_ref, _ = oracle.gemv(q[r * e.cols:(r + 1) * e.cols], 1, e.cols, e.qp.scale, e.qp.zero_point, xh)
+            yh = ys_p[i].cpu().numpy().astype(np.float64)
+            if abs(yh[r] - y_ref[0]) > 1e-3 * max(abs(y_ref[0]), np.sqrt(np.mean(yh ** 2))):
+                print(f"bench.py: plain uint8 GEMV differs from the oracle, tensor {e.name} row {r}", file=sys.stderr)
+                sys.exit(1)
+        result["gemv_plain_uint8"] = {"workload": "the same 224 products on the decoded weights stored one byte each (what the "
+                                                  "entropy-coded model is compared with), one launch per tensor",
+                                      "us_per_layer": round(wpl * 1e3 / args.layers, 2),
+                                      "kernel_us_per_layer": round(kpl * 1e3 / args.layers, 2),
+                                      "weight_GBps": round(n_sym / (kpl * 1e-3) / 1e9, 1),
+                                      "hbm_frac": round(n_sym / (kpl * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "verified_rows": 4}
+        log(f"plain uint8 gemv: {kpl * 1e3 / args.layers:.1f} us/layer")
+        del out_u8, v8, ts8, plan8, xs_p, ys_p
 
         log("timing entro_decode_gemv (batch-1 token step, 4 launches per layer)")
         groups = [(0, 3), (3, 4), (4, 6), (6, 7)]          # q,k,v | o | gate,up | down

@@ -308,6 +308,13 @@ entro_status entro_encode_device_status(uint32_t status_word);
 entro_status entro_stream_probe(const void *src, uint64_t read_bytes, void *dst, uint64_t write_bytes, void *scratch4,
                                 void *hip_stream);
 
+/* Comparison for the GEMV figures, not part of the path: y = s * W x on weights stored as plain bytes
+ * (q: device, rows * cols symbols one per byte, row-major; cols a multiple of 16; x: device, bf16[cols];
+ * y: device, float[rows]; all 16-byte aligned), the uint8 model that the paper's Table 3 compares the
+ * entropy-coded one with.  Bound by reading rows * cols bytes. */
+entro_status entro_gemv_u8_plain(const uint8_t *q, uint32_t rows, uint32_t cols, const entro_qparams *qp, const void *x, float *y,
+                                 void *hip_stream);
+
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char *entro_last_device_error(void);
 

@@ -102,6 +102,7 @@ def lib():
         "entro_decode_gemv_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_last_device_error": (C.c_char_p, []),
         "entro_stream_probe": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+        "entro_gemv_u8_plain": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(QParams), C.c_void_p, C.c_void_p, C.c_void_p]),
         "entro_range_device": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
         "entro_qparams_from_range": (C.c_int, [C.c_float, C.c_float, C.c_uint32, C.c_int, C.c_int, C.POINTER(QParams)]),
         "entro_scheme_for_range": (C.c_int, [C.c_float, C.c_float]),
@@ -125,7 +126,7 @@ EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_count
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
-            "entro_stream_probe", "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
+            "entro_stream_probe", "entro_gemv_u8_plain", "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
             "entro_encoded_bytes", "entro_encode_device", "entro_encode_device_status"]
 
 
@@ -359,6 +360,12 @@ def entro_stream_probe(src, read_bytes: int, dst, write_bytes: int, scratch, str
     """Calibration kernel: read read_bytes of src, write write_bytes of dst (torch device tensors)."""
     _check(lib().entro_stream_probe(src.data_ptr(), int(read_bytes), dst.data_ptr(), int(write_bytes), scratch.data_ptr(),
                                     _stream_ptr(stream)), "entro_stream_probe")
+
+
+def entro_gemv_u8_plain(q, rows: int, cols: int, qp: QParams, x, y, stream=None):
+    """Comparison kernel: y = s * (q - z) x on plain uint8 weights (torch device tensors)."""
+    _check(lib().entro_gemv_u8_plain(q.data_ptr(), rows, cols, C.byref(qp), x.data_ptr(), y.data_ptr(), _stream_ptr(stream)),
+           "entro_gemv_u8_plain")
 
 
 # ------------------------------------------------------- device-side compression

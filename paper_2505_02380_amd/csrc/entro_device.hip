@@ -1398,9 +1398,49 @@ void entro_detail_note_hip_error(const char *what, int hip_error) {
     hip_ok(static_cast<hipError_t>(hip_error), what);
 }
 
+// Comparison, not part of the path: the same product on weights that are stored as plain bytes.
+// One wavefront per matrix row, 16 weights per lane and load, the lanes' sums added by shuffles.
+__global__ __launch_bounds__(256) void k_gemv_u8_plain(const uint8_t *__restrict__ q, uint32_t rows, uint32_t cols, float scale,
+                                                       float zf, const uint16_t *__restrict__ x, float *__restrict__ y) {
+    const uint32_t lane = threadIdx.x & 63u;
+    for (uint32_t r = blockIdx.x * 4u + (threadIdx.x >> 6); r < rows; r += gridDim.x * 4u) {
+        const uint8_t *row = q + static_cast<uint64_t>(r) * cols;
+        float acc = 0.0f;
+        for (uint32_t c = lane * 16u; c < cols; c += 1024u) {
+            const u32x4 w = *(global_u4_ptr)(row + c);
+            const u32x4 xa = *(global_u4_ptr)(x + c), xb = *(global_u4_ptr)(x + c + 8u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4 xv = j < 2 ? xa : xb;
+                const uint32_t x01 = (j & 1) ? xv.z : xv.x, x23 = (j & 1) ? xv.w : xv.y;
+                acc = fmaf(static_cast<float>(w[j] & 0xffu) - zf, __uint_as_float(x01 << 16), acc);
+                acc = fmaf(static_cast<float>((w[j] >> 8) & 0xffu) - zf, __uint_as_float(x01 & 0xffff0000u), acc);
+                acc = fmaf(static_cast<float>((w[j] >> 16) & 0xffu) - zf, __uint_as_float(x23 << 16), acc);
+                acc = fmaf(static_cast<float>(w[j] >> 24) - zf, __uint_as_float(x23 & 0xffff0000u), acc);
+            }
+        }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) acc += __shfl_xor(acc, m, 64);
+        if (lane == 0) y[r] = acc * scale;
+    }
+}
+
 extern "C" {
 
 const char *entro_last_device_error(void) { return g_last_error.c_str(); }
+
+entro_status entro_gemv_u8_plain(const uint8_t *q, uint32_t rows, uint32_t cols, const entro_qparams *qp, const void *x, float *y,
+                                 void *hip_stream) {
+    if (!q || !qp || !x || !y) return ENTRO_ERR_NULL;
+    if (rows == 0 || cols == 0 || (cols & 15u)) return ENTRO_ERR_SIZE;
+    if (!aligned16(q) || !aligned16(x) || !aligned16(y)) return ENTRO_ERR_ALIGN;
+    if (qp->zero_point > (1 << 24) || qp->zero_point < -(1 << 24)) return ENTRO_ERR_RANGE;
+    const unsigned grid = std::min<unsigned>((rows + 3u) / 4u, 256u * 8u);
+    hipLaunchKernelGGL(k_gemv_u8_plain, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream), q, rows, cols,
+                       qp->scale, static_cast<float>(qp->zero_point), static_cast<const uint16_t *>(x), y);
+    if (!hip_ok(hipGetLastError(), "launch plain GEMV")) return ENTRO_ERR_DEVICE;
+    return ENTRO_OK;
+}
 
 entro_status entro_stream_probe(const void *src, uint64_t read_bytes, void *dst, uint64_t write_bytes, void *scratch4,
                                 void *hip_stream) {

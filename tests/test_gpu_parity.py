@@ -582,3 +582,17 @@ def test_prepared_launches_replay_in_a_hip_graph():
             assert torch.equal(o.view(torch.int16), ref.view(torch.int16)), rep
         for y, ref in zip(ys, eager_y):
             assert torch.equal(y, ref), rep                # the row sums are taken in a fixed order: bit-identical
+
+
+def test_plain_uint8_gemv_comparison_kernel_matches_the_oracle():
+    for rows, cols in [(300, 4096), (7, 14336), (1000, 64), (33, 1040)]:
+        rng = np.random.default_rng(rows)
+        q = np.minimum(rng.geometric(0.05, rows * cols) - 1, 255).astype(np.uint8)
+        xb = synth.make_x_bf16(2, rows % 5, cols)
+        y_ref, _ = oracle.gemv(q, rows, cols, np.float32(0.013), 21, xb)
+        y = torch.full((rows + 4,), 9.0, dtype=torch.float32, device=DEV)
+        E.entro_gemv_u8_plain(torch.from_numpy(q).to(DEV), rows, cols, B.QParams(np.float32(0.013), 21, 8, 1),
+                              torch.from_numpy(xb.view(np.int16)).to(DEV).view(torch.bfloat16), y)
+        got = y.cpu().numpy()
+        assert np.all(got[rows:] == 9.0)
+        _assert_gemv_close(got[:rows].astype(np.float64), y_ref)
