@@ -606,6 +606,12 @@ def main():
         result["cpu_baseline_threads"] = {"value": round(syms * 2 / t_par / 1e9, 4), "unit": "GB/s", "cores": n_thr,
                                           "kind": "oracle", "sample": "the same tensors, one oracle call per tensor and thread",
                                           "symbols_per_s": round(syms / t_par, 0)}
+    # the paper's own figures, from another machine: context beside the numbers above, not a target
+    result["paper_context"] = {"hardware": "NVIDIA Jetson P3450, Huffman decode on 4 Cortex-A57 threads (Table 3)",
+                               "decode_whole_model_s": {"uint8": 6.66, "uint4": 1.66, "params": 3.8e9},
+                               "decode_G_symbols_per_s": {"uint8": 0.57, "uint4": 2.29},
+                               "token_generation_speedup": {"uint8": 1.32, "uint4": 2.47},
+                               "effective_bits": {"uint8": 5.58, "uint4": 1.39}}
     print(json.dumps(result), flush=True)
 
 
