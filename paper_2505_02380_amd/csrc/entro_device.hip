@@ -1406,6 +1406,7 @@ __global__ __launch_bounds__(256) void k_gemv_u8_plain(const uint8_t *__restrict
     for (uint32_t r = blockIdx.x * 4u + (threadIdx.x >> 6); r < rows; r += gridDim.x * 4u) {
         const uint8_t *row = q + static_cast<uint64_t>(r) * cols;
         float acc = 0.0f;
+#pragma unroll 4
         for (uint32_t c = lane * 16u; c < cols; c += 1024u) {
             const u32x4 w = *(global_u4_ptr)(row + c);
             const u32x4 xa = *(global_u4_ptr)(x + c), xb = *(global_u4_ptr)(x + c + 8u);
