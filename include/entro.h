@@ -215,6 +215,17 @@ uint64_t entro_gemv_workspace_bytes(const entro_tensor *t);
 entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *workspace,
                                uint64_t workspace_bytes, void *hip_stream);
 
+/* entro_decode_gemv for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and
+ * results as entro_decode_gemv; the partial sums of rows that straddle segments live in an array
+ * inside the library's device image (8 * ENTRO_STATIC_GEMV_MAX_SEGMENTS bytes per GPU, held until the
+ * process ends) instead of a workspace.  The call allocates nothing and only enqueues kernels.
+ * ENTRO_ERR_CAPACITY if the tensor needs partial sums and has more than
+ * ENTRO_STATIC_GEMV_MAX_SEGMENTS segments.  All calls on one GPU share the array: calls that may
+ * overlap there (different streams, or graphs replayed concurrently) race; order them. */
+#define ENTRO_STATIC_GEMV_MAX_SEGMENTS 65536
+entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type, void *hip_stream);
+
 /* Batched forms: ONE launch over `count` tensors (a single tensor has too few
  * segments to fill 256 compute units).  The descriptor table, the work list
  * and the GEMV partial sums live in `workspace` (device). */

@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     entro_codebook_from_counts_limited, entro_build_codebook_limited,
     entro_num_chunks, entro_encode_bound, entro_encode, entro_check_offsets,
     entro_bits_saved, entro_theoretical_speedup, entro_status_string,
-    entro_decode, entro_decode_dequant, entro_decode_gemv, entro_gemv_workspace_bytes,
+    entro_decode, entro_decode_dequant, entro_decode_gemv, entro_decode_gemv_static, entro_gemv_workspace_bytes,
     entro_workspace_bytes, entro_plan_init, entro_plan_run,
     entro_decode_batch, entro_decode_dequant_batch, entro_decode_gemv_batch,
     entro_last_device_error, entro_stream_probe, entro_gemv_u8_plain, encode_tensor, to_device,

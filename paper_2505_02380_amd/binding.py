@@ -94,6 +94,7 @@ def lib():
         "entro_decode_dequant": (C.c_int, [tp, C.c_int, C.c_void_p]),
         "entro_gemv_workspace_bytes": (C.c_uint64, [tp]),
         "entro_decode_gemv": (C.c_int, [tp, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
+        "entro_decode_gemv_static": (C.c_int, [tp, C.c_int, C.c_void_p]),
         "entro_workspace_bytes": (C.c_uint64, [tp, C.c_uint32, C.c_int]),
         "entro_plan_init": (C.c_int, [pp, tp, C.c_uint32, C.c_int, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_plan_run": (C.c_int, [pp, C.c_void_p]),
@@ -123,7 +124,7 @@ def lib():
 EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_counts",
             "entro_codebook_from_lengths", "entro_codebook_from_counts_limited", "entro_build_codebook_limited", "entro_num_chunks", "entro_encode_bound", "entro_encode",
             "entro_check_offsets", "entro_bits_saved", "entro_theoretical_speedup", "entro_status_string",
-            "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv",
+            "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv", "entro_decode_gemv_static",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
             "entro_stream_probe", "entro_gemv_u8_plain", "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
@@ -329,6 +330,10 @@ def entro_decode_gemv(t: CTensor, y_type: int, workspace=None, stream=None):
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().entro_decode_gemv(C.byref(t), y_type, ws_ptr, ws_bytes, _stream_ptr(stream)), "entro_decode_gemv")
+
+
+def entro_decode_gemv_static(t: CTensor, y_type: int, stream=None):
+    _check(lib().entro_decode_gemv_static(C.byref(t), y_type, _stream_ptr(stream)), "entro_decode_gemv_static")
 
 
 def entro_workspace_bytes(ts: Sequence[CTensor], op: int) -> int:

@@ -28,8 +28,14 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
+
+// Partial sums of entro_decode_gemv_static: two floats per segment.  Every GPU the library runs on holds
+// its own copy of this array until the process ends.  In host code the name stands for the symbol only;
+// the array's address on a device comes from hipGetSymbolAddress (static_scratch below).
+static __device__ __align__(256) float scratch[2 * ENTRO_STATIC_GEMV_MAX_SEGMENTS];
 
 namespace {
 
@@ -1344,6 +1350,27 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     return ENTRO_OK;
 }
 
+// Device address of `scratch` on the current device, looked up once per device; nullptr if the
+// lookup fails (the error text is kept for entro_last_device_error).
+float *static_scratch() {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static float *ptrs[kMaxDevices] = {};
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        g_last_error = "device index beyond the static scratch table";
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> guard(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return nullptr;
+        ptrs[dev] = static_cast<float *>(p);
+    }
+    return ptrs[dev];
+}
+
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
@@ -1483,6 +1510,17 @@ entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *
         if (!aligned16(workspace)) return ENTRO_ERR_ALIGN;
     }
     return launch_single(t, ENTRO_OP_GEMV, y_type, static_cast<float *>(workspace), hip_stream);
+}
+
+entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type, void *hip_stream) {
+    if (!t) return ENTRO_ERR_NULL;
+    float *partials = nullptr;
+    if (entro_gemv_workspace_bytes(t)) {
+        if (entro_num_chunks(t->n, t->chunk_symbols) > ENTRO_STATIC_GEMV_MAX_SEGMENTS) return ENTRO_ERR_CAPACITY;
+        partials = static_scratch();
+        if (!partials) return ENTRO_ERR_DEVICE;
+    }
+    return launch_single(t, ENTRO_OP_GEMV, y_type, partials, hip_stream);
 }
 
 uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op) {
