@@ -51,6 +51,8 @@ constexpr int kTripGroups = 4;           // ring reads between two checks of the
 constexpr int kScalarProbes = 2;         // scalar reader: symbols per 64-bit load, 33 valid bits >= 2 * kL1
 constexpr int kRingBits = 1024;          // a lane's ring: two 64-byte lines (eight 16-byte blocks)
 constexpr int kRingDwords = kRingBits / 32 + 2;   // and two mirror dwords
+constexpr int kRing2Bits = 512;          // the short ring: four blocks
+constexpr int kRing2Dwords = kRing2Bits / 32 + 2;
 constexpr int kGroupBits = kGroup * kL1;           // most stream bits a group takes through the first level
 constexpr int kTripBits = (kTripGroups - 1) * kGroupBits + 64;   // a trip's last ring read ends this far past its start
 constexpr uint32_t kMaxChunkSymbols = 1u << 20;
@@ -99,17 +101,17 @@ constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == 
 // in memory.  The host glue sizes its launches with the same numbers.  The GEMV
 // has no tile (only spb, the symbols between two ring refills, and waves count).
 template <int MODE> struct Cfg;
-template <> struct Cfg<kModeU8> { static constexpr int spb = 64, row = 64, waves = 10, piece = 16, out_row = 64; };
-template <> struct Cfg<kModeU4> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 64; };
-template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 256; };
-template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 10, piece = 8, out_row = 128; };
+template <> struct Cfg<kModeU8> { static constexpr int spb = 64, row = 64, waves = 14, piece = 16, out_row = 64; };
+template <> struct Cfg<kModeU4> { static constexpr int spb = 128, row = 64, waves = 14, piece = 16, out_row = 64; };
+template <> struct Cfg<kModeF32> { static constexpr int spb = 64, row = 64, waves = 16, piece = 8, out_row = 256; };
+template <> struct Cfg<kModeBF16> { static constexpr int spb = 64, row = 64, waves = 16, piece = 8, out_row = 128; };
 template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvF32P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
-template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 16, out_row = 128; };
-template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 512; };
-template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 10, piece = 8, out_row = 256; };
+template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 16, out_row = 128; };
+template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 512; };
+template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 256; };
 // Packed 4-bit output decodes two symbols per lookup, and so do the P modes.
 template <int MODE> constexpr bool kPairMode = MODE == kModeU4 || MODE == kModeU8P || MODE == kModeF32P || MODE == kModeBF16P ||
                                                MODE == kModeGemvF32P || MODE == kModeGemvBF16P;
@@ -156,13 +158,25 @@ template <int ROW>
 struct alignas(256) WaveMem {
     static constexpr int row_dwords = ROW / 4;
     static_assert(row_dwords == 16 || row_dwords == 32, "the rotation below is made for these");
-    uint32_t ring[kRingDwords * 64];
+    uint32_t ring[kRing2Dwords * 64];
     uint32_t tile[64 * row_dwords];
     // rows of 16 dwords alternate between the two halves of the 32 banks, so pairs of rows share a rotation
     static __device__ __forceinline__ uint32_t tile_rot(uint32_t row) { return row_dwords == 16 ? row >> 1 : row; }
     // where dword j of row `row` lives
     static __device__ __forceinline__ uint32_t tile_at(uint32_t row, uint32_t j) {
         return row * row_dwords + ((j + tile_rot(row)) & (row_dwords - 1));
+    }
+};
+
+// Per-wave LDS of the kernels that use the short ring: 64 bytes of stream per lane and rows of 32
+// symbol bytes.  Row r is rotated by 2 * ((r >> 2) & 3) dwords, which keeps its dword pairs aligned
+// and spreads rows four apart (which start on the same bank) over the banks.
+struct alignas(256) WaveMem2 {
+    static constexpr int row_dwords = 8;
+    uint32_t ring[18 * 64];
+    uint32_t tile[64 * row_dwords];
+    static __device__ __forceinline__ uint32_t tile_at(uint32_t row, uint32_t j) {
+        return row * row_dwords + ((j + 2u * ((row >> 2) & 3u)) & (row_dwords - 1));
     }
 };
 
@@ -611,6 +625,111 @@ __device__ __forceinline__ uint64_t ring_read(const RingReader<LB> &r) {
     return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
+// ------------------------------------------------------------- short ring reader
+// The same reader with half the LDS, for the kernels whose wavefront count is what limits them
+// (a lane's chain of dependent table lookups is bound by LDS latency, so the number of lanes a
+// compute unit keeps decoding is its throughput, and LDS is what limits that number): a ring of
+// four 16-byte blocks per lane (block j in slot j & 3, dwords 16 and 17 mirror dwords 0 and 1)
+// and registers moving into the ring after every 32 symbols instead of 64.  The registers still
+// hold a whole 128-byte line (asking memory for 64 bytes at a time reads every line twice).  Block
+// i of a line goes to slot i & 3, so the moves are four statically addressed steps, each taken by
+// the lanes whose next block belongs into that slot and whose slot is free.  A lane asks for its
+// next line when the last block of the current one has moved; it is used from the next boundary
+// on, one wait for the whole wavefront.
+struct Ring2 {
+    const uint8_t *stream;
+    lds_v32 ring;          // this lane's dword 0; dword d is ring[d * 64]
+    uint32_t start64;      // byte offset of line 0 (a multiple of 128)
+    uint32_t last_blk;     // stream_bytes - 16
+    uint32_t q;            // p - 1, in bits from line 0
+    uint32_t end;          // the ring holds the stream up to here; a multiple of 128, at most kRing2Bits past p's block
+    u32x4 nx[8];           // the line that holds block end >> 7
+};
+
+template <int SLOT>
+__device__ __forceinline__ void ring2_store(Ring2 &r, const u32x4 v) {
+    lds_v32 dst = r.ring + SLOT * 256;
+    dst[0] = v.x; dst[64] = v.y; dst[128] = v.z; dst[192] = v.w;
+    if (SLOT == 0) { r.ring[16 * 64] = v.x; r.ring[17 * 64] = v.y; }
+}
+
+__device__ __forceinline__ void ring2_load_line(Ring2 &r, uint32_t line) {
+    const uint32_t base = r.start64 + line * 128u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r.nx[i] = load_block(r.stream, base + 16u * i, r.last_blk);
+}
+
+// Fill the ring with the four blocks from the one that holds absolute stream bit `pos` on and ask
+// for the line that holds the block after them (line 0 again, if they end inside it).
+template <bool RARE>
+__device__ __forceinline__ void ring2_fill(Ring2 &r, uint64_t pos) {
+    r.start64 = static_cast<uint32_t>(pos >> 3) & ~127u;
+    r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - 1u;
+    const uint32_t first = (r.q + 1u) >> 7;                          // 0..7
+    r.end = (first + 4u) * 128u;
+    if (RARE) {
+#pragma unroll 1
+        for (uint32_t b = first; b < first + 4u; ++b) {
+            const u32x4 v = load_block(r.stream, r.start64 + 16u * b, r.last_blk);
+            lds_v32 dst = r.ring + (b & 3u) * 256u;
+            dst[0] = v.x; dst[64] = v.y; dst[128] = v.z; dst[192] = v.w;
+            if ((b & 3u) == 0) { r.ring[16 * 64] = v.x; r.ring[17 * 64] = v.y; }
+        }
+    } else {
+        u32x4 v[4];
+#pragma unroll
+        for (uint32_t b = 0; b < 4; ++b) v[b] = load_block(r.stream, r.start64 + 16u * (first + b), r.last_blk);
+#pragma unroll
+        for (uint32_t b = 0; b < 4; ++b) {
+            lds_v32 dst = r.ring + ((first + b) & 3u) * 256u;
+            dst[0] = v[b].x; dst[64] = v[b].y; dst[128] = v[b].z; dst[192] = v[b].w;
+            if (((first + b) & 3u) == 0) { r.ring[16 * 64] = v[b].x; r.ring[17 * 64] = v[b].y; }
+        }
+    }
+    ring2_load_line(r, r.end >> 10);
+}
+
+__device__ __forceinline__ bool ring_short(const Ring2 &r, uint32_t ahead) { return r.q + ahead + 64u >= r.end; }
+
+__device__ __forceinline__ void ring_reload(Ring2 &r) {
+    ring2_fill<true>(r, (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u);
+}
+
+template <int J>
+__device__ __forceinline__ void ring2_step(Ring2 &r, uint32_t pblk, bool &wants_line) {
+    if (((r.end >> 7) & 3u) == J && r.end - pblk <= kRing2Bits - 128u) {
+        const bool upper = (r.end >> 9) & 1u;                        // the line's second half
+        u32x4 v;
+        v.x = upper ? r.nx[J + 4].x : r.nx[J].x;
+        v.y = upper ? r.nx[J + 4].y : r.nx[J].y;
+        v.z = upper ? r.nx[J + 4].z : r.nx[J].z;
+        v.w = upper ? r.nx[J + 4].w : r.nx[J].w;
+        ring2_store<J>(r, v);
+        r.end += 128u;
+        if (J == 3 && upper) wants_line = true;
+    }
+}
+
+// Between two half blocks of output: registers into the slots p has left behind, then the request for the
+// next line by the lanes whose registers are used up.
+__device__ __forceinline__ void ring2_topup(Ring2 &r) {
+    const uint32_t pblk = ((r.q + 1u) >> 7) << 7;
+    bool wants_line = false;
+    ring2_step<0>(r, pblk, wants_line);
+    ring2_step<1>(r, pblk, wants_line);
+    ring2_step<2>(r, pblk, wants_line);
+    ring2_step<3>(r, pblk, wants_line);
+    if (wants_line) ring2_load_line(r, r.end >> 10);
+}
+
+__device__ __forceinline__ uint64_t ring_read(const Ring2 &r) {
+    const lds_p32 src = (lds_p32)(r.ring + ((r.q >> 5) & 15u) * 64u);
+    const uint32_t w0 = src[0], w1 = src[64], w2 = src[128];
+    const uint32_t lo = __builtin_amdgcn_alignbit(w1, w0, r.q);
+    const uint32_t hi = __builtin_amdgcn_alignbit(w2, w1, r.q);
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
 __device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) {
     return *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
 }
@@ -625,8 +744,8 @@ __device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) 
 // With pair tables a miss is a pair that the index bits do not hold in full: its
 // two codes, and whatever pair after it misses again, come from the table of
 // single codes, every one with a window of its own.
-template <bool PAIR, int LB>
-__device__ __forceinline__ uint32_t careful_group(RingReader<LB> &r, const Tables &tb, uint32_t max_len, uint32_t e0,
+template <bool PAIR, class Reader>
+__device__ __forceinline__ uint32_t careful_group(Reader &r, const Tables &tb, uint32_t max_len, uint32_t e0,
                                                   uint32_t e1, uint32_t e2, uint32_t e3, uint64_t w, uint32_t packed) {
     const uint32_t l0 = entry_len(e0), l1 = entry_len(e1), l2 = entry_len(e2);
     const uint32_t at = l0 == 0 ? 0u : l1 == 0 ? 1u : l2 == 0 ? 2u : 3u;     // place of the long code
@@ -693,8 +812,8 @@ __device__ __forceinline__ uint32_t careful_group(RingReader<LB> &r, const Table
 // bits and give the same entry of length zero); if the wave has such a lane, the
 // rest of its group is decoded with more care.  Returns the group's four symbols,
 // first one lowest.
-template <bool PAIR, int LB>
-__device__ __forceinline__ uint32_t ring_group(RingReader<LB> &r, const Tables &tb, uint32_t max_len) {
+template <bool PAIR, class Reader>
+__device__ __forceinline__ uint32_t ring_group(Reader &r, const Tables &tb, uint32_t max_len) {
     uint64_t w = ring_read(r);
     const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
     w >>= (e0 & 63u);
@@ -757,13 +876,12 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const bool fast = nsym != 0;
     const uint32_t my_blocks = nsym / SPB;
     uint64_t tail_pos = fast ? t.offsets[k] : 0;          // where the symbols behind the lane's last whole block start
-    // memory serves a scattered 128-byte request far better than two of 64 bytes at different times
-    RingReader<8> r;
+    Ring2 r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(wm.ring + lane);
     // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
-    ring_load(r, fast ? t.offsets[k] : 0);
+    ring2_fill<false>(r, fast ? t.offsets[k] : 0);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
     const uint32_t n_full = static_cast<uint32_t>(t.n / C);          // segments of full length
     // whole blocks of the shorter last segment, if there is one
@@ -788,9 +906,10 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
 #pragma unroll
             for (int g = 0; g < kTripGroups; ++g)
                 tile[WaveMem<ROW>::tile_at(lane, trip * kTripGroups + g)] = ring_group<PAIR>(r, tb, max_len);
+            // the short ring is topped up after every eight groups
+            if (trip & 1) ring2_topup(r);
         }
         if (bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
-        ring_topup(r);
         wave_sync_lds();
 #pragma unroll
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
@@ -883,6 +1002,116 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     }
     const uint32_t rest = nsym - my_blocks * SPB;
     if (rest) decode_scalar_from<MODE>(t, tb, tail_pos, static_cast<uint64_t>(k) * C + my_blocks * SPB, rest);
+}
+
+// decode_rows for the fp32 and bf16 outputs, on the short ring: sixteen wavefronts per workgroup
+// instead of ten.  A block of 64 symbols per lane is decoded and flushed in two halves of 32.  A
+// half makes 128 bytes of fp32 per row, which go out as they are; of bf16 it makes 64, so the first
+// half's symbols wait in registers (in the lanes that will convert them) and the second half's flush
+// writes whole 128-byte rows.
+// ALLFULL: the unit's 64 segments all have full length (decided per wavefront): no store needs a
+// condition, no lane a tail.
+template <int MODE, bool ALLFULL>
+__device__ __forceinline__ void decode_rows2_impl(const DevTensor &t, const Tables &tb, WaveMem2 &wm, uint32_t wave_first) {
+    static_assert(MODE == kModeF32 || MODE == kModeBF16, "single codes, two or four bytes per symbol");
+    constexpr int SPB = Cfg<MODE>::spb;                   // 64
+    constexpr uint32_t EBITS = OutTraits<MODE>::ebits;
+    constexpr int HALF_GROUPS = 8;                        // groups of four symbols per half block
+    static_assert(SPB == 64 && HALF_GROUPS * kGroup * 2 == SPB && HALF_GROUPS % kTripGroups == 0, "two halves of two trips");
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t C = t.chunk_symbols;
+    const uint32_t blocks_total = C / SPB;
+    const uint32_t k = wave_first + lane;
+    uint32_t nsym = C;
+    if (!ALLFULL) {
+        nsym = 0;
+        if (k < t.n_chunks) {
+            const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
+            nsym = left < C ? static_cast<uint32_t>(left) : C;
+        }
+    }
+    const bool fast = nsym != 0;
+    const uint32_t my_blocks = nsym / SPB;
+    uint64_t tail_pos = fast ? t.offsets[k] : 0;
+    Ring2 r;
+    r.stream = t.stream;
+    r.last_blk = t.stream_bytes - 16u;
+    r.ring = (lds_v32)(wm.ring + lane);
+    ring2_fill<false>(r, tail_pos);
+    const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
+    const uint32_t n_full = static_cast<uint32_t>(t.n / C);
+    const uint32_t tail_blocks = static_cast<uint32_t>((t.n - static_cast<uint64_t>(n_full) * C) / SPB);
+    const uint32_t wave_blocks = ALLFULL || wave_first < n_full ? blocks_total : tail_blocks;
+    // a flush pass serves eight rows, eight lanes each; the passes are eight rows apart
+    const uint32_t piece = lane & 7u;
+    uint8_t *const row0 = static_cast<uint8_t *>(t.out) + (wave_first + (lane >> 3)) * bytes_per_chunk + piece * 16u;
+    const uint32_t max_len = t.max_len;
+    const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
+    const float scale = t.scale;
+    lds_v32 tile = (lds_v32)wm.tile;
+    typedef const u32x2 __attribute__((address_space(3))) *lds_p64;
+    u32x2 held[8];                                        // bf16: the first half's eight symbols of each pass
+    for (uint32_t bs = 0; bs < wave_blocks; ++bs) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll 1
+            for (int trip = 0; trip < HALF_GROUPS / kTripGroups; ++trip) {
+                if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
+#pragma unroll
+                for (int g = 0; g < kTripGroups; ++g)
+                    tile[WaveMem2::tile_at(lane, trip * kTripGroups + g)] = ring_group<false>(r, tb, max_len);
+            }
+            if (!ALLFULL && half == 1 && bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
+            ring2_topup(r);
+            wave_sync_lds();
+#pragma unroll
+            for (uint32_t it = 0; it < 8; ++it) {
+                const uint32_t rr = it * 8u + (lane >> 3);
+                const uint32_t kk = wave_first + rr;
+                const bool full = ALLFULL || kk < n_full || (kk == n_full && bs < tail_blocks);
+                uint8_t *const dst = row0 + static_cast<uint64_t>(it) * (8u * bytes_per_chunk);
+                if constexpr (MODE == kModeF32) {
+                    const uint32_t raw = tile[WaveMem2::tile_at(rr, piece)];
+                    u32x4 v;
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; ++j)
+                        v[j] = __float_as_uint((static_cast<float>((raw >> (8 * j)) & 0xffu) - zf) * scale);
+                    if (full) *(global_u4_wptr)(dst + (static_cast<uint64_t>(bs) * 2u + half) * 128u) = v;
+                } else {
+                    // lanes 0..3 of a row convert the first half's symbols, lanes 4..7 the second half's
+                    const u32x2 raw = *(lds_p64)(wm.tile + WaveMem2::tile_at(rr, 2u * (piece & 3u)));
+                    if (half == 0) {
+                        held[it] = raw;
+                    } else {
+                        const u32x2 sym8 = piece < 4u ? held[it] : raw;
+                        u32x4 v;
+#pragma unroll
+                        for (uint32_t j = 0; j < 4; ++j) {
+                            const uint32_t d = sym8[j / 2];
+                            const f32x2 pr = {(static_cast<float>((d >> (16 * (j & 1))) & 0xffu) - zf) * scale,
+                                              (static_cast<float>((d >> (16 * (j & 1) + 8)) & 0xffu) - zf) * scale};
+                            v[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));   // round to nearest even
+                        }
+                        if (full) __builtin_nontemporal_store(v, (global_u4_wptr)(dst + static_cast<uint64_t>(bs) * 128u));
+                    }
+                }
+            }
+            wave_sync_lds();
+        }
+    }
+    if (!ALLFULL) {
+        const uint32_t rest = nsym - my_blocks * SPB;
+        if (rest) decode_scalar_from<MODE>(t, tb, tail_pos, static_cast<uint64_t>(k) * C + my_blocks * SPB, rest);
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void decode_rows2(const DevTensor &t, const Tables &tb, WaveMem2 *wms, uint32_t wave_first) {
+    if (wave_first >= t.n_chunks) return;
+    WaveMem2 &wm = wms[threadIdx.x >> 6];
+    const uint32_t n_full = static_cast<uint32_t>(t.n / t.chunk_symbols);
+    if (wave_first + kUnit <= n_full) decode_rows2_impl<MODE, true>(t, tb, wm, wave_first);
+    else decode_rows2_impl<MODE, false>(t, tb, wm, wave_first);
 }
 
 // Decode one segment straight into dot products with x.  A segment covers one
@@ -1059,8 +1288,11 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
 
 // The GEMV kernels need the tables and the scratch table only.
 struct alignas(256) RingMem { uint32_t ring[kRingDwords * 64]; };
-template <int MODE, bool GEMV = is_gemv(MODE)> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
-template <int MODE> struct SmemFor<MODE, true> { Tables tb; RingMem wm[Cfg<MODE>::waves]; };
+// which modes decode on the short ring (decode_rows2)
+constexpr bool short_ring(int mode) { return mode == kModeF32 || mode == kModeBF16; }
+template <int MODE, bool GEMV = is_gemv(MODE), bool SHORT = short_ring(MODE)> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor<MODE, true, false> { Tables tb; RingMem wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor<MODE, false, true> { Tables tb; WaveMem2 wm[Cfg<MODE>::waves]; };
 
 // Does the tensor go through decode_rows?  Segments must tile into blocks; for the
 // GEMV, pieces of eight must not straddle a matrix row and a segment must touch at
@@ -1091,7 +1323,7 @@ __device__ __forceinline__ void scalar_chunks(const DevTensor &t, const Tables &
 // (kUnit segments each, one unit per wavefront; at most as many as it has
 // wavefronts) from unit b * wg_units on.
 template <int MODE>
-__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t, uint32_t wg_units) {
+__device__ __forceinline__ void single_body(const DevTensor &t, uint32_t wg_units) {
     constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     __shared__ SmemFor<MODE> sm;
     // the per-wave symbol counts of the build live in the first wave's buffers, which are not in use yet
@@ -1101,6 +1333,7 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTenso
         const uint32_t wave = threadIdx.x >> 6;
         if (wave < wg_units) {
             if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
+            else if constexpr (short_ring(MODE)) decode_rows2<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
             else decode_rows<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
         }
     } else {
@@ -1119,9 +1352,8 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTenso
 // SIMDs, three on two of them and two on the others), so a fixed split would
 // leave the faster ones waiting.
 template <int MODE>
-__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor *__restrict__ tensors,
-                                                                 const WorkItem *__restrict__ items, uint32_t n_items,
-                                                                 uint32_t item_units) {
+__device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors, const WorkItem *__restrict__ items,
+                                           uint32_t n_items, uint32_t item_units) {
     constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     __shared__ SmemFor<MODE> sm;
     __shared__ uint32_t next_unit;
@@ -1146,6 +1378,7 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor
                 u = __builtin_amdgcn_readfirstlane(u);
                 if (u >= n_units) break;
                 if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
+                else if constexpr (short_ring(MODE)) decode_rows2<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
                 else decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
             }
         } else {
@@ -1154,6 +1387,17 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor
         }
         i += (n_units + item_units - 1) / item_units;
     }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_single(const DevTensor t, uint32_t wg_units) {
+    single_body<MODE>(t, wg_units);
+}
+template <int MODE>
+__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor *__restrict__ tensors,
+                                                                 const WorkItem *__restrict__ items, uint32_t n_items,
+                                                                 uint32_t item_units) {
+    batch_body<MODE>(tensors, items, n_items, item_units);
 }
 
 // Second stage of the GEMV: rows that straddle segments are summed in segment order.
@@ -1229,7 +1473,8 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     if (!dtype_ok(op, d, bits)) return ENTRO_ERR_SCHEME;
     if (t->n == 0 || t->chunk_symbols == 0 || t->chunk_symbols > kMaxChunkSymbols) return ENTRO_ERR_SIZE;
     if (d == ENTRO_U4_PACKED && (t->chunk_symbols & 1u)) return ENTRO_ERR_SIZE;
-    if (t->stream_bytes < 32 || (t->stream_bytes & 15u) || t->stream_bytes >= (uint64_t{1} << 32))
+    // offsets into the stream are 32-bit numbers in the kernels, with room for a line or two past the end
+    if (t->stream_bytes < 32 || (t->stream_bytes & 15u) || t->stream_bytes >= (uint64_t{1} << 32) - 65536)
         return ENTRO_ERR_SIZE;
     const uint64_t n_chunks = entro_num_chunks(t->n, t->chunk_symbols);
     if (n_chunks >= (uint64_t{1} << 32) - 1024) return ENTRO_ERR_SIZE;
@@ -1338,7 +1583,8 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     const unsigned wg_units = std::min(wg / 64u, std::max(1u, units / slots));
     const unsigned grid = (units + wg_units - 1) / wg_units;
     dispatch_mode(mode, [&](auto m) {
-        hipLaunchKernelGGL(k_single<decltype(m)::value>, dim3(grid), dim3(wg), 0, s, dt, static_cast<uint32_t>(wg_units));
+        constexpr int M = decltype(m)::value;
+        hipLaunchKernelGGL(k_single<M>, dim3(grid), dim3(wg), 0, s, dt, static_cast<uint32_t>(wg_units));
     });
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
@@ -1604,8 +1850,8 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const unsigned grid = plan->n_items < slots ? plan->n_items : slots;
     dispatch_mode(mode, [&](auto m) {
-        hipLaunchKernelGGL(k_batch<decltype(m)::value>, dim3(grid), dim3(wg_of(mode)), 0, s, dts, items,
-                           plan->n_items, plan->item_units);
+        constexpr int M = decltype(m)::value;
+        hipLaunchKernelGGL(k_batch<M>, dim3(grid), dim3(wg_of(mode)), 0, s, dts, items, plan->n_items, plan->item_units);
     });
     if (!hip_ok(hipGetLastError(), "launch batched decode kernel")) return ENTRO_ERR_DEVICE;
     if (plan->n_fix) {
