@@ -47,6 +47,9 @@ def lib():
         L.oracle_decode_chunks.argtypes = [u8p, C.c_uint64, u64p, C.c_uint64, C.c_uint32, u8p, u32p, C.c_int,
                                            C.c_uint64, C.c_uint64, u8p]
         L.oracle_decode.argtypes = [u8p, C.c_uint64, u64p, C.c_uint64, C.c_uint32, u8p, u32p, C.c_int, u8p]
+        L.oracle_sub_index.argtypes = [u8p, C.c_uint64, u8p, C.c_int, C.c_uint32, C.c_uint32, u16p]
+        L.oracle_decode_subs.argtypes = [u8p, C.c_uint64, u64p, u16p, C.c_uint64, C.c_uint32, C.c_uint32, u8p, u32p, C.c_int,
+                                         C.c_uint64, C.c_uint64, u8p]
         L.oracle_pack_u4.argtypes = [u8p, C.c_uint64, u8p]
         L.oracle_pack_u4.restype = None
         L.oracle_dequant_f32.argtypes = [u8p, C.c_uint64, C.c_float, C.c_int32, f32p]
@@ -155,6 +158,32 @@ def decode_chunks(stream, offsets, n: int, chunk_symbols: int, ln, code, first_c
     _check(lib().oracle_decode_chunks(_p(stream, C.c_uint8), stream.size, _p(offsets, C.c_uint64), n,
                                       chunk_symbols, _p(ln, C.c_uint8), _p(code, C.c_uint32), ln.size,
                                       first_chunk, num_chunks, _p(out, C.c_uint8)), "decode_chunks")
+    return out
+
+
+def sub_index(q, ln, chunk_symbols: int, sub_symbols: int) -> np.ndarray:
+    """-> uint16[ceil(n / sub_symbols)]: stream bits of every piece of sub_symbols symbols."""
+    q = _c(q, np.uint8).ravel()
+    ln = _c(ln, np.uint8)
+    out = np.zeros((q.size + sub_symbols - 1) // sub_symbols, np.uint16)
+    _check(lib().oracle_sub_index(_p(q, C.c_uint8), q.size, _p(ln, C.c_uint8), ln.size, chunk_symbols, sub_symbols,
+                                  _p(out, C.c_uint16)), "sub_index")
+    return out
+
+
+def decode_subs(stream, offsets, sub_bits, n: int, chunk_symbols: int, sub_symbols: int, ln, code, first_sub: int,
+                num_subs: int, out: np.ndarray | None = None) -> np.ndarray:
+    """Decode only pieces [first_sub, first_sub + num_subs), each from its own entry point."""
+    stream = _c(stream, np.uint8)
+    offsets = _c(offsets, np.uint64)
+    sub_bits = _c(sub_bits, np.uint16)
+    ln = _c(ln, np.uint8)
+    code = _c(code, np.uint32)
+    if out is None:
+        out = np.zeros(n, np.uint8)
+    _check(lib().oracle_decode_subs(_p(stream, C.c_uint8), stream.size, _p(offsets, C.c_uint64), _p(sub_bits, C.c_uint16), n,
+                                    chunk_symbols, sub_symbols, _p(ln, C.c_uint8), _p(code, C.c_uint32), ln.size,
+                                    first_sub, num_subs, _p(out, C.c_uint8)), "decode_subs")
     return out
 
 

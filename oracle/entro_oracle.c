@@ -22,6 +22,9 @@
  *   decode          the serial definition (Fig. 3, top): walk an explicit
  *                   binary tree one bit at a time, for each segment on its own
  *                   starting from the segment's recorded boundary.
+ *   sub_index       an extension of the same segmentation: stream positions
+ *                   recorded inside a segment as well (16-bit piece lengths), and
+ *                   the decode of single pieces from those entry points.
  *   dequant / gemv  the inverse grid map (q - z) * s and the batch-1 linear
  *                   layer y = W x of the token-generation phase ("Latency
  *                   Reduction from Huffman Coding").
@@ -317,6 +320,73 @@ int oracle_decode(const uint8_t *stream, uint64_t stream_bytes, const uint64_t *
     if (n == 0 || chunk_symbols == 0) return OR_ERR_ARG;
     return oracle_decode_chunks(stream, stream_bytes, offsets, n, chunk_symbols, len, code, nsym,
                                 0, (n + chunk_symbols - 1) / chunk_symbols, out);
+}
+
+/* ------------------------------------------------- entry points inside a segment
+ * An extension of "Segmentation for parallel Huffman decoding" (segments with known
+ * boundaries decode independently, Fig. 3): inside a segment the stream position
+ * is recorded every `sub_symbols` symbols as well, so that a piece of a segment
+ * can be decoded on its own.  chunk_symbols must be a multiple of sub_symbols.
+ * sub_bits[j], j = 0 .. ceil(n / sub_symbols) - 1, is the number of stream bits
+ * that piece j (symbols j*sub_symbols .. (j+1)*sub_symbols - 1) occupies, so
+ * piece j starts at its segment's offset plus the sub_bits of the pieces in
+ * front of it in the same segment.  A piece longer than 65535 bits does not fit
+ * the 16-bit entry (OR_ERR_TOO_LONG). */
+int oracle_sub_index(const uint8_t *q, uint64_t n, const uint8_t *len, int nsym,
+                     uint32_t chunk_symbols, uint32_t sub_symbols, uint16_t *sub_bits)
+{
+    if (!q || !len || !sub_bits || n == 0 || chunk_symbols == 0 || sub_symbols == 0) return OR_ERR_ARG;
+    if (chunk_symbols % sub_symbols != 0) return OR_ERR_ARG;
+    uint64_t bits = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (q[i] >= nsym || len[q[i]] == 0) return OR_ERR_SYMBOL;
+        bits += len[q[i]];
+        if ((i + 1) % sub_symbols == 0 || i + 1 == n) {
+            if (bits > 65535u) return OR_ERR_TOO_LONG;
+            sub_bits[i / sub_symbols] = (uint16_t)bits;
+            bits = 0;
+        }
+    }
+    return OR_OK;
+}
+
+/* Decode pieces [first_sub, first_sub + num_subs), each on its own from its
+ * entry point, into out (indexed by absolute symbol position). */
+int oracle_decode_subs(const uint8_t *stream, uint64_t stream_bytes, const uint64_t *offsets,
+                       const uint16_t *sub_bits, uint64_t n, uint32_t chunk_symbols,
+                       uint32_t sub_symbols, const uint8_t *len, const uint32_t *code, int nsym,
+                       uint64_t first_sub, uint64_t num_subs, uint8_t *out)
+{
+    if (!stream || !offsets || !sub_bits || !len || !code || !out || n == 0) return OR_ERR_ARG;
+    if (chunk_symbols == 0 || sub_symbols == 0 || chunk_symbols % sub_symbols != 0) return OR_ERR_ARG;
+    const uint64_t per_chunk = chunk_symbols / sub_symbols;
+    const uint64_t n_subs = (n + sub_symbols - 1) / sub_symbols;
+    if (first_sub + num_subs > n_subs) return OR_ERR_ARG;
+    const int cap = 2 * ORACLE_MAX_SYMBOLS * ORACLE_MAX_LEN;
+    tree_node *t = (tree_node *)malloc(sizeof(tree_node) * (size_t)cap);
+    if (!t) return OR_ERR_ARG;
+    if (build_tree(len, code, nsym, t, cap) < 0) { free(t); return OR_ERR_CORRUPT; }
+    const uint64_t limit_bits = stream_bytes * 8;
+    int rc = OR_OK;
+    for (uint64_t j = first_sub; j < first_sub + num_subs && rc == OR_OK; ++j) {
+        const uint64_t chunk = j / per_chunk;
+        uint64_t pos = offsets[chunk];
+        for (uint64_t i = chunk * per_chunk; i < j; ++i) pos += sub_bits[i];
+        const uint64_t lo = j * (uint64_t)sub_symbols;
+        const uint64_t hi = lo + sub_symbols < n ? lo + sub_symbols : n;
+        for (uint64_t i = lo; i < hi; ++i) {
+            int v = 0;
+            while (t[v].symbol < 0) {
+                if (pos >= limit_bits) { rc = OR_ERR_CORRUPT; break; }
+                v = t[v].child[get_bit(stream, pos++)];
+                if (v < 0) { rc = OR_ERR_CORRUPT; break; }
+            }
+            if (rc != OR_OK) break;
+            out[i] = (uint8_t)t[v].symbol;
+        }
+    }
+    free(t);
+    return rc;
 }
 
 /* Two 4-bit symbols per byte: symbol 2i in the low nibble, 2i+1 in the high

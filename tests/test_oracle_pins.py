@@ -420,6 +420,77 @@ def test_segments_decode_independently_and_in_any_order():
     assert np.array_equal(out, sym)
 
 
+# ------------------------------------------------- entry points inside a segment
+def test_sub_index_handworked():
+    rows = _lines("handworked_sub_index.txt")
+    ln = np.array([int(v) for v in rows[0].split()], np.uint8)
+    sym = np.array([int(v) for v in rows[1].split()], np.uint8)
+    want_bits = [int(v) for v in rows[2].split()]
+    want_off = [int(v) for v in rows[3].split()]
+    want_starts = [int(v) for v in rows[4].split()]
+    code = oracle.canonical_codes(ln)
+    stream, off = oracle.encode(sym, ln, code, 4)
+    assert off.tolist() == want_off
+    sub = oracle.sub_index(sym, ln, 4, 2)
+    assert sub.tolist() == want_bits
+    starts = [int(off[j // 2]) + int(sub[(j // 2) * 2:j].sum()) for j in range(3)]
+    assert starts == want_starts
+    for j in range(3):                                   # every piece decodes on its own
+        out = oracle.decode_subs(stream, off, sub, sym.size, 4, 2, ln, code, j, 1, np.full(5, 9, np.uint8))
+        assert out[2 * j:2 * j + 2].tolist() == sym[2 * j:2 * j + 2].tolist()
+        assert (np.delete(out, range(2 * j, min(2 * j + 2, 5))) == 9).all()
+
+
+@pytest.mark.parametrize("chunk,sub,n", [(4096, 256, 70000), (1024, 64, 10000 + 37), (512, 512, 3000), (96, 32, 1000)])
+def test_sub_index_agrees_with_a_finer_segmentation(chunk, sub, n):
+    """The entry points of pieces of `sub` symbols are the segment offsets of the same symbols encoded with segments
+    of `sub` symbols (a path through encode that does not know of pieces), the pieces of a segment add up to the
+    segment, and decoding from the entry points gives the symbols."""
+    rng = np.random.default_rng(chunk + sub)
+    sym = np.minimum(rng.geometric(0.25, n) - 1, 255).astype(np.uint8)
+    ln, code, _ = oracle.codebook_from_symbols(sym, 8)
+    stream, off = oracle.encode(sym, ln, code, chunk)
+    _, off_fine = oracle.encode(sym, ln, code, sub)
+    bits = oracle.sub_index(sym, ln, chunk, sub)
+    per = chunk // sub
+    n_sub = (n + sub - 1) // sub
+    assert bits.size == n_sub
+    starts = np.array([int(off[j // per]) + int(bits[(j // per) * per:j].astype(np.uint64).sum()) for j in range(n_sub)])
+    assert np.array_equal(starts, off_fine[:-1].astype(np.int64))
+    for c in range(off.size - 1):
+        assert int(bits[c * per:(c + 1) * per].astype(np.uint64).sum()) == int(off[c + 1] - off[c])
+    lens = ln.astype(np.int64)[sym]
+    assert bits.tolist() == [int(lens[j * sub:(j + 1) * sub].sum()) for j in range(n_sub)]
+    out = np.full(n, 255, np.uint8)
+    for j in rng.permutation(n_sub)[:40]:
+        oracle.decode_subs(stream, off, bits, n, chunk, sub, ln, code, int(j), 1, out)
+        assert np.array_equal(out[j * sub:(j + 1) * sub], sym[j * sub:(j + 1) * sub])
+    assert np.array_equal(oracle.decode_subs(stream, off, bits, n, chunk, sub, ln, code, 0, n_sub), sym)
+
+
+def test_sub_index_errors():
+    sym = np.zeros(100, np.uint8)
+    ln = np.zeros(256, np.uint8)
+    ln[0] = 1
+    with pytest.raises(oracle.OracleError):
+        oracle.sub_index(sym, ln, 48, 32)                # segments are not a whole number of pieces
+    ln32 = np.zeros(256, np.uint8)
+    ln32[:2] = [1, 32]
+    with pytest.raises(oracle.OracleError) as e:         # 2048 codes of 32 bits do not fit a 16-bit entry
+        oracle.sub_index(np.ones(4096, np.uint8), ln32, 4096, 2048)
+    assert e.value.code == oracle.ERR_TOO_LONG
+
+
+def test_histogram_is_a_bincount():
+    rng = np.random.default_rng(8)
+    for bits in (8, 4):
+        q = rng.integers(0, 1 << bits, 100001).astype(np.uint8)
+        q[q == 3] = 5                                    # an absent symbol
+        assert np.array_equal(oracle.histogram(q, bits), np.bincount(q, minlength=1 << bits).astype(np.uint64))
+    with pytest.raises(oracle.OracleError):
+        oracle.histogram(np.array([16], np.uint8), 4)
+
+
 def test_pack_u4_layout():
     q = np.array([1, 2, 3, 4, 15], np.uint8)
     assert oracle.pack_u4(q).tolist() == [0x21, 0x43, 0x0F]
