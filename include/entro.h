@@ -56,6 +56,7 @@ extern "C" {
 
 #define ENTRO_MAX_CODE_LEN 32
 #define ENTRO_MAX_SYMBOLS 256
+#define ENTRO_MAX_SUB_PER_CHUNK 16   /* entry points per segment (entro_sub_index) */
 
 typedef enum {
     ENTRO_OK = 0,
@@ -103,11 +104,12 @@ typedef struct {
     uint64_t n;                  /* symbols (= rows * cols for the GEMV) */
     uint32_t chunk_symbols;      /* symbols per segment; even when the output is ENTRO_U4_PACKED */
     uint32_t rows, cols;         /* GEMV only: W is [rows][cols] row-major */
-    uint32_t reserved;
+    uint32_t sub_symbols;        /* 0, or the spacing of the entry points in sub_bits (see entro_sub_index) */
     const entro_codebook *cb;    /* host */
     entro_qparams qp;            /* dequant and GEMV: scale and zero_point; bits must equal cb->bits */
     const void *x;               /* GEMV only, device: bf16[cols] */
     void *out;                   /* device: u8[n] | u8[(n+1)/2] | f32[n] | bf16[n]; GEMV: f32[rows] | bf16[rows] */
+    const uint16_t *sub_bits;    /* device, 4-byte aligned: ceil(n / sub_symbols) piece lengths; NULL if sub_symbols == 0 */
 } entro_tensor;
 
 /* A prepared launch over `count` tensors.  Filled by entro_plan_init; plain data, caller-owned.
@@ -174,6 +176,21 @@ uint64_t entro_encode_bound(uint64_t n, const entro_codebook *cb);
 entro_status entro_encode(const uint8_t *q, uint64_t n, const entro_codebook *cb,
                           uint32_t chunk_symbols, uint8_t *stream, uint64_t stream_cap,
                           uint64_t *stream_bytes, uint64_t *offsets);
+
+/* Entry points inside the segments (an extension of "Segmentation for parallel Huffman
+ * decoding", Fig. 3: the more places of the stream have known positions, the more lanes
+ * can decode it at once; a segment of 4096 symbols is one lane's serial work otherwise,
+ * which bounds the latency of a small launch from below).  chunk_symbols must be
+ * sub_symbols times a power of two of at most ENTRO_MAX_SUB_PER_CHUNK.
+ * sub_bits[j], j = 0 .. ceil(n / sub_symbols) - 1 (host), receives the number of stream
+ * bits that piece j (symbols j * sub_symbols ...) occupies: piece j starts at its
+ * segment's offset plus the entries of the pieces before it in the same segment.  The
+ * stream and the offset table are those of entro_encode, unchanged.  With sub_bits and
+ * sub_symbols in an entro_tensor the device calls give a lane a piece instead of a
+ * segment; results are identical.  ENTRO_ERR_CODE_TOO_LONG if a piece exceeds 65535 bits
+ * (cannot happen for sub_symbols <= 2047), ENTRO_ERR_SYMBOL for a symbol without a code. */
+entro_status entro_sub_index(const uint8_t *q, uint64_t n, const entro_codebook *cb, uint32_t chunk_symbols,
+                             uint32_t sub_symbols, uint16_t *sub_bits);
 
 /* Consistency check of a host copy of an offset table against a stream size:
  * offsets[0] == 0, non-decreasing, each segment no longer than

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     lib, library_path,
     entro_quantize, entro_build_codebook, entro_codebook_from_counts, entro_codebook_from_lengths,
     entro_codebook_from_counts_limited, entro_build_codebook_limited,
-    entro_num_chunks, entro_encode_bound, entro_encode, entro_check_offsets,
+    entro_num_chunks, entro_encode_bound, entro_encode, entro_check_offsets, entro_sub_index,
     entro_bits_saved, entro_theoretical_speedup, entro_status_string,
     entro_decode, entro_decode_dequant, entro_decode_gemv, entro_decode_gemv_static, entro_gemv_workspace_bytes,
     entro_workspace_bytes, entro_plan_init, entro_plan_run,

@@ -37,8 +37,8 @@ class Codebook(C.Structure):
 class CTensor(C.Structure):
     _fields_ = [("stream", C.c_void_p), ("stream_bytes", C.c_uint64), ("offsets", C.c_void_p),
                 ("n", C.c_uint64), ("chunk_symbols", C.c_uint32), ("rows", C.c_uint32), ("cols", C.c_uint32),
-                ("reserved", C.c_uint32), ("cb", C.POINTER(Codebook)), ("qp", QParams), ("x", C.c_void_p),
-                ("out", C.c_void_p)]
+                ("sub_symbols", C.c_uint32), ("cb", C.POINTER(Codebook)), ("qp", QParams), ("x", C.c_void_p),
+                ("out", C.c_void_p), ("sub_bits", C.c_void_p)]
 
 
 class Plan(C.Structure):
@@ -87,6 +87,7 @@ def lib():
         "entro_encode_bound": (C.c_uint64, [C.c_uint64, cbp]),
         "entro_encode": (C.c_int, [u8p, C.c_uint64, cbp, C.c_uint32, u8p, C.c_uint64, u64p, u64p]),
         "entro_check_offsets": (C.c_int, [u64p, C.c_uint64, C.c_uint32, C.c_uint64, cbp]),
+        "entro_sub_index": (C.c_int, [u8p, C.c_uint64, cbp, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint16)]),
         "entro_bits_saved": (C.c_double, [C.c_int, C.c_double]),
         "entro_theoretical_speedup": (C.c_double, [C.c_int, C.c_double]),
         "entro_status_string": (C.c_char_p, [C.c_int]),
@@ -123,7 +124,7 @@ def lib():
 
 EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_counts",
             "entro_codebook_from_lengths", "entro_codebook_from_counts_limited", "entro_build_codebook_limited", "entro_num_chunks", "entro_encode_bound", "entro_encode",
-            "entro_check_offsets", "entro_bits_saved", "entro_theoretical_speedup", "entro_status_string",
+            "entro_check_offsets", "entro_sub_index", "entro_bits_saved", "entro_theoretical_speedup", "entro_status_string",
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv", "entro_decode_gemv_static",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
@@ -222,6 +223,15 @@ def entro_encode(q: np.ndarray, cb: Codebook, chunk_symbols: int):
     return stream[: nbytes.value].copy(), offsets
 
 
+def entro_sub_index(q: np.ndarray, cb: Codebook, chunk_symbols: int, sub_symbols: int) -> np.ndarray:
+    """-> uint16[ceil(n / sub_symbols)]: stream bits of every piece of sub_symbols symbols."""
+    q = np.ascontiguousarray(q, dtype=np.uint8).ravel()
+    sub = np.empty(entro_num_chunks(q.size, sub_symbols), np.uint16)
+    _check(lib().entro_sub_index(_ptr(q, C.c_uint8), q.size, C.byref(cb), chunk_symbols, sub_symbols,
+                                 _ptr(sub, C.c_uint16)), "entro_sub_index")
+    return sub
+
+
 def entro_check_offsets(offsets: np.ndarray, n: int, chunk_symbols: int, stream_bytes: int, cb: Codebook) -> int:
     offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
     return int(lib().entro_check_offsets(_ptr(offsets, C.c_uint64), n, chunk_symbols, stream_bytes, C.byref(cb)))
@@ -248,6 +258,8 @@ class EncodedTensor:
     rows: int = 0
     cols: int = 0
     name: str = ""
+    sub_symbols: int = 0                   # spacing of the entry points inside the segments (0: none)
+    sub_bits: Optional[np.ndarray] = None  # uint16 piece lengths (entro_sub_index)
 
     @property
     def total_bits(self) -> int:
@@ -259,12 +271,15 @@ class EncodedTensor:
 
 
 def encode_tensor(w: np.ndarray, bits: int, scheme: int, chunk_symbols: int, rows: int = 0, cols: int = 0,
-                  name: str = "", return_q: bool = False, max_len: int = 0):
-    """entro_quantize -> entro_build_codebook (length-limited if max_len is given) -> entro_encode."""
+                  name: str = "", return_q: bool = False, max_len: int = 0, sub_symbols: int = 0):
+    """entro_quantize -> entro_build_codebook (length-limited if max_len is given) -> entro_encode
+    (-> entro_sub_index if sub_symbols is given)."""
     q, qp = entro_quantize(w, bits, scheme)
     cb = entro_build_codebook_limited(q, bits, max_len) if max_len else entro_build_codebook(q, bits)
     stream, offsets = entro_encode(q, cb, chunk_symbols)
     enc = EncodedTensor(stream, offsets, q.size, chunk_symbols, cb, qp, rows, cols, name)
+    if sub_symbols:
+        enc.sub_symbols, enc.sub_bits = sub_symbols, entro_sub_index(q, cb, chunk_symbols, sub_symbols)
     return (enc, q) if return_q else enc
 
 
@@ -277,6 +292,7 @@ class DeviceTensor:
         # stream / offsets given: the tensor was encoded on the device and enc holds no host copy of them
         self.stream = torch.from_numpy(enc.stream).to(device) if stream is None else stream
         self.offsets = torch.from_numpy(enc.offsets.view(np.int64)).to(device) if offsets is None else offsets
+        self.sub_bits = torch.from_numpy(enc.sub_bits.view(np.int16)).to(device) if enc.sub_symbols else None
         self.x = None
         self.out = None
 
@@ -288,6 +304,8 @@ class DeviceTensor:
         t.offsets = self.offsets.data_ptr()
         t.n = e.n
         t.chunk_symbols = e.chunk_symbols
+        t.sub_symbols = e.sub_symbols
+        t.sub_bits = self.sub_bits.data_ptr() if self.sub_bits is not None else None
         t.rows, t.cols = e.rows, e.cols
         t.cb = C.pointer(e.cb)
         t.qp = e.qp

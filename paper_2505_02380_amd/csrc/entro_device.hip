@@ -66,10 +66,12 @@ struct DevTensor {
     void *out;
     const uint16_t *x;
     float *partials;            // GEMV: head/tail partial sums, 2 per segment
+    const uint16_t *sub;        // entry points inside the segments: stream bits of every piece (or null)
     uint64_t n;
     uint32_t stream_bytes;
-    uint32_t chunk_symbols;
-    uint32_t n_chunks;
+    uint32_t chunk_symbols;     // symbols one lane decodes: a piece, where the tensor has entry points, else a segment
+    uint32_t n_chunks;          // and how many of those the tensor has
+    uint32_t sub_shift;         // log2 of pieces per segment (0: none)
     uint32_t rows;
     uint32_t cols;
     uint32_t bits;
@@ -424,6 +426,20 @@ __device__ __forceinline__ uint32_t single_entry(const Tables &tb, uint32_t wind
     return e;
 }
 
+// Stream bit at which a lane's piece k starts: the segment's offset, plus the lengths of the pieces in
+// front of it in the same segment where the tensor has entry points inside its segments.
+__device__ __forceinline__ uint64_t seg_start(const DevTensor &t, uint32_t k) {
+    const uint32_t sh = t.sub_shift;
+    if (sh == 0) return t.offsets[k];
+    const uint32_t c = k >> sh, j = k - (c << sh);
+    const uint16_t *sb = t.sub + (static_cast<uint64_t>(c) << sh);
+    uint32_t add = 0;
+#pragma unroll
+    for (uint32_t i = 0; i + 1 < ENTRO_MAX_SUB_PER_CHUNK; ++i)
+        if (i < j) add += sb[i];
+    return t.offsets[c] + add;
+}
+
 // ---------------------------------------------------------------- scalar reader
 // Reads straight from global memory, one symbol per lookup; used for segments
 // whose size does not fit the row path and for shorter last segments.
@@ -506,7 +522,7 @@ __device__ void decode_scalar_from(const DevTensor &t, const Tables &tb, uint64_
 // All nsym symbols of segment k, element by element.
 template <int MODE>
 __device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t nsym) {
-    decode_scalar_from<MODE>(t, tb, t.offsets[k], static_cast<uint64_t>(k) * t.chunk_symbols, nsym);
+    decode_scalar_from<MODE>(t, tb, seg_start(t, k), static_cast<uint64_t>(k) * t.chunk_symbols, nsym);
 }
 
 // ------------------------------------------------------------------ ring reader
@@ -875,13 +891,13 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     // rest.  The lane moves on with the others past its own end; what it decodes there is not stored.
     const bool fast = nsym != 0;
     const uint32_t my_blocks = nsym / SPB;
-    uint64_t tail_pos = fast ? t.offsets[k] : 0;          // where the symbols behind the lane's last whole block start
+    uint64_t tail_pos = fast ? seg_start(t, k) : 0;       // where the symbols behind the lane's last whole block start
     Ring2 r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(wm.ring + lane);
     // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
-    ring2_fill<false>(r, fast ? t.offsets[k] : 0);
+    ring2_fill<false>(r, tail_pos);
     const uint64_t bytes_per_chunk = (static_cast<uint64_t>(C) * EBITS) >> 3;
     const uint32_t n_full = static_cast<uint32_t>(t.n / C);          // segments of full length
     // whole blocks of the shorter last segment, if there is one
@@ -1032,7 +1048,7 @@ __device__ __forceinline__ void decode_rows2_impl(const DevTensor &t, const Tabl
     }
     const bool fast = nsym != 0;
     const uint32_t my_blocks = nsym / SPB;
-    uint64_t tail_pos = fast ? t.offsets[k] : 0;
+    uint64_t tail_pos = fast ? seg_start(t, k) : 0;
     Ring2 r;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
@@ -1126,7 +1142,7 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &t
     ScalarReader r;
     r.stream = t.stream;
     r.last_off = t.stream_bytes - 8u;
-    r.pos = t.offsets[k];
+    r.pos = seg_start(t, k);
     r.buf = 0;
     const uint32_t max_len = t.max_len;
     const int32_t z = t.zero_point;
@@ -1199,7 +1215,7 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(ring_mem + lane);
     // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
-    ring_load(r, fast ? t.offsets[k] : 0);
+    ring_load(r, fast ? seg_start(t, k) : 0);
     const uint32_t cols = t.cols;
     const uint16_t *xvec = t.x;
     const uint32_t max_len = t.max_len;
@@ -1476,7 +1492,19 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     // offsets into the stream are 32-bit numbers in the kernels, with room for a line or two past the end
     if (t->stream_bytes < 32 || (t->stream_bytes & 15u) || t->stream_bytes >= (uint64_t{1} << 32) - 65536)
         return ENTRO_ERR_SIZE;
-    const uint64_t n_chunks = entro_num_chunks(t->n, t->chunk_symbols);
+    // the symbols one lane decodes: a piece, where the tensor has entry points inside its segments
+    uint32_t lane_symbols = t->chunk_symbols, sub_shift = 0;
+    if (t->sub_symbols) {
+        if (!t->sub_bits) return ENTRO_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(t->sub_bits) & 3u) return ENTRO_ERR_ALIGN;
+        if (t->chunk_symbols % t->sub_symbols != 0) return ENTRO_ERR_SIZE;
+        const uint32_t per = t->chunk_symbols / t->sub_symbols;
+        if (per > ENTRO_MAX_SUB_PER_CHUNK || (per & (per - 1u)) != 0) return ENTRO_ERR_SIZE;
+        if (d == ENTRO_U4_PACKED && (t->sub_symbols & 1u)) return ENTRO_ERR_SIZE;
+        while ((1u << sub_shift) < per) ++sub_shift;
+        lane_symbols = t->sub_symbols;
+    }
+    const uint64_t n_chunks = entro_num_chunks(t->n, lane_symbols);
     if (n_chunks >= (uint64_t{1} << 32) - 1024) return ENTRO_ERR_SIZE;
     if (!aligned16(t->stream) || !aligned16(t->offsets) || !aligned16(t->out)) return ENTRO_ERR_ALIGN;
     if (op != ENTRO_OP_DECODE && t->qp.bits != bits) return ENTRO_ERR_BITS;
@@ -1495,15 +1523,17 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     dt->x = static_cast<const uint16_t *>(t->x);
     dt->n = t->n;
     dt->stream_bytes = static_cast<uint32_t>(t->stream_bytes);
-    dt->chunk_symbols = t->chunk_symbols;
+    dt->chunk_symbols = lane_symbols;
     dt->n_chunks = static_cast<uint32_t>(n_chunks);
+    dt->sub = sub_shift ? t->sub_bits : nullptr;
+    dt->sub_shift = sub_shift;
     dt->rows = t->rows;
     dt->cols = t->cols;
     dt->bits = static_cast<uint32_t>(bits);
     dt->scale = t->qp.scale;
     dt->zero_point = t->qp.zero_point;
     dt->max_len = static_cast<uint32_t>(t->cb->max_len);
-    dt->need_fix = (op == ENTRO_OP_GEMV && (t->chunk_symbols % t->cols) != 0) ? 1u : 0u;
+    dt->need_fix = (op == ENTRO_OP_GEMV && (lane_symbols % t->cols) != 0) ? 1u : 0u;
     std::memcpy(dt->len, t->cb->len, 256);
     return ENTRO_OK;
 }
@@ -1619,6 +1649,9 @@ float *static_scratch() {
 
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
+// Symbols one lane decodes of this tensor (what the work list and the partial sums are counted in).
+uint32_t lane_symbols_of(const entro_tensor &t) { return t.sub_symbols ? t.sub_symbols : t.chunk_symbols; }
+
 struct Layout {
     uint64_t off_tensors, off_items, off_fix, off_partials, total;
     uint32_t n_items, n_fix;
@@ -1629,9 +1662,9 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
     uint64_t items = 0, fix = 0, partial_floats = 0;
     for (uint32_t i = 0; i < count; ++i) {
         if (ts[i].chunk_symbols == 0 || ts[i].n == 0) return false;
-        const uint64_t nc = entro_num_chunks(ts[i].n, ts[i].chunk_symbols);
+        const uint64_t nc = entro_num_chunks(ts[i].n, lane_symbols_of(ts[i]));
         items += (nc + kUnit - 1) / kUnit;
-        if (op == ENTRO_OP_GEMV && ts[i].cols && (ts[i].chunk_symbols % ts[i].cols) != 0) {
+        if (op == ENTRO_OP_GEMV && ts[i].cols && (lane_symbols_of(ts[i]) % ts[i].cols) != 0) {
             fix += (static_cast<uint64_t>(ts[i].rows) + kFixWG - 1) / kFixWG;
             partial_floats += 2 * nc;
         }
@@ -1742,8 +1775,8 @@ entro_status entro_decode_dequant(const entro_tensor *t, entro_dtype out_type, v
 
 uint64_t entro_gemv_workspace_bytes(const entro_tensor *t) {
     if (!t || t->chunk_symbols == 0 || t->cols == 0) return 0;
-    if ((t->chunk_symbols % t->cols) == 0) return 0;
-    return align_up(2 * sizeof(float) * entro_num_chunks(t->n, t->chunk_symbols), 256);
+    if ((lane_symbols_of(*t) % t->cols) == 0) return 0;
+    return align_up(2 * sizeof(float) * entro_num_chunks(t->n, lane_symbols_of(*t)), 256);
 }
 
 entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *workspace,
@@ -1762,7 +1795,7 @@ entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type,
     if (!t) return ENTRO_ERR_NULL;
     float *partials = nullptr;
     if (entro_gemv_workspace_bytes(t)) {
-        if (entro_num_chunks(t->n, t->chunk_symbols) > ENTRO_STATIC_GEMV_MAX_SEGMENTS) return ENTRO_ERR_CAPACITY;
+        if (entro_num_chunks(t->n, lane_symbols_of(*t)) > ENTRO_STATIC_GEMV_MAX_SEGMENTS) return ENTRO_ERR_CAPACITY;
         partials = static_scratch();
         if (!partials) return ENTRO_ERR_DEVICE;
     }

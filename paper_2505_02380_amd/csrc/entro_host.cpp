@@ -474,6 +474,38 @@ entro_status entro_encode(const uint8_t *q, uint64_t n, const entro_codebook *cb
     return ENTRO_OK;
 }
 
+entro_status entro_sub_index(const uint8_t *q, uint64_t n, const entro_codebook *cb, uint32_t chunk_symbols,
+                             uint32_t sub_symbols, uint16_t *sub_bits) {
+    if (!q || !cb || !sub_bits) return ENTRO_ERR_NULL;
+    if (!bits_ok(cb->bits)) return ENTRO_ERR_BITS;
+    if (n == 0 || chunk_symbols == 0 || sub_symbols == 0 || chunk_symbols % sub_symbols != 0) return ENTRO_ERR_SIZE;
+    const uint32_t per = chunk_symbols / sub_symbols;
+    if (per > ENTRO_MAX_SUB_PER_CHUNK || (per & (per - 1u)) != 0) return ENTRO_ERR_SIZE;
+    const int nsym = 1 << cb->bits;
+    uint8_t len[256];
+    for (int s = 0; s < 256; ++s) len[s] = s < nsym ? cb->len[s] : 0;
+    const uint64_t n_sub = entro_num_chunks(n, sub_symbols);
+    std::atomic<int> bad{0};           // 1: a symbol without a code, 2: a piece too long for 16 bits
+    parallel_ranges(n_sub, 256, [&](unsigned, uint64_t j0, uint64_t j1) {
+        for (uint64_t j = j0; j < j1; ++j) {
+            const uint64_t lo = j * sub_symbols, hi = std::min<uint64_t>(n, lo + sub_symbols);
+            uint64_t bits_here = 0;
+            bool miss = false;
+            for (uint64_t i = lo; i < hi; ++i) {
+                const unsigned l = len[q[i]];
+                miss |= (l == 0);
+                bits_here += l;
+            }
+            if (miss) bad.store(1, std::memory_order_relaxed);
+            else if (bits_here > 65535u) bad.store(2, std::memory_order_relaxed);
+            sub_bits[j] = static_cast<uint16_t>(bits_here);
+        }
+    });
+    if (bad.load() == 1) return ENTRO_ERR_SYMBOL;
+    if (bad.load() == 2) return ENTRO_ERR_CODE_TOO_LONG;
+    return ENTRO_OK;
+}
+
 entro_status entro_check_offsets(const uint64_t *offsets, uint64_t n, uint32_t chunk_symbols,
                                  uint64_t stream_bytes, const entro_codebook *cb) {
     if (!offsets || !cb) return ENTRO_ERR_NULL;

@@ -17,20 +17,22 @@ def default_threads() -> int:
     return max(1, min(16, os.cpu_count() or 1))
 
 
-def encode_spec(spec: "synth.TensorSpec", chunk_symbols: Optional[int] = None, max_len: int = 0) -> B.EncodedTensor:
+def encode_spec(spec: "synth.TensorSpec", chunk_symbols: Optional[int] = None, max_len: int = 0,
+                sub_symbols: int = 0) -> B.EncodedTensor:
     w = synth.make_tensor(spec)
     cs = chunk_symbols or synth.config_chunk_symbols(spec.cfg)
     enc = B.encode_tensor(w, spec.bits, spec.scheme, cs, rows=spec.rows, cols=spec.cols,
-                          name=f"L{spec.layer}.{spec.name}", max_len=max_len)
+                          name=f"L{spec.layer}.{spec.name}", max_len=max_len, sub_symbols=sub_symbols)
     return enc
 
 
 def prepare_config(cfg: int, layers: Optional[int] = None, threads: Optional[int] = None,
-                   progress=None, chunk_symbols: Optional[int] = None, max_len: int = 0) -> List[B.EncodedTensor]:
+                   progress=None, chunk_symbols: Optional[int] = None, max_len: int = 0,
+                   sub_symbols: int = 0) -> List[B.EncodedTensor]:
     """Encoded tensors of workload `cfg` in the order of synth.config_tensors.
 
     chunk_symbols overrides the workload's own segment size (an encode-time choice per tensor);
-    max_len > 0 asks for length-limited codebooks."""
+    max_len > 0 asks for length-limited codebooks; sub_symbols > 0 adds entry points inside the segments."""
     specs = synth.config_tensors(cfg, layers)
     threads = threads or default_threads()
     # the host library spawns its own threads per call; keep the product bounded
@@ -38,7 +40,7 @@ def prepare_config(cfg: int, layers: Optional[int] = None, threads: Optional[int
     out: List[Optional[B.EncodedTensor]] = [None] * len(specs)
 
     def work(i):
-        out[i] = encode_spec(specs[i], chunk_symbols, max_len)
+        out[i] = encode_spec(specs[i], chunk_symbols, max_len, sub_symbols)
         if progress:
             progress(i, len(specs))
         return i

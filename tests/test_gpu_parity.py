@@ -21,8 +21,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _oracle_encoded(sym, bits, chunk, rows=0, cols=0, s=1.0, z=0):
-    """EncodedTensor whose codebook and stream both come from the oracle."""
+def _oracle_encoded(sym, bits, chunk, rows=0, cols=0, s=1.0, z=0, sub=0):
+    """EncodedTensor whose codebook, stream (and entry points inside the segments, if sub is given) all come from
+    the oracle."""
     ln, code, _ = oracle.codebook_from_symbols(sym, bits)
     stream, off = oracle.encode(sym, ln, code, chunk)
     full = np.zeros(1 << bits, np.uint8)
@@ -30,7 +31,10 @@ def _oracle_encoded(sym, bits, chunk, rows=0, cols=0, s=1.0, z=0):
     cb = E.entro_codebook_from_lengths(full, bits)
     assert np.array_equal(cb.codes(), code)
     qp = B.QParams(np.float32(s), int(z), bits, E.ENTRO_ASYMMETRIC)
-    return B.EncodedTensor(stream, off, sym.size, chunk, cb, qp, rows, cols)
+    enc = B.EncodedTensor(stream, off, sym.size, chunk, cb, qp, rows, cols)
+    if sub:
+        enc.sub_symbols, enc.sub_bits = sub, oracle.sub_index(sym, ln, chunk, sub)
+    return enc
 
 
 def _bf16_ulp_diff(a_bits, b_bits):
@@ -375,6 +379,41 @@ def test_gemv_unit_vector_picks_a_column_exactly():
 
 
 # ------------------------------------------------------------- batched launches
+# ------------------------------------------------- entry points inside the segments
+@pytest.mark.parametrize("batch", [False, True])
+@pytest.mark.parametrize("bits,chunk,sub,n", [(8, 4096, 256, 300 * 4096), (8, 4096, 256, 70 * 4096 + 1000), (8, 4096, 1024, 9 * 4096 + 5),
+                                              (8, 2048, 128, 64 * 2048 + 130), (8, 1024, 64, 33 * 1024 + 63), (4, 8192, 512, 20 * 8192 + 700),
+                                              (8, 4096, 4096, 3 * 4096 + 17), (8, 1000, 250, 17 * 1000 + 3)])
+def test_entry_points_inside_segments_every_output(bits, chunk, sub, n, batch):
+    """A lane decodes a piece of a segment from its entry point: the outputs are those of the oracle's plain decode."""
+    rng = np.random.default_rng(n + sub)
+    sym = np.clip(np.rint(rng.standard_t(4, n) * (6 if bits == 8 else 0.8) + (1 << (bits - 1))), 0, (1 << bits) - 1).astype(np.uint8)
+    enc = _oracle_encoded(sym, bits, chunk, s=0.0173, z=(1 << (bits - 1)) + 3, sub=sub)
+    q = oracle.decode(enc.stream, enc.offsets, n, chunk, enc.cb.lengths(), enc.cb.codes())
+    assert np.array_equal(q, sym)
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, batch), q)
+    if bits == 4:
+        assert np.array_equal(_gpu_decode(enc, E.ENTRO_U4_PACKED, batch), oracle.pack_u4(q))
+    w32 = _gpu_dequant(enc, E.ENTRO_F32, batch)
+    assert np.array_equal(w32.view(np.uint32), oracle.dequant_f32(q, enc.qp.scale, enc.qp.zero_point).view(np.uint32))
+    assert _bf16_ulp_diff(_gpu_dequant(enc, E.ENTRO_BF16, batch), oracle.dequant_bf16(q, enc.qp.scale, enc.qp.zero_point)).max() <= 1
+
+
+@pytest.mark.parametrize("batch", [False, True])
+@pytest.mark.parametrize("rows,cols,chunk,sub", [(128, 4096, 4096, 256), (96, 14336, 4096, 256), (300, 1024, 4096, 512), (65, 1536, 2048, 128),
+                                                 (40, 200, 1024, 64), (520, 128, 4096, 1024)])
+def test_gemv_with_entry_points_inside_segments(rows, cols, chunk, sub, batch):
+    rng = np.random.default_rng(rows * cols + sub)
+    sym = np.clip(np.rint(rng.standard_t(5, rows * cols) * 6 + 128), 0, 255).astype(np.uint8)
+    enc = _oracle_encoded(sym, 8, chunk, rows, cols, s=0.011, z=125, sub=sub)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal(cols).astype(np.float32))
+    y_ref, _ = oracle.gemv(sym, rows, cols, enc.qp.scale, enc.qp.zero_point, xb)
+    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), y_ref)
+    plain = _oracle_encoded(sym, 8, chunk, rows, cols, s=0.011, z=125)
+    # against the same product with one lane per segment: the same sums in another order
+    assert np.allclose(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), _gpu_gemv(plain, xb, E.ENTRO_F32, batch), rtol=1e-4, atol=1e-4)
+
+
 def test_many_tensors_in_one_launch():
     rng = np.random.default_rng(12)
     encs, refs = [], []

@@ -32,7 +32,7 @@ def test_library_loads_and_exports_every_declared_symbol():
 def test_struct_layouts_match_header():
     assert C.sizeof(B.QParams) == 16
     assert C.sizeof(B.Codebook) == 16 + 256 + 1024
-    assert C.sizeof(B.CTensor) == 8 + 8 + 8 + 8 + 16 + 8 + 16 + 8 + 8
+    assert C.sizeof(B.CTensor) == 8 + 8 + 8 + 8 + 16 + 8 + 16 + 8 + 8 + 8
     assert C.sizeof(B.Plan) == 16 + 32 + 32
 
 
@@ -227,6 +227,38 @@ def test_encode_errors():
     assert E.entro_num_chunks(10, 0) == 0 and E.entro_num_chunks(10, 3) == 4
 
 
+@pytest.mark.parametrize("bits,chunk,sub,n", [(8, 4096, 256, 3 * 4096 + 700), (8, 1024, 1024, 5000), (4, 8192, 512, 40000),
+                                              (8, 512, 32, 2049)])
+def test_sub_index_equals_oracle(bits, chunk, sub, n):
+    rng = np.random.default_rng(bits * 1000 + sub)
+    sym = np.minimum(rng.geometric(0.3, n) - 1, (1 << bits) - 1).astype(np.uint8)
+    cb = E.entro_build_codebook(sym, bits)
+    got = E.entro_sub_index(sym, cb, chunk, sub)
+    assert np.array_equal(got, oracle.sub_index(sym, cb.lengths(), chunk, sub))
+    # the pieces of a segment add up to the segment
+    _, off = E.entro_encode(sym, cb, chunk)
+    per = chunk // sub
+    for c in range(off.size - 1):
+        assert int(got[c * per:(c + 1) * per].astype(np.uint64).sum()) == int(off[c + 1] - off[c])
+
+
+def test_sub_index_errors():
+    sym = np.zeros(4096, np.uint8)
+    cb = E.entro_build_codebook(np.array([0, 1, 1, 1], np.uint8), 8)
+    L = E.lib()
+    out = np.zeros(64, np.uint16)
+    args = (sym.ctypes.data_as(C.POINTER(C.c_uint8)), sym.size, C.byref(cb))
+    po = out.ctypes.data_as(C.POINTER(C.c_uint16))
+    assert L.entro_sub_index(*args, 4096, 96, po) == B.ENTRO_ERR_SIZE          # not a divisor
+    assert L.entro_sub_index(*args, 4096, 128, po) == B.ENTRO_ERR_SIZE         # 32 pieces per segment: more than 16
+    assert L.entro_sub_index(*args, 3072, 1024, po) == B.ENTRO_ERR_SIZE        # 3 pieces: not a power of two
+    assert L.entro_sub_index(None, sym.size, C.byref(cb), 4096, 256, po) == B.ENTRO_ERR_NULL
+    bad = np.full(4096, 7, np.uint8)                                           # a symbol without a code
+    assert L.entro_sub_index(bad.ctypes.data_as(C.POINTER(C.c_uint8)), bad.size, C.byref(cb), 4096, 256, po) \
+        == B.ENTRO_ERR_SYMBOL
+    assert L.entro_sub_index(*args, 4096, 256, po) == B.ENTRO_OK
+
+
 def test_check_offsets_flags_corruption():
     rng = np.random.default_rng(1)
     sym = rng.integers(0, 7, 20000).astype(np.uint8)
@@ -287,6 +319,14 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     t.cb = C.pointer(bad)
     assert L.entro_decode(C.byref(t), E.ENTRO_U8, None) == B.ENTRO_ERR_CORRUPT        # codes not canonical
     t.cb = C.pointer(cb)
+    t.sub_symbols = 16                                                                # entry points announced, table missing
+    assert L.entro_decode(C.byref(t), E.ENTRO_U8, None) == B.ENTRO_ERR_NULL
+    t.sub_bits = 20480
+    t.sub_symbols = 12
+    assert L.entro_decode(C.byref(t), E.ENTRO_U8, None) == B.ENTRO_ERR_SIZE           # segments are not whole pieces
+    t.sub_symbols = 1
+    assert L.entro_decode(C.byref(t), E.ENTRO_U8, None) == B.ENTRO_ERR_SIZE           # 32 pieces per segment
+    t.sub_symbols, t.sub_bits = 0, None
     assert L.entro_workspace_bytes(C.byref(t), 1, E.ENTRO_OP_DECODE) > 0
     plan = B.Plan()
     assert L.entro_plan_init(C.byref(plan), C.byref(t), 1, E.ENTRO_OP_DECODE, E.ENTRO_U8, 4096, 16, None) \
