@@ -19,8 +19,14 @@
  *     "device" pointers are HIP device memory of the current device.
  *   - The caller owns every buffer.  The library allocates no device memory
  *     and keeps no state between calls.
- *   - Device entry points only enqueue work on `hip_stream` (a hipStream_t
- *     passed as void*, NULL = the default stream) and return without waiting.
+ *   - Device entry points enqueue their work on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and return without waiting
+ *     for it.  Two exceptions wait for the stream ONCE, before their kernel is
+ *     enqueued, because they upload a table from memory that dies with the
+ *     call: entro_plan_init, and the three *_batch forms, which call it.  The
+ *     form for callers that must not block is entro_plan_init_staged (the
+ *     table goes through pinned memory of the caller's) followed by
+ *     entro_plan_run.
  *   - Every failure is a return code; nothing is thrown, nothing aborts.  All
  *     argument checks happen on the host before any launch.  A corrupt stream
  *     can decode to wrong symbols but is never read outside
@@ -248,8 +254,10 @@ entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type,
  * and the GEMV partial sums live in `workspace` (device). */
 uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
 
-/* Validate, build the table on the host and copy it into the workspace
- * (stream-ordered).  The tensors' device buffers are referenced, not copied.
+/* Validate, build the table on the host and copy it into the workspace.  BLOCKS until
+ * the copy, and with it everything enqueued on hip_stream before, has completed (the
+ * table is staged in memory that dies with the call); entro_plan_init_staged does not.
+ * The tensors' device buffers are referenced, not copied.
  * The work list is cut for the current device (its number of compute units
  * decides how many units a work item holds): run the plan on the device it was
  * prepared on.  The launch is one workgroup per compute unit at most; inside a
@@ -259,10 +267,21 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
                              entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
                              void *hip_stream);
 
-/* Enqueue the prepared launch; no host-side table work, no copies. */
+/* The same without waiting: the table is built in `staging` (host memory of the caller's,
+ * at least entro_plan_staging_bytes, pinned -- hipHostMalloc -- if the copy is to be
+ * asynchronous) and copied from there on hip_stream.  The caller keeps `staging` alive
+ * and unchanged until that copy has completed (a stream or event wait of its own).
+ * ENTRO_ERR_CAPACITY if staging_bytes is too small. */
+uint64_t entro_plan_staging_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
+entro_status entro_plan_init_staged(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
+                                    entro_dtype out_type, void *workspace, uint64_t workspace_bytes, void *staging,
+                                    uint64_t staging_bytes, void *hip_stream);
+
+/* Enqueue the prepared launch; no host-side table work, no copies, no waiting. */
 entro_status entro_plan_run(const entro_plan *plan, void *hip_stream);
 
-/* entro_plan_init followed by entro_plan_run. */
+/* entro_plan_init followed by entro_plan_run (so these wait for the stream once, before
+ * their kernel is enqueued; they return without waiting for the kernel). */
 entro_status entro_decode_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,
                                 void *workspace, uint64_t workspace_bytes, void *hip_stream);
 entro_status entro_decode_dequant_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,

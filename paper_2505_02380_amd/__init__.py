@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     entro_num_chunks, entro_encode_bound, entro_encode, entro_check_offsets, entro_sub_index,
     entro_bits_saved, entro_theoretical_speedup, entro_status_string,
     entro_decode, entro_decode_dequant, entro_decode_gemv, entro_decode_gemv_static, entro_gemv_workspace_bytes,
-    entro_workspace_bytes, entro_plan_init, entro_plan_run,
+    entro_workspace_bytes, entro_plan_init, entro_plan_staging_bytes, entro_plan_init_staged, entro_plan_run,
     entro_decode_batch, entro_decode_dequant_batch, entro_decode_gemv_batch,
     entro_last_device_error, entro_stream_probe, entro_gemv_u8_plain, encode_tensor, to_device,
     entro_range_device, entro_qparams_from_range, entro_scheme_for_range, entro_quantize_device, entro_encoded_bytes,

@@ -98,6 +98,9 @@ def lib():
         "entro_decode_gemv_static": (C.c_int, [tp, C.c_int, C.c_void_p]),
         "entro_workspace_bytes": (C.c_uint64, [tp, C.c_uint32, C.c_int]),
         "entro_plan_init": (C.c_int, [pp, tp, C.c_uint32, C.c_int, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
+        "entro_plan_staging_bytes": (C.c_uint64, [tp, C.c_uint32, C.c_int]),
+        "entro_plan_init_staged": (C.c_int, [pp, tp, C.c_uint32, C.c_int, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
+                                             C.c_void_p]),
         "entro_plan_run": (C.c_int, [pp, C.c_void_p]),
         "entro_decode_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_decode_dequant_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
@@ -126,7 +129,7 @@ EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_count
             "entro_codebook_from_lengths", "entro_codebook_from_counts_limited", "entro_build_codebook_limited", "entro_num_chunks", "entro_encode_bound", "entro_encode",
             "entro_check_offsets", "entro_sub_index", "entro_bits_saved", "entro_theoretical_speedup", "entro_status_string",
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv", "entro_decode_gemv_static",
-            "entro_workspace_bytes", "entro_plan_init", "entro_plan_run", "entro_decode_batch",
+            "entro_workspace_bytes", "entro_plan_init", "entro_plan_staging_bytes", "entro_plan_init_staged", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
             "entro_stream_probe", "entro_gemv_u8_plain", "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
             "entro_encoded_bytes", "entro_encode_device", "entro_encode_device_status"]
@@ -365,6 +368,23 @@ def entro_plan_init(ts: Sequence[CTensor], op: int, out_type: int, workspace, st
     _check(lib().entro_plan_init(C.byref(plan), arr, len(ts), op, out_type, workspace.data_ptr(),
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
            "entro_plan_init")
+    return plan
+
+
+def entro_plan_staging_bytes(ts: Sequence[CTensor], op: int) -> int:
+    arr = _tensor_array(ts)
+    return int(lib().entro_plan_staging_bytes(arr, len(ts), op))
+
+
+def entro_plan_init_staged(ts: Sequence[CTensor], op: int, out_type: int, workspace, staging, stream=None) -> Plan:
+    """Non-blocking entro_plan_init: `staging` is a pinned host tensor (torch, uint8) that the caller keeps alive
+    until the copy enqueued here has completed."""
+    arr = _tensor_array(ts)
+    plan = Plan()
+    _check(lib().entro_plan_init_staged(C.byref(plan), arr, len(ts), op, out_type, workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), staging.data_ptr(),
+                                        staging.numel() * staging.element_size(), _stream_ptr(stream)),
+           "entro_plan_init_staged")
     return plan
 
 

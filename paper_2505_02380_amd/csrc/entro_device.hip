@@ -71,7 +71,8 @@ struct DevTensor {
     uint32_t stream_bytes;
     uint32_t chunk_symbols;     // symbols one lane decodes: a piece, where the tensor has entry points, else a segment
     uint32_t n_chunks;          // and how many of those the tensor has
-    uint32_t sub_shift;         // log2 of pieces per segment (0: none)
+    uint32_t sub_shift;         // log2 of lanes per segment (0: a lane takes a whole segment)
+    uint32_t sub_merge;         // log2 of the pieces of the entry-point table that one lane takes
     uint32_t rows;
     uint32_t cols;
     uint32_t bits;
@@ -431,12 +432,13 @@ __device__ __forceinline__ uint32_t single_entry(const Tables &tb, uint32_t wind
 __device__ __forceinline__ uint64_t seg_start(const DevTensor &t, uint32_t k) {
     const uint32_t sh = t.sub_shift;
     if (sh == 0) return t.offsets[k];
-    const uint32_t c = k >> sh, j = k - (c << sh);
-    const uint16_t *sb = t.sub + (static_cast<uint64_t>(c) << sh);
+    const uint32_t c = k >> sh;
+    const uint32_t before = (k - (c << sh)) << t.sub_merge;          // pieces of the segment in front of the lane's
+    const uint16_t *sb = t.sub + (static_cast<uint64_t>(c) << (sh + t.sub_merge));
     uint32_t add = 0;
 #pragma unroll
     for (uint32_t i = 0; i + 1 < ENTRO_MAX_SUB_PER_CHUNK; ++i)
-        if (i < j) add += sb[i];
+        if (i < before) add += sb[i];
     return t.offsets[c] + add;
 }
 
@@ -1481,7 +1483,36 @@ entro_status check_codebook(const entro_codebook *cb) {
     return ENTRO_OK;
 }
 
-entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, DevTensor *dt) {
+// log2 of the entry points per segment of a tensor (0: none inside the segments)
+uint32_t sub_levels(const entro_tensor &t) {
+    if (!t.sub_symbols || !t.chunk_symbols || t.chunk_symbols % t.sub_symbols) return 0;
+    uint32_t per = t.chunk_symbols / t.sub_symbols, lg = 0;
+    while ((1u << lg) < per) ++lg;
+    return lg;
+}
+
+// Symbols a lane takes of this tensor when pieces are merged `level` times pairwise (at most up to whole segments).
+uint64_t lane_symbols_at(const entro_tensor &t, uint32_t level) {
+    if (!t.sub_symbols) return t.chunk_symbols;
+    return static_cast<uint64_t>(t.sub_symbols) << std::min(level, sub_levels(t));
+}
+
+// How coarse the lanes of a launch over these tensors are: as coarse as still gives every lane slot of the
+// device (`lane_slots`) a lane -- a lane's work is serial, so small launches are cut as fine as the entry
+// points allow, and large ones as coarse as their segments, which costs the least per symbol.
+uint32_t choose_level(const entro_tensor *ts, uint32_t count, uint64_t lane_slots) {
+    uint32_t top = 0;
+    for (uint32_t i = 0; i < count; ++i) top = std::max(top, sub_levels(ts[i]));
+    for (uint32_t level = top; level > 0; --level) {
+        uint64_t lanes = 0;
+        for (uint32_t i = 0; i < count; ++i)
+            if (ts[i].chunk_symbols) lanes += (ts[i].n + lane_symbols_at(ts[i], level) - 1) / lane_symbols_at(ts[i], level);
+        if (lanes >= lane_slots) return level;
+    }
+    return 0;
+}
+
+entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, uint32_t level, DevTensor *dt) {
     if (!t || !t->stream || !t->offsets || !t->out || !t->cb) return ENTRO_ERR_NULL;
     entro_status st = check_codebook(t->cb);
     if (st != ENTRO_OK) return st;
@@ -1492,8 +1523,8 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     // offsets into the stream are 32-bit numbers in the kernels, with room for a line or two past the end
     if (t->stream_bytes < 32 || (t->stream_bytes & 15u) || t->stream_bytes >= (uint64_t{1} << 32) - 65536)
         return ENTRO_ERR_SIZE;
-    // the symbols one lane decodes: a piece, where the tensor has entry points inside its segments
-    uint32_t lane_symbols = t->chunk_symbols, sub_shift = 0;
+    // the symbols one lane decodes: 2^level pieces, where the tensor has entry points inside its segments
+    uint32_t lane_symbols = t->chunk_symbols, sub_shift = 0, sub_merge = 0;
     if (t->sub_symbols) {
         if (!t->sub_bits) return ENTRO_ERR_NULL;
         if (reinterpret_cast<uintptr_t>(t->sub_bits) & 3u) return ENTRO_ERR_ALIGN;
@@ -1501,8 +1532,9 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
         const uint32_t per = t->chunk_symbols / t->sub_symbols;
         if (per > ENTRO_MAX_SUB_PER_CHUNK || (per & (per - 1u)) != 0) return ENTRO_ERR_SIZE;
         if (d == ENTRO_U4_PACKED && (t->sub_symbols & 1u)) return ENTRO_ERR_SIZE;
-        while ((1u << sub_shift) < per) ++sub_shift;
-        lane_symbols = t->sub_symbols;
+        sub_merge = std::min(level, sub_levels(*t));
+        sub_shift = sub_levels(*t) - sub_merge;
+        lane_symbols = t->sub_symbols << sub_merge;
     }
     const uint64_t n_chunks = entro_num_chunks(t->n, lane_symbols);
     if (n_chunks >= (uint64_t{1} << 32) - 1024) return ENTRO_ERR_SIZE;
@@ -1527,6 +1559,7 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     dt->n_chunks = static_cast<uint32_t>(n_chunks);
     dt->sub = sub_shift ? t->sub_bits : nullptr;
     dt->sub_shift = sub_shift;
+    dt->sub_merge = sub_merge;
     dt->rows = t->rows;
     dt->cols = t->cols;
     dt->bits = static_cast<uint32_t>(bits);
@@ -1598,17 +1631,21 @@ unsigned resident_workgroups(int mode) {
 
 entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, float *partials,
                            void *hip_stream) {
+    // all argument checks first, on the host alone; then the device is asked how many lanes it holds, which
+    // decides how fine the lanes are cut
     DevTensor dt;
-    entro_status st = fill_dev_tensor(t, op, d, &dt);
+    entro_status st = fill_dev_tensor(t, op, d, 0, &dt);
+    if (st != ENTRO_OK) return st;
+    const int mode = mode_of(op, d, dt.bits == 4);
+    const unsigned wg = wg_of(mode);
+    const unsigned slots = resident_workgroups(mode);
+    if (slots == 0) return ENTRO_ERR_DEVICE;
+    st = fill_dev_tensor(t, op, d, choose_level(t, 1, static_cast<uint64_t>(slots) * wg), &dt);
     if (st != ENTRO_OK) return st;
     dt.partials = partials;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int mode = mode_of(op, d, dt.bits == 4);
-    const unsigned wg = wg_of(mode);
     // a unit per wavefront when the tensor is large; fewer units per workgroup, down to one, when
     // that would leave compute units without a workgroup
-    const unsigned slots = resident_workgroups(mode);
-    if (slots == 0) return ENTRO_ERR_DEVICE;
     const unsigned units = (dt.n_chunks + kUnit - 1) / kUnit;
     const unsigned wg_units = std::min(wg / 64u, std::max(1u, units / slots));
     const unsigned grid = (units + wg_units - 1) / wg_units;
@@ -1808,27 +1845,32 @@ uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op 
     return L.total;
 }
 
-entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
-                             entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
-                             void *hip_stream) {
-    if (!plan || !ts || !workspace) return ENTRO_ERR_NULL;
-    if (count == 0) return ENTRO_ERR_SIZE;
-    if (op != ENTRO_OP_DECODE && op != ENTRO_OP_DEQUANT && op != ENTRO_OP_GEMV) return ENTRO_ERR_SCHEME;
-    if (!aligned16(workspace)) return ENTRO_ERR_ALIGN;
-    Layout L;
-    if (!plan_layout(ts, count, op, &L)) return ENTRO_ERR_SIZE;
-    if (workspace_bytes < L.total) return ENTRO_ERR_CAPACITY;
-
-    std::vector<unsigned char> host(L.off_partials, 0);
-    DevTensor *dts = reinterpret_cast<DevTensor *>(host.data() + L.off_tensors);
-    WorkItem *items = reinterpret_cast<WorkItem *>(host.data() + L.off_items);
-    WorkItem *fix = reinterpret_cast<WorkItem *>(host.data() + L.off_fix);
+// Validate, lay the table out in `host` (L.off_partials bytes) and fill in the plan; nothing touches the device.
+static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op, entro_dtype out_type,
+                               void *workspace, uint64_t workspace_bytes, const Layout &L, unsigned char *host) {
+    std::memset(host, 0, L.off_partials);
+    DevTensor *dts = reinterpret_cast<DevTensor *>(host + L.off_tensors);
+    WorkItem *items = reinterpret_cast<WorkItem *>(host + L.off_items);
+    WorkItem *fix = reinterpret_cast<WorkItem *>(host + L.off_fix);
     uint64_t n_items = 0, n_fix = 0, partial_floats = 0, total_units = 0;
     bool pairs = true;                                       // every tensor 4-bit: two codes per table entry
     bool multirow = false;                                   // GEMV: a tensor's segments are longer than its rows
     float *partials_base = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + L.off_partials);
+    // how fine the lanes are cut is decided for the launch as a whole (all its tensors are 4-bit, or the
+    // tables take single codes: the kernel and with it the lane slots are known before the tensors are looked at)
+    // (all argument checks come first, on the host alone)
+    bool all4 = true;
     for (uint32_t i = 0; i < count; ++i) {
-        entro_status st = fill_dev_tensor(&ts[i], op, out_type, &dts[i]);
+        entro_status st = fill_dev_tensor(&ts[i], op, out_type, 0, &dts[i]);
+        if (st != ENTRO_OK) return st;
+        all4 = all4 && dts[i].bits == 4;
+    }
+    const int mode0 = mode_of(op, out_type, all4);
+    const unsigned slots0 = resident_workgroups(mode0);
+    if (slots0 == 0) return ENTRO_ERR_DEVICE;
+    const uint32_t level = choose_level(ts, count, static_cast<uint64_t>(slots0) * wg_of(mode0));
+    for (uint32_t i = 0; i < count; ++i) {
+        entro_status st = fill_dev_tensor(&ts[i], op, out_type, level, &dts[i]);
         if (st != ENTRO_OK) return st;
         total_units += (dts[i].n_chunks + kUnit - 1) / kUnit;
         pairs = pairs && dts[i].bits == 4;
@@ -1848,18 +1890,13 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     const uint32_t item_units = static_cast<uint32_t>(std::min<uint64_t>(waves, std::max<uint64_t>(1, total_units / slots)));
     for (uint32_t i = 0; i < count; ++i)
         for (uint32_t c = 0; c < dts[i].n_chunks; c += item_units * kUnit) items[n_items++] = WorkItem{i, c};
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (!hip_ok(hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, s), "copy plan table"))
-        return ENTRO_ERR_DEVICE;
-    // the staging vector dies with this call, so wait for the copy
-    if (!hip_ok(hipStreamSynchronize(s), "wait for plan table")) return ENTRO_ERR_DEVICE;
     plan->workspace = workspace;
     plan->workspace_bytes = workspace_bytes;
     plan->op = op;
     plan->out = out_type;
     plan->count = count;
     plan->n_items = static_cast<uint32_t>(n_items);
-    plan->n_fix = L.n_fix;
+    plan->n_fix = static_cast<uint32_t>(n_fix);
     plan->item_units = item_units;
     plan->pair_tables = pairs ? 1u : 0u;
     plan->gemv_multirow = multirow ? 1u : 0u;
@@ -1867,6 +1904,56 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
     plan->off_items = L.off_items;
     plan->off_partials = L.off_partials;
     plan->off_fix = L.off_fix;
+    return ENTRO_OK;
+}
+
+static entro_status plan_checks(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op, void *workspace,
+                                uint64_t workspace_bytes, Layout *L) {
+    if (!plan || !ts || !workspace) return ENTRO_ERR_NULL;
+    if (count == 0) return ENTRO_ERR_SIZE;
+    if (op != ENTRO_OP_DECODE && op != ENTRO_OP_DEQUANT && op != ENTRO_OP_GEMV) return ENTRO_ERR_SCHEME;
+    if (!aligned16(workspace)) return ENTRO_ERR_ALIGN;
+    if (!plan_layout(ts, count, op, L)) return ENTRO_ERR_SIZE;
+    if (workspace_bytes < L->total) return ENTRO_ERR_CAPACITY;
+    return ENTRO_OK;
+}
+
+uint64_t entro_plan_staging_bytes(const entro_tensor *ts, uint32_t count, entro_op op) {
+    Layout L;
+    if (!ts || count == 0 || !plan_layout(ts, count, op, &L)) return 0;
+    return L.off_partials;
+}
+
+entro_status entro_plan_init_staged(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
+                                    entro_dtype out_type, void *workspace, uint64_t workspace_bytes, void *staging,
+                                    uint64_t staging_bytes, void *hip_stream) {
+    Layout L;
+    entro_status st = plan_checks(plan, ts, count, op, workspace, workspace_bytes, &L);
+    if (st != ENTRO_OK) return st;
+    if (!staging) return ENTRO_ERR_NULL;
+    if (staging_bytes < L.off_partials) return ENTRO_ERR_CAPACITY;
+    st = build_plan(plan, ts, count, op, out_type, workspace, workspace_bytes, L, static_cast<unsigned char *>(staging));
+    if (st != ENTRO_OK) return st;
+    if (!hip_ok(hipMemcpyAsync(workspace, staging, L.off_partials, hipMemcpyHostToDevice, static_cast<hipStream_t>(hip_stream)),
+                "copy plan table"))
+        return ENTRO_ERR_DEVICE;
+    return ENTRO_OK;
+}
+
+entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
+                             entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
+                             void *hip_stream) {
+    Layout L;
+    entro_status st = plan_checks(plan, ts, count, op, workspace, workspace_bytes, &L);
+    if (st != ENTRO_OK) return st;
+    std::vector<unsigned char> host(L.off_partials);
+    st = build_plan(plan, ts, count, op, out_type, workspace, workspace_bytes, L, host.data());
+    if (st != ENTRO_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (!hip_ok(hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, s), "copy plan table"))
+        return ENTRO_ERR_DEVICE;
+    // the staging vector dies with this call, so wait for the copy
+    if (!hip_ok(hipStreamSynchronize(s), "wait for plan table")) return ENTRO_ERR_DEVICE;
     return ENTRO_OK;
 }
 

@@ -414,6 +414,54 @@ def test_gemv_with_entry_points_inside_segments(rows, cols, chunk, sub, batch):
     assert np.allclose(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), _gpu_gemv(plain, xb, E.ENTRO_F32, batch), rtol=1e-4, atol=1e-4)
 
 
+def test_large_launch_merges_pieces_into_coarser_lanes():
+    """A launch with more pieces than the chip has lanes lets a lane take 2^k pieces (the coarsest cut that still
+    gives every lane slot a lane): 40 M symbols with entry points every 64 symbols in segments of 1024."""
+    n, chunk, sub = 40 * 1024 * 1024, 1024, 64
+    rng = np.random.default_rng(5)
+    sym = np.clip(np.rint(rng.standard_t(4, n) * 5 + 128), 0, 255).astype(np.uint8)
+    enc = _oracle_encoded(sym, 8, chunk, s=0.02, z=131, sub=sub)
+    assert np.array_equal(_gpu_decode(enc, E.ENTRO_U8, True), sym)
+    assert _bf16_ulp_diff(_gpu_dequant(enc, E.ENTRO_BF16, False), oracle.dequant_bf16(sym, enc.qp.scale, enc.qp.zero_point)).max() <= 1
+
+
+def test_staged_plan_init_does_not_block_and_batch_calls_return_before_their_kernel_ends():
+    from paper_2505_02380_amd.workload import prepare_config
+    encs = prepare_config(4, layers=8)
+    dts = [E.to_device(e, DEV) for e in encs]
+    outs = [torch.zeros(e.n, dtype=torch.bfloat16, device=DEV) for e in encs]
+    ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+    ws = torch.zeros(E.entro_workspace_bytes(ts, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=DEV)
+    staging = torch.zeros(E.entro_plan_staging_bytes(ts, E.ENTRO_OP_DEQUANT), dtype=torch.uint8).pin_memory()
+    assert staging.numel() > 0
+    torch.cuda.synchronize()
+    # something long in front of it on the stream: the staged form must not wait for it
+    filler = torch.empty(1 << 30, dtype=torch.uint8, device=DEV)
+    for _ in range(8):
+        filler.fill_(1)
+    busy = torch.cuda.Event()
+    busy.record()
+    plan = E.entro_plan_init_staged(ts, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws, staging)
+    E.entro_plan_run(plan)
+    assert not busy.query(), "entro_plan_init_staged or entro_plan_run waited for the stream"
+    torch.cuda.synchronize()
+    first = [o.clone() for o in outs]
+    for o in outs:
+        o.zero_()
+    # the batch form waits once for the stream (the table upload), then enqueues: it is back before its kernel ends
+    done = torch.cuda.Event()
+    E.entro_decode_dequant_batch(ts, E.ENTRO_BF16, ws)
+    done.record()
+    assert not done.query(), "entro_decode_dequant_batch returned only after its kernel had ended"
+    torch.cuda.synchronize()
+    for a, b in zip(first, outs):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    e = encs[3]
+    q = oracle.decode(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes())
+    assert _bf16_ulp_diff(outs[3].view(torch.int16).cpu().numpy().view(np.uint16),
+                          oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)).max() <= 1
+
+
 def test_many_tensors_in_one_launch():
     rng = np.random.default_rng(12)
     encs, refs = [], []
