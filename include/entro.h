@@ -131,6 +131,8 @@ typedef struct {
     uint32_t item_units;  /* units (64 segments of one tensor) per work item */
     uint32_t pair_tables; /* 1: every tensor holds 4-bit symbols, the kernels decode two per table lookup */
     uint32_t gemv_multirow; /* 1: a tensor's segments are longer than its matrix rows (information only) */
+    uint32_t wide_tables; /* 1: GEMV over 8-bit tensors with zero-points in [-1, 256]: table entries hold the centred value */
+    uint32_t reserved;
     uint64_t off_tensors, off_items, off_partials, off_fix;   /* byte offsets inside the workspace */
 } entro_plan;
 

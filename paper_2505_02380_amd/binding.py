@@ -44,7 +44,7 @@ class CTensor(C.Structure):
 class Plan(C.Structure):
     _fields_ = [("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("op", C.c_uint32),
                 ("out", C.c_uint32), ("count", C.c_uint32), ("n_items", C.c_uint32), ("n_fix", C.c_uint32),
-                ("item_units", C.c_uint32), ("pair_tables", C.c_uint32), ("gemv_multirow", C.c_uint32), ("off_tensors", C.c_uint64), ("off_items", C.c_uint64),
+                ("item_units", C.c_uint32), ("pair_tables", C.c_uint32), ("gemv_multirow", C.c_uint32), ("wide_tables", C.c_uint32), ("reserved", C.c_uint32), ("off_tensors", C.c_uint64), ("off_items", C.c_uint64),
                 ("off_partials", C.c_uint64), ("off_fix", C.c_uint64)]
 
 

@@ -30,6 +30,7 @@
 #include <cstring>
 #include <mutex>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 // Partial sums of entro_decode_gemv_static: two floats per segment.  Every GPU the library runs on holds
@@ -90,10 +91,15 @@ struct WorkItem {
 
 // The P modes are the byte, fp32 and bf16 outputs and the GEMV of launches whose tensors all hold
 // 4-bit symbols: they decode two symbols per lookup, like the packed output.
+// The W modes are the GEMV on wide tables (8-bit symbols, zero-point within [-1, 256]): gemv_direct2.
 enum Mode { kModeU8 = 0, kModeU4 = 1, kModeF32 = 2, kModeBF16 = 3, kModeGemvF32 = 4, kModeGemvBF16 = 5,
-            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32P = 9, kModeGemvBF16P = 10 };
-constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32P; }
-constexpr bool is_gemv(int mode) { return gemv_f32(mode) || mode == kModeGemvBF16 || mode == kModeGemvBF16P; }
+            kModeU8P = 6, kModeF32P = 7, kModeBF16P = 8, kModeGemvF32P = 9, kModeGemvBF16P = 10,
+            kModeGemvF32W = 11, kModeGemvBF16W = 12 };
+constexpr bool gemv_f32(int mode) { return mode == kModeGemvF32 || mode == kModeGemvF32P || mode == kModeGemvF32W; }
+constexpr bool is_gemv(int mode) {
+    return gemv_f32(mode) || mode == kModeGemvBF16 || mode == kModeGemvBF16P || mode == kModeGemvBF16W;
+}
+constexpr bool wide_gemv(int mode) { return mode == kModeGemvF32W || mode == kModeGemvBF16W; }
 // the output format of a mode
 constexpr int base_mode(int mode) { return mode == kModeU8P ? kModeU8 : mode == kModeF32P ? kModeF32 : mode == kModeBF16P ? kModeBF16 : mode; }
 
@@ -112,6 +118,8 @@ template <> struct Cfg<kModeGemvF32> { static constexpr int spb = 64, row = 64, 
 template <> struct Cfg<kModeGemvBF16> { static constexpr int spb = 64, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvF32P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeGemvBF16P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvF32W> { static constexpr int spb = 64, row = 64, waves = 16, piece = 8, out_row = 0; };
+template <> struct Cfg<kModeGemvBF16W> { static constexpr int spb = 64, row = 64, waves = 16, piece = 8, out_row = 0; };
 template <> struct Cfg<kModeU8P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 16, out_row = 128; };
 template <> struct Cfg<kModeF32P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 512; };
 template <> struct Cfg<kModeBF16P> { static constexpr int spb = 128, row = 64, waves = 14, piece = 8, out_row = 256; };
@@ -136,8 +144,7 @@ template <int MODE> constexpr bool kPairMode = MODE == kModeU4 || MODE == kModeU
 // zero entry otherwise.  There is no second level then; lut2 starts with a
 // table of single codes up to kSingleBits long instead, for what the pair table
 // leaves out and for the element-by-element paths.
-struct alignas(16) Tables {
-    uint16_t lut[1 << kL1];
+struct alignas(16) TablesTail {
     uint16_t lut2[kL2Cap];
     uint32_t cnt[ENTRO_MAX_CODE_LEN + 2];
     uint32_t first[ENTRO_MAX_CODE_LEN + 2];
@@ -149,6 +156,17 @@ struct alignas(16) Tables {
     uint32_t pad[2];
     uint8_t sorted[256];
 };
+// E: the first level's entry.  16 bits: as described above.  32 bits (the GEMV's wide tables): the same in the
+// low half and, in the high half, the value the symbol contributes, ready for use: bf16(symbol - zero_point),
+// which is exact (an integer of at most 256 in magnitude), so that the product needs neither a conversion
+// nor a subtraction per symbol.  A window that is to index 32-bit entries carries two stale low bits.
+template <class E>
+struct alignas(16) TablesT : TablesTail {
+    static constexpr uint32_t stale = sizeof(E) == 2 ? 1u : 2u;
+    E lut[1 << kL1];
+};
+using Tables = TablesT<uint16_t>;
+using Tables32 = TablesT<uint32_t>;
 
 // Per-wave LDS: the lanes' stream rings and their output rows.
 // The ring is stored dword-major (dword d of lane l at d * 64 + l): whatever
@@ -207,7 +225,7 @@ __device__ __forceinline__ float dequant(uint32_t sym, int32_t z, float s) {
 
 __device__ __forceinline__ uint32_t pack_entry(uint32_t sym, uint32_t len) { return len | (sym << 8); }
 __device__ __forceinline__ uint32_t entry_len(uint32_t e) { return e & 0x3fu; }
-__device__ __forceinline__ uint32_t entry_sym(uint32_t e) { return e >> 8; }
+__device__ __forceinline__ uint32_t entry_sym(uint32_t e) { return (e >> 8) & 0xffu; }
 
 // The eight 4-bit symbols of four pair bytes, one per byte, in order.
 __device__ __forceinline__ void unpack_nibbles(uint32_t d, uint32_t &lo, uint32_t &hi) {
@@ -224,8 +242,8 @@ __device__ __forceinline__ void wave_sync_lds() {
 // Canonical code tables and both lookup levels, built from the 256 (or 16)
 // code lengths by the whole workgroup of WG >= 256 lanes (four waves hold the
 // symbols).  `wcnt` is scratch of 4 * 33 words.
-template <int WG, bool PAIR>
-__device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
+template <int WG, bool PAIR, class TB>
+__device__ __forceinline__ void build_tables(const DevTensor &t, TB &tb, uint32_t *wcnt) {
     static_assert(WG >= 256, "one lane per symbol");
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6;
@@ -377,7 +395,7 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
                 }
                 if (len1 && l0 + len1 <= static_cast<uint32_t>(kL1)) e = pack_entry(s0 | (static_cast<uint32_t>(tb.sorted[idx1]) << 4), l0 + len1);
             }
-            tb.lut[i] = static_cast<uint16_t>(e);
+            tb.lut[i] = static_cast<std::remove_reference_t<decltype(tb.lut[0])>>(e);
             continue;
         }
         // no match: the start of a longer code (the entry says where its second-level block is),
@@ -387,15 +405,19 @@ __device__ void build_tables(const DevTensor &t, Tables &tb, uint32_t *wcnt) {
             e = 7u << 8;
             if (v >= first_prefix) e = (tb.pdepth[v - first_prefix] << 8) | ((tb.pbase[v - first_prefix] >> 4) << 11);
         }
-        if (len) e = pack_entry(tb.sorted[idx], len);
-        tb.lut[i] = static_cast<uint16_t>(e);
+        if (len) {
+            e = pack_entry(tb.sorted[idx], len);
+            if constexpr (sizeof(tb.lut[0]) == 4)       // wide entry: the centred symbol as bf16 in the high half
+                e |= __float_as_uint(static_cast<float>(static_cast<int32_t>(tb.sorted[idx]) - t.zero_point)) & 0xffff0000u;
+        }
+        tb.lut[i] = static_cast<std::remove_reference_t<decltype(tb.lut[0])>>(e);
     }
     __syncthreads();
 }
 
 // Canonical search over the lengths from `from` on.  `window` holds the next 32
 // stream bits, first bit in bit 0.
-__device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t window, uint32_t from, uint32_t max_len) {
+__device__ __noinline__ uint32_t decode_canonical(const TablesTail &tb, uint32_t window, uint32_t from, uint32_t max_len) {
     const uint32_t v = __brev(window);
     for (uint32_t l = from; l <= max_len; ++l) {
         const uint32_t d = (v >> (32 - l)) - tb.first[l];
@@ -407,21 +429,21 @@ __device__ __noinline__ uint32_t decode_canonical(const Tables &tb, uint32_t win
 // The code at the start of `window`, which the first level answered with the
 // miss entry `miss`: second level (needs kL1 + kL2MaxBits valid bits).  Zero if
 // the code is longer still.
-__device__ __forceinline__ uint32_t lookup_l2(const Tables &tb, uint32_t miss, uint32_t window) {
+__device__ __forceinline__ uint32_t lookup_l2(const TablesTail &tb, uint32_t miss, uint32_t window) {
     const uint32_t depth = (miss >> 8) & 7u;
     if (depth > static_cast<uint32_t>(kL2MaxBits)) return 0;
     return tb.lut2[(((miss >> 11) << 4) + __builtin_amdgcn_ubfe(window, kL1, depth)) & (kL2Cap - 1)];
 }
 
 // The same with the canonical search behind it; `window` holds the next 32 stream bits.
-__device__ __forceinline__ uint32_t decode_long(const Tables &tb, uint32_t miss, uint32_t window, uint32_t max_len) {
+__device__ __forceinline__ uint32_t decode_long(const TablesTail &tb, uint32_t miss, uint32_t window, uint32_t max_len) {
     uint32_t e = lookup_l2(tb, miss, window);
     if (__builtin_expect(e == 0, 0)) e = decode_canonical(tb, window, kL1 + 1, max_len);
     return e;
 }
 
 // Pair tables: the single code at the start of `window` (the next 32 stream bits).
-__device__ __forceinline__ uint32_t single_entry(const Tables &tb, uint32_t window, uint32_t max_len) {
+__device__ __forceinline__ uint32_t single_entry(const TablesTail &tb, uint32_t window, uint32_t max_len) {
     uint32_t e = tb.lut2[window & ((1u << kSingleBits) - 1u)];
     if (__builtin_expect(e == 0, 0)) e = decode_canonical(tb, window, kSingleBits + 1, max_len);
     return e;
@@ -466,8 +488,8 @@ struct ScalarReader {
 
 // The next symbol's entry from the scalar reader; r.buf must hold kL1 valid bits.
 // With pair tables the table of single codes answers.
-template <bool PAIR>
-__device__ __forceinline__ uint32_t next_entry(ScalarReader &r, const Tables &tb, uint32_t max_len) {
+template <bool PAIR, class TB>
+__device__ __forceinline__ uint32_t next_entry(ScalarReader &r, const TB &tb, uint32_t max_len) {
     uint32_t e = PAIR ? tb.lut2[static_cast<uint32_t>(r.buf) & ((1u << kSingleBits) - 1u)]
                       : tb.lut[static_cast<uint32_t>(r.buf) & kL1Mask];
     if (__builtin_expect(entry_len(e) == 0, 0)) {
@@ -493,8 +515,8 @@ template <> struct OutTraits<kModeBF16P> { static constexpr int ebits = 16; };
 
 // nsym symbols, element by element: the stream from absolute bit `pos` on holds the tensor's symbols
 // first_sym, first_sym + 1, ... (first_sym is even for packed 4-bit output).
-template <int MODE>
-__device__ void decode_scalar_from(const DevTensor &t, const Tables &tb, uint64_t pos, uint64_t first_sym, uint32_t nsym) {
+template <int MODE, class TB>
+__device__ void decode_scalar_from(const DevTensor &t, const TB &tb, uint64_t pos, uint64_t first_sym, uint32_t nsym) {
     ScalarReader r;
     r.stream = t.stream;
     r.last_off = t.stream_bytes - 8u;
@@ -522,8 +544,8 @@ __device__ void decode_scalar_from(const DevTensor &t, const Tables &tb, uint64_
 }
 
 // All nsym symbols of segment k, element by element.
-template <int MODE>
-__device__ void decode_scalar(const DevTensor &t, const Tables &tb, uint32_t k, uint32_t nsym) {
+template <int MODE, class TB>
+__device__ void decode_scalar(const DevTensor &t, const TB &tb, uint32_t k, uint32_t nsym) {
     decode_scalar_from<MODE>(t, tb, seg_start(t, k), static_cast<uint64_t>(k) * t.chunk_symbols, nsym);
 }
 
@@ -659,7 +681,8 @@ struct Ring2 {
     lds_v32 ring;          // this lane's dword 0; dword d is ring[d * 64]
     uint32_t start64;      // byte offset of line 0 (a multiple of 128)
     uint32_t last_blk;     // stream_bytes - 16
-    uint32_t q;            // p - 1, in bits from line 0
+    uint32_t stale;        // stale low bits of a window: 1 for tables of 16-bit entries, 2 for 32-bit entries
+    uint32_t q;            // p - stale, in bits from line 0
     uint32_t end;          // the ring holds the stream up to here; a multiple of 128, at most kRing2Bits past p's block
     u32x4 nx[8];           // the line that holds block end >> 7
 };
@@ -682,8 +705,8 @@ __device__ __forceinline__ void ring2_load_line(Ring2 &r, uint32_t line) {
 template <bool RARE>
 __device__ __forceinline__ void ring2_fill(Ring2 &r, uint64_t pos) {
     r.start64 = static_cast<uint32_t>(pos >> 3) & ~127u;
-    r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - 1u;
-    const uint32_t first = (r.q + 1u) >> 7;                          // 0..7
+    r.q = static_cast<uint32_t>(pos - (static_cast<uint64_t>(r.start64) << 3)) - r.stale;
+    const uint32_t first = (r.q + r.stale) >> 7;                     // 0..7
     r.end = (first + 4u) * 128u;
     if (RARE) {
 #pragma unroll 1
@@ -710,7 +733,7 @@ __device__ __forceinline__ void ring2_fill(Ring2 &r, uint64_t pos) {
 __device__ __forceinline__ bool ring_short(const Ring2 &r, uint32_t ahead) { return r.q + ahead + 64u >= r.end; }
 
 __device__ __forceinline__ void ring_reload(Ring2 &r) {
-    ring2_fill<true>(r, (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u);
+    ring2_fill<true>(r, (static_cast<uint64_t>(r.start64) << 3) + r.q + r.stale);
 }
 
 template <int J>
@@ -731,7 +754,7 @@ __device__ __forceinline__ void ring2_step(Ring2 &r, uint32_t pblk, bool &wants_
 // Between two half blocks of output: registers into the slots p has left behind, then the request for the
 // next line by the lanes whose registers are used up.
 __device__ __forceinline__ void ring2_topup(Ring2 &r) {
-    const uint32_t pblk = ((r.q + 1u) >> 7) << 7;
+    const uint32_t pblk = ((r.q + r.stale) >> 7) << 7;
     bool wants_line = false;
     ring2_step<0>(r, pblk, wants_line);
     ring2_step<1>(r, pblk, wants_line);
@@ -748,8 +771,11 @@ __device__ __forceinline__ uint64_t ring_read(const Ring2 &r) {
     return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
-__device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) {
-    return *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
+// The first-level entry at this byte offset (an index shifted left by the table's number of stale bits).
+template <class TB>
+__device__ __forceinline__ uint32_t lut_at(const TB &tb, uint32_t byte_off) {
+    typedef std::remove_const_t<std::remove_reference_t<decltype(tb.lut[0])>> E;
+    return *reinterpret_cast<const E *>(reinterpret_cast<const char *>(tb.lut) + byte_off);
 }
 
 // The rest of a group for the lanes that met a code longer than kL1 bits.  e0..e3
@@ -762,8 +788,8 @@ __device__ __forceinline__ uint32_t lut_at(const Tables &tb, uint32_t byte_off) 
 // With pair tables a miss is a pair that the index bits do not hold in full: its
 // two codes, and whatever pair after it misses again, come from the table of
 // single codes, every one with a window of its own.
-template <bool PAIR, class Reader>
-__device__ __forceinline__ uint32_t careful_group(Reader &r, const Tables &tb, uint32_t max_len, uint32_t e0,
+template <bool PAIR, class Reader, class TB>
+__device__ __forceinline__ uint32_t careful_group(Reader &r, const TB &tb, uint32_t max_len, uint32_t e0,
                                                   uint32_t e1, uint32_t e2, uint32_t e3, uint64_t w, uint32_t packed) {
     const uint32_t l0 = entry_len(e0), l1 = entry_len(e1), l2 = entry_len(e2);
     const uint32_t at = l0 == 0 ? 0u : l1 == 0 ? 1u : l2 == 0 ? 2u : 3u;     // place of the long code
@@ -773,12 +799,12 @@ __device__ __forceinline__ uint32_t careful_group(Reader &r, const Tables &tb, u
 #pragma unroll 1
         for (uint32_t i = at; i < static_cast<uint32_t>(kGroup); ++i) {
             if (ring_short(r, 0)) ring_reload(r);
-            uint32_t e = lut_at(tb, static_cast<uint32_t>(ring_read(r)) & (kL1Mask << 1));
+            uint32_t e = lut_at(tb, static_cast<uint32_t>(ring_read(r)) & (kL1Mask << TB::stale));
             if (entry_len(e) == 0) {
-                const uint32_t a = single_entry(tb, static_cast<uint32_t>(ring_read(r) >> 1), max_len);
+                const uint32_t a = single_entry(tb, static_cast<uint32_t>(ring_read(r) >> TB::stale), max_len);
                 r.q += entry_len(a);
                 if (ring_short(r, 0)) ring_reload(r);
-                const uint32_t b = single_entry(tb, static_cast<uint32_t>(ring_read(r) >> 1), max_len);
+                const uint32_t b = single_entry(tb, static_cast<uint32_t>(ring_read(r) >> TB::stale), max_len);
                 r.q += entry_len(b);
                 e = ((entry_sym(a) & 0xfu) | ((entry_sym(b) & 0xfu) << 4)) << 8;
             } else {
@@ -789,10 +815,10 @@ __device__ __forceinline__ uint32_t careful_group(Reader &r, const Tables &tb, u
         if (ring_short(r, kTripBits - 64)) ring_reload(r);
         return packed;
     }
-    uint32_t e = lookup_l2(tb, e3, static_cast<uint32_t>(w >> 1));
+    uint32_t e = lookup_l2(tb, e3, static_cast<uint32_t>(w >> TB::stale));
     if (__builtin_expect(e == 0, 0)) {
         if (ring_short(r, 0)) ring_reload(r);
-        e = decode_canonical(tb, static_cast<uint32_t>(ring_read(r) >> 1), kL1 + 1, max_len);
+        e = decode_canonical(tb, static_cast<uint32_t>(ring_read(r) >> TB::stale), kL1 + 1, max_len);
     }
     packed = __builtin_amdgcn_ubfe(packed, 0, 8u * at) | (entry_sym(e) << (8u * at));
     r.q += entry_len(e);
@@ -803,11 +829,11 @@ __device__ __forceinline__ uint32_t careful_group(Reader &r, const Tables &tb, u
 #pragma unroll
         for (uint32_t i = 1; i < static_cast<uint32_t>(kGroup); ++i) {
             if (i > at) {
-                e = lut_at(tb, static_cast<uint32_t>(wi) & (kL1Mask << 1));
+                e = lut_at(tb, static_cast<uint32_t>(wi) & (kL1Mask << TB::stale));
                 if (__builtin_expect(entry_len(e) == 0, 0)) {
                     if (ring_short(r, 0)) ring_reload(r);
                     wi = ring_read(r);
-                    e = decode_long(tb, e, static_cast<uint32_t>(wi >> 1), max_len);
+                    e = decode_long(tb, e, static_cast<uint32_t>(wi >> TB::stale), max_len);
                     r.q += entry_len(e);
                     if (ring_short(r, 0)) ring_reload(r);
                     wi = ring_read(r);
@@ -830,16 +856,16 @@ __device__ __forceinline__ uint32_t careful_group(Reader &r, const Tables &tb, u
 // bits and give the same entry of length zero); if the wave has such a lane, the
 // rest of its group is decoded with more care.  Returns the group's four symbols,
 // first one lowest.
-template <bool PAIR, class Reader>
-__device__ __forceinline__ uint32_t ring_group(Reader &r, const Tables &tb, uint32_t max_len) {
+template <bool PAIR, class Reader, class TB>
+__device__ __forceinline__ uint32_t ring_group(Reader &r, const TB &tb, uint32_t max_len) {
     uint64_t w = ring_read(r);
-    const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << TB::stale));
     w >>= (e0 & 63u);
-    const uint32_t e1 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    const uint32_t e1 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << TB::stale));
     w >>= (e1 & 63u);
-    const uint32_t e2 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    const uint32_t e2 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << TB::stale));
     w >>= (e2 & 63u);
-    const uint32_t e3 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << 1));
+    const uint32_t e3 = lut_at(tb, static_cast<uint32_t>(w) & (kL1Mask << TB::stale));
     // byte 1 of each entry, in order
     uint32_t packed = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u) | __builtin_amdgcn_perm(e3, e2, 0x05010c0cu);
     uint32_t q_next = r.q + ((e0 + e1 + e2 + e3) & 0xffu);            // lengths add up in the low byte (<= 56)
@@ -854,8 +880,42 @@ __device__ __forceinline__ uint32_t ring_group(Reader &r, const Tables &tb, uint
     return packed;
 }
 
-template <int MODE>
-__device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &tb, uint32_t k);
+// ring_group on wide tables, for the GEMV: returns the four symbols' values (symbol - zero_point as bf16, two per
+// dword, first one lowest) instead of the symbols.
+template <class Reader>
+__device__ __forceinline__ u32x2 ring_group_wide(Reader &r, const Tables32 &tb, uint32_t max_len, float zf) {
+    constexpr uint32_t kMask = kL1Mask << Tables32::stale;
+    uint64_t w = ring_read(r);
+    const uint32_t e0 = lut_at(tb, static_cast<uint32_t>(w) & kMask);
+    w >>= (e0 & 63u);
+    const uint32_t e1 = lut_at(tb, static_cast<uint32_t>(w) & kMask);
+    w >>= (e1 & 63u);
+    const uint32_t e2 = lut_at(tb, static_cast<uint32_t>(w) & kMask);
+    w >>= (e2 & 63u);
+    const uint32_t e3 = lut_at(tb, static_cast<uint32_t>(w) & kMask);
+    // the high halves of the entries, in order
+    u32x2 vals = {__builtin_amdgcn_perm(e1, e0, 0x07060302u), __builtin_amdgcn_perm(e3, e2, 0x07060302u)};
+    uint32_t q_next = r.q + ((e0 + e1 + e2 + e3) & 0xffu);
+    const bool miss = (e3 & 0xffu) == 0;
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(miss) != 0, 0)) {
+        if (miss) {
+            const uint32_t packed = careful_group<false>(r, tb, max_len, e0, e1, e2, e3, w,
+                                                         __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u) | __builtin_amdgcn_perm(e3, e2, 0x05010c0cu));
+            // the same values by arithmetic: an integer of at most 256 in magnitude is a bf16 as it stands
+            const uint32_t v0 = __float_as_uint(static_cast<float>(packed & 0xffu) - zf) >> 16;
+            const uint32_t v1 = __float_as_uint(static_cast<float>((packed >> 8) & 0xffu) - zf) & 0xffff0000u;
+            const uint32_t v2 = __float_as_uint(static_cast<float>((packed >> 16) & 0xffu) - zf) >> 16;
+            const uint32_t v3 = __float_as_uint(static_cast<float>(packed >> 24) - zf) & 0xffff0000u;
+            vals = u32x2{v0 | v1, v2 | v3};
+            q_next = r.q;
+        }
+    }
+    r.q = q_next;
+    return vals;
+}
+
+template <int MODE, class TB>
+__device__ __forceinline__ void gemv_segment(const DevTensor &t, const TB &tb, uint32_t k);
 
 // Decode the kUnit segments from wave_first on, one per lane of this wavefront,
 // SPB symbols per lane at a time into the wave's
@@ -895,6 +955,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     const uint32_t my_blocks = nsym / SPB;
     uint64_t tail_pos = fast ? seg_start(t, k) : 0;       // where the symbols behind the lane's last whole block start
     Ring2 r;
+    r.stale = Tables::stale;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(wm.ring + lane);
@@ -927,7 +988,7 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
             // the short ring is topped up after every eight groups
             if (trip & 1) ring2_topup(r);
         }
-        if (bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
+        if (bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + r.stale;
         wave_sync_lds();
 #pragma unroll
         for (uint32_t it = 0; it < 64 / RPI; ++it) {
@@ -1052,6 +1113,7 @@ __device__ __forceinline__ void decode_rows2_impl(const DevTensor &t, const Tabl
     const uint32_t my_blocks = nsym / SPB;
     uint64_t tail_pos = fast ? seg_start(t, k) : 0;
     Ring2 r;
+    r.stale = Tables::stale;
     r.stream = t.stream;
     r.last_blk = t.stream_bytes - 16u;
     r.ring = (lds_v32)(wm.ring + lane);
@@ -1079,7 +1141,7 @@ __device__ __forceinline__ void decode_rows2_impl(const DevTensor &t, const Tabl
                 for (int g = 0; g < kTripGroups; ++g)
                     tile[WaveMem2::tile_at(lane, trip * kTripGroups + g)] = ring_group<false>(r, tb, max_len);
             }
-            if (!ALLFULL && half == 1 && bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + 1u;
+            if (!ALLFULL && half == 1 && bs + 1 == my_blocks) tail_pos = (static_cast<uint64_t>(r.start64) << 3) + r.q + r.stale;
             ring2_topup(r);
             wave_sync_lds();
 #pragma unroll
@@ -1135,8 +1197,8 @@ __device__ __forceinline__ void decode_rows2(const DevTensor &t, const Tables &t
 // Decode one segment straight into dot products with x.  A segment covers one
 // or more row fragments; complete rows are stored, a leading / trailing
 // incomplete fragment goes to the segment's head / tail partial.
-template <int MODE>
-__device__ __forceinline__ void gemv_segment(const DevTensor &t, const Tables &tb, uint32_t k) {
+template <int MODE, class TB>
+__device__ __forceinline__ void gemv_segment(const DevTensor &t, const TB &tb, uint32_t k) {
     const uint32_t C = t.chunk_symbols;
     const uint64_t first_sym = static_cast<uint64_t>(k) * C;
     const uint64_t left = t.n - first_sym;
@@ -1304,13 +1366,138 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
     }
 }
 
+// The same on wide tables and the short ring (8-bit symbols whose zero-point lies in [-1, 256], so that
+// symbol - zero_point is a bf16): sixteen wavefronts, two products per instruction, no conversion per symbol.
+// GEMV: the lane that decodes a segment also multiplies it into x, a group of symbols at a time as
+// they come out of the table; there is no tile and no flush, which leaves LDS for 14 wavefronts.
+// All lanes are at the same place of their segments, so where segments and rows coincide the lanes
+// of a wave ask for the same piece of x (one request); elsewhere they ask for a handful of
+// different ones.  The 64 activations of a half block are requested one half block ahead, before
+// the stream lines that ring_topup asks for: loads return in order, and a wait for x must not
+// become a wait for the stream.
+// A segment may begin and end anywhere in a row and hold any number of row ends (cols >= 64, so a
+// half block holds at most one): the sum up to the first row end is the head fragment (or a whole
+// row, if the segment starts one), every further row end completes a whole row, which the lane
+// stores itself, and what is left at the end is the tail fragment; the fragments go to the
+// segment's two partial sums, which the second stage adds up per row.
+template <int MODE>
+__device__ __forceinline__ void gemv_direct2(const DevTensor &t, const Tables32 &tb, uint32_t *ring_mem, uint32_t wave_first) {
+    constexpr int GPH = 16;                                // groups of four symbols per half block of 64 symbols
+    const uint32_t lane = threadIdx.x & 63u;
+    if (wave_first >= t.n_chunks) return;
+    const uint32_t C = t.chunk_symbols;
+    const uint32_t k = wave_first + lane;
+    uint32_t nsym = 0;
+    if (k < t.n_chunks) {
+        const uint64_t left = t.n - static_cast<uint64_t>(k) * C;
+        nsym = left < C ? static_cast<uint32_t>(left) : C;
+    }
+    const bool fast = nsym == C;                           // a shorter last segment takes the element-by-element path
+    Ring2 r;
+    r.stale = Tables32::stale;
+    r.stream = t.stream;
+    r.last_blk = t.stream_bytes - 16u;
+    r.ring = (lds_v32)(ring_mem + lane);
+    // a lane without a full segment decodes the start of the stream along with the others; nothing of it is stored
+    ring2_fill<false>(r, fast ? seg_start(t, k) : 0);
+    const uint32_t cols = t.cols;
+    const uint16_t *xvec = t.x;
+    const uint32_t max_len = t.max_len;
+    const float zf = static_cast<float>(t.zero_point);    // exact: the host rejects |z| > 2^24
+    const float scale = t.scale;
+    const uint64_t flat0 = static_cast<uint64_t>(k) * C;
+    uint32_t col = fast ? static_cast<uint32_t>(flat0 % cols) : 0u;    // column of the half block's first symbol
+    uint32_t row = fast ? static_cast<uint32_t>(flat0 / cols) : 0u;    // the row the lane is in
+    const bool starts_row = col == 0;
+    float acc = 0.0f, first = 0.0f, end_sum = 0.0f;
+    bool crossed = false;                                  // a row end has been passed
+    bool ended = false;                                    // a row ended in this half block: end_sum holds its sum
+    // eight activations per piece; a piece never straddles a row end (cols % 8 == 0, segments start at multiples of 64)
+    u32x4 xb[8];
+    auto ask_x = [&](uint32_t c0) {
+#pragma unroll
+        for (uint32_t p = 0; p < 8; ++p) {
+            uint32_t c = c0 + 8u * p;
+            c -= c >= cols ? cols : 0u;
+            xb[p] = *(global_u4_ptr)(xvec + c);
+        }
+    };
+    // two products per instruction: the table entries hold symbol - zero_point as bf16, x is bf16 as it stands
+    // (the halves of v go through scalars: a bit cast applied to a vector's element reads element 0 whichever is named)
+    auto mul4 = [&](u32x2 v, uint32_t xa, uint32_t xc) {
+        const uint32_t lo = v.x, hi = v.y;
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, lo), __builtin_bit_cast(bf16x2, xa), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, hi), __builtin_bit_cast(bf16x2, xc), acc, false);
+    };
+    ask_x(col);
+    const uint32_t halves = C / 64u;
+    // eight groups as one stretch of straight-line code; PART says which eight of the half block's sixteen
+    auto eight = [&](auto part_tag) __attribute__((always_inline)) {
+        constexpr int PART = decltype(part_tag)::value;
+#pragma unroll
+        for (int gg = 0; gg < GPH / 2; ++gg) {
+            const int g = PART * (GPH / 2) + gg;
+            if (g % kTripGroups == 0)
+                if (__builtin_expect(ring_short(r, kTripBits - 64), 0)) ring_reload(r);
+            const u32x2 v4 = ring_group_wide(r, tb, max_len, zf);
+            const u32x4 xv = xb[g / 2];
+            mul4(v4, (g & 1) ? xv.z : xv.x, (g & 1) ? xv.w : xv.y);
+            if (g & 1) {
+                // a row ends behind this piece (at most once per half block: cols >= 64): its sum is set
+                // aside without a branch, so that the groups stay one stretch of code
+                const uint32_t piece = g / 2;
+                const bool row_end = col + 8u * piece + 8u == cols;
+                end_sum = row_end ? acc : end_sum;
+                acc = row_end ? 0.0f : acc;
+                ended |= row_end;
+            }
+        }
+    };
+    for (uint32_t h = 0; h < halves; ++h) {
+        eight(std::integral_constant<int, 0>{});
+        ring2_topup(r);                                    // the short ring is topped up after every eight groups
+        eight(std::integral_constant<int, 1>{});
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(ended) != 0, 0)) {
+            if (ended) {
+                if (!crossed && !starts_row) {
+                    first = end_sum;                       // the head fragment
+                } else if (fast) {                         // a whole row
+                    const float y = end_sum * scale;
+                    if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
+                    else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
+                }
+                crossed = true;
+                row += 1u;
+                ended = false;
+            }
+        }
+        col += 64u;
+        col -= col >= cols ? cols : 0u;
+        if (h + 1 < halves) ask_x(col);
+        ring2_topup(r);
+    }
+    if (fast) {
+        if (!crossed) {
+            t.partials[2 * static_cast<uint64_t>(k)] = acc;              // the segment lies inside one row
+        } else {
+            if (!starts_row) t.partials[2 * static_cast<uint64_t>(k)] = first;
+            if (col != 0) t.partials[2 * static_cast<uint64_t>(k) + 1] = acc;   // the segment ends inside a row
+        }
+    } else if (nsym) {
+        gemv_segment<MODE>(t, tb, k);
+    }
+}
+
 // The GEMV kernels need the tables and the scratch table only.
 struct alignas(256) RingMem { uint32_t ring[kRingDwords * 64]; };
 // which modes decode on the short ring (decode_rows2)
 constexpr bool short_ring(int mode) { return mode == kModeF32 || mode == kModeBF16; }
-template <int MODE, bool GEMV = is_gemv(MODE), bool SHORT = short_ring(MODE)> struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
-template <int MODE> struct SmemFor<MODE, true, false> { Tables tb; RingMem wm[Cfg<MODE>::waves]; };
-template <int MODE> struct SmemFor<MODE, false, true> { Tables tb; WaveMem2 wm[Cfg<MODE>::waves]; };
+struct alignas(256) Ring2Mem { uint32_t ring[kRing2Dwords * 64]; };
+template <int MODE, bool GEMV = is_gemv(MODE), bool SHORT = short_ring(MODE), bool WIDE = wide_gemv(MODE)>
+struct SmemFor { Tables tb; WaveMem<Cfg<MODE>::row> wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor<MODE, true, false, false> { Tables tb; RingMem wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor<MODE, true, false, true> { Tables32 tb; Ring2Mem wm[Cfg<MODE>::waves]; };
+template <int MODE> struct SmemFor<MODE, false, true, false> { Tables tb; WaveMem2 wm[Cfg<MODE>::waves]; };
 
 // Does the tensor go through decode_rows?  Segments must tile into blocks; for the
 // GEMV, pieces of eight must not straddle a matrix row and a segment must touch at
@@ -1324,8 +1511,8 @@ __device__ __forceinline__ bool rows_fit(const DevTensor &t) {
 
 // Segments [first, end) of a tensor that does not fit the row path: one lane per
 // segment, element by element, the whole workgroup striding over them.
-template <int MODE>
-__device__ __forceinline__ void scalar_chunks(const DevTensor &t, const Tables &tb, uint32_t first, uint32_t end) {
+template <int MODE, class TB>
+__device__ __forceinline__ void scalar_chunks(const DevTensor &t, const TB &tb, uint32_t first, uint32_t end) {
     constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
     for (uint32_t k = first + threadIdx.x; k < end; k += WG) {
         if constexpr (is_gemv(MODE)) {
@@ -1350,7 +1537,8 @@ __device__ __forceinline__ void single_body(const DevTensor &t, uint32_t wg_unit
     if (rows_fit<MODE>(t)) {
         const uint32_t wave = threadIdx.x >> 6;
         if (wave < wg_units) {
-            if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
+            if constexpr (wide_gemv(MODE)) gemv_direct2<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
+            else if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[wave].ring, first + wave * kUnit);
             else if constexpr (short_ring(MODE)) decode_rows2<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
             else decode_rows<MODE>(t, sm.tb, sm.wm, first + wave * kUnit);
         }
@@ -1395,7 +1583,8 @@ __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors
                 if ((threadIdx.x & 63u) == 0) u = atomicAdd(&next_unit, 1u);
                 u = __builtin_amdgcn_readfirstlane(u);
                 if (u >= n_units) break;
-                if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
+                if constexpr (wide_gemv(MODE)) gemv_direct2<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
+                else if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
                 else if constexpr (short_ring(MODE)) decode_rows2<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
                 else decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
             }
@@ -1584,6 +1773,8 @@ void dispatch_mode(int mode, F f) {
         case kModeBF16P: f(std::integral_constant<int, kModeBF16P>{}); break;
         case kModeGemvF32P: f(std::integral_constant<int, kModeGemvF32P>{}); break;
         case kModeGemvBF16P: f(std::integral_constant<int, kModeGemvBF16P>{}); break;
+        case kModeGemvF32W: f(std::integral_constant<int, kModeGemvF32W>{}); break;
+        case kModeGemvBF16W: f(std::integral_constant<int, kModeGemvBF16W>{}); break;
         default: f(std::integral_constant<int, kModeGemvBF16>{}); break;
     }
 }
@@ -1596,9 +1787,15 @@ unsigned wg_of(int mode) {
 }
 
 // `pairs`: every tensor of the launch holds 4-bit symbols, so the tables can hold two codes per entry.
-int mode_of(entro_op op, entro_dtype d, bool pairs) {
+// Does the GEMV of this tensor fit the wide tables?
+bool wide_ok(const DevTensor &dt) { return dt.bits == 8 && dt.zero_point >= -1 && dt.zero_point <= 256; }
+
+// `wide`: a GEMV all of whose tensors hold 8-bit symbols with a zero-point in [-1, 256] (symbol - zero_point is a
+// bf16 then, which the wide tables hold ready for use).
+int mode_of(entro_op op, entro_dtype d, bool pairs, bool wide = false) {
     if (op == ENTRO_OP_GEMV) {
         if (pairs) return d == ENTRO_F32 ? kModeGemvF32P : kModeGemvBF16P;
+        if (wide) return d == ENTRO_F32 ? kModeGemvF32W : kModeGemvBF16W;
         return d == ENTRO_F32 ? kModeGemvF32 : kModeGemvBF16;
     }
     switch (d) {
@@ -1636,7 +1833,7 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     DevTensor dt;
     entro_status st = fill_dev_tensor(t, op, d, 0, &dt);
     if (st != ENTRO_OK) return st;
-    const int mode = mode_of(op, d, dt.bits == 4);
+    const int mode = mode_of(op, d, dt.bits == 4, wide_ok(dt));
     const unsigned wg = wg_of(mode);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
@@ -1859,13 +2056,14 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
     // how fine the lanes are cut is decided for the launch as a whole (all its tensors are 4-bit, or the
     // tables take single codes: the kernel and with it the lane slots are known before the tensors are looked at)
     // (all argument checks come first, on the host alone)
-    bool all4 = true;
+    bool all4 = true, wide = true;
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, 0, &dts[i]);
         if (st != ENTRO_OK) return st;
         all4 = all4 && dts[i].bits == 4;
+        wide = wide && wide_ok(dts[i]);
     }
-    const int mode0 = mode_of(op, out_type, all4);
+    const int mode0 = mode_of(op, out_type, all4, wide);
     const unsigned slots0 = resident_workgroups(mode0);
     if (slots0 == 0) return ENTRO_ERR_DEVICE;
     const uint32_t level = choose_level(ts, count, static_cast<uint64_t>(slots0) * wg_of(mode0));
@@ -1883,9 +2081,8 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
     }
     // A work item is what a workgroup takes in one round when the launch is large (a unit per
     // wavefront), and less when the launch would not give every compute unit an item otherwise.
-    const int mode = mode_of(op, out_type, pairs);
-    const unsigned slots = resident_workgroups(mode);
-    if (slots == 0) return ENTRO_ERR_DEVICE;
+    const int mode = mode0;
+    const unsigned slots = slots0;
     const uint64_t waves = wg_of(mode) / 64u;
     const uint32_t item_units = static_cast<uint32_t>(std::min<uint64_t>(waves, std::max<uint64_t>(1, total_units / slots)));
     for (uint32_t i = 0; i < count; ++i)
@@ -1899,6 +2096,7 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
     plan->n_fix = static_cast<uint32_t>(n_fix);
     plan->item_units = item_units;
     plan->pair_tables = pairs ? 1u : 0u;
+    plan->wide_tables = (op == ENTRO_OP_GEMV && !pairs && wide) ? 1u : 0u;
     plan->gemv_multirow = multirow ? 1u : 0u;
     plan->off_tensors = L.off_tensors;
     plan->off_items = L.off_items;
@@ -1965,7 +2163,8 @@ entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {
     const DevTensor *dts = reinterpret_cast<const DevTensor *>(ws + plan->off_tensors);
     const WorkItem *items = reinterpret_cast<const WorkItem *>(ws + plan->off_items);
     const WorkItem *fix = reinterpret_cast<const WorkItem *>(ws + plan->off_fix);
-    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0);
+    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0,
+                             plan->wide_tables != 0);
     const unsigned slots = resident_workgroups(mode);
     if (slots == 0) return ENTRO_ERR_DEVICE;
     const unsigned grid = plan->n_items < slots ? plan->n_items : slots;

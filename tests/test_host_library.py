@@ -33,7 +33,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(B.QParams) == 16
     assert C.sizeof(B.Codebook) == 16 + 256 + 1024
     assert C.sizeof(B.CTensor) == 8 + 8 + 8 + 8 + 16 + 8 + 16 + 8 + 8 + 8
-    assert C.sizeof(B.Plan) == 16 + 32 + 32
+    assert C.sizeof(B.Plan) == 16 + 32 + 8 + 32
 
 
 @pytest.mark.parametrize("bits,scheme", [(8, 1), (8, 0), (4, 1), (4, 0)])
