@@ -6,8 +6,11 @@ A step is one entro_decode_dequant pass (-> bf16) over the whole mistral-7B-shap
 the compressed streams and offset tables already resident in HBM.  The same run
 also times the two other sinks of the path on the same compressed set -- integer
 output (entro_decode -> u8) and the fused batch-1 GEMV (entro_decode_gemv, four
-launches per layer as the layer's data dependencies allow) -- and reports them
-as extra fields.  One JSON line is printed at the end.
+launches per layer as the layer's data dependencies allow, eagerly and as one
+captured HIP graph; and all products in one launch) -- and reports them as extra
+fields.  The memory probe and the plain uint8 GEMV it is compared with come from
+bench_kernels/ (their own shared object, not the library).  One JSON line is
+printed at the end.
 """
 import argparse
 import json
@@ -23,17 +26,24 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_batch_bf16_mistral7b_pmc_hbm_bytes.txt")
 
 
-def measured_traffic():
-    """HBM bytes per launch of the headline kernel as the rocprofv3 byte counters gave them
-    (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size); None when no summary is there."""
+def profiled_traffic():
+    """(HBM bytes per launch of the headline kernel, where that number comes from): the rocprofv3 byte
+    counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size) are taken in runs of their own,
+    so this is read from the committed summary, which names the commit it was taken at; (None, None)
+    when no summary is there."""
+    value, commit = None, "unknown"
     try:
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 if line.startswith("traffic_bytes_per_launch"):
-                    return int(line.split("=")[1])
+                    value = int(line.split("=")[1])
+                if line.startswith("commit"):
+                    commit = line.split("=")[1].strip()
     except OSError:
         pass
-    return None
+    if value is None:
+        return None, None
+    return value, f"not measured in this run: copied from profiles/{os.path.basename(TRAFFIC_FILE)}, taken at commit {commit}"
 
 
 def log(msg):
@@ -49,6 +59,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the u8 and GEMV legs")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the legs on configs[0..2]")
+    ap.add_argument("--sub-symbols", type=int, default=256,
+                    help="entry points inside the segments every this many symbols (0: none)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -62,6 +74,7 @@ def main():
     import synth
     import paper_2505_02380_amd as E
     from paper_2505_02380_amd.workload import prepare_config, default_threads
+    import bench_kernels
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -72,6 +85,9 @@ def main():
         from paper_2505_02380_amd import build as lib_build
         lib_build.build(force=True)
     E.lib()
+    if not os.path.exists(bench_kernels.LIB):
+        bench_kernels.build(force=True)
+    bench_kernels.lib()
 
     # ------------------------------------------------------------------ inputs
     t0 = time.time()
@@ -83,10 +99,11 @@ def main():
             log(f"encoded {done[0]}/{total} tensors ({time.time() - t0:.0f} s)")
 
     log(f"preparing mistral-7B-shaped set, {args.layers} layers, {default_threads()} host threads")
-    encs = prepare_config(4, layers=args.layers, progress=progress)
+    encs = prepare_config(4, layers=args.layers, progress=progress, sub_symbols=args.sub_symbols)
     n_sym = sum(e.n for e in encs)
     stream_bytes = sum(e.stream.size for e in encs)
     offset_bytes = sum(e.offsets.size * 8 for e in encs)
+    sub_bytes = sum(e.sub_bits.size * 2 for e in encs if e.sub_symbols)
     total_bits = sum(e.total_bits for e in encs)
     mean_len = total_bits / n_sym
     log(f"{n_sym} symbols, {stream_bytes / 1e9:.3f} GB compressed, mean code length {mean_len:.3f} bits, "
@@ -126,34 +143,65 @@ def main():
     achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
     log(f"dequant: {wall_ms:.3f} ms/step wall, {kern_ms:.3f} ms kernel, {achieved:.0f} GB/s algorithmic")
 
-    # ---------------------------------------------- check sampled segments against the oracle
+    # ------------------------- check against the oracle: whole tensors of every kind, sampled segments of the rest
     import oracle
-    rng = np.random.default_rng(2024)
-    checked = 0
-    for _ in range(24):
-        i = int(rng.integers(0, len(encs)))
-        e = encs[i]
-        k = int(rng.integers(0, e.offsets.size - 1))
-        lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
-        q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
-                                 out=np.zeros(e.n, np.uint8))[lo:hi]
-        ref = oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
-        got = views[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
-        if not np.array_equal(got, ref):
-            print(f"bench.py: GPU output differs from the oracle in tensor {e.name} segment {k}", file=sys.stderr)
-            sys.exit(1)
-        checked += 1
-    log(f"{checked} sampled segments match the oracle")
+    from concurrent.futures import ThreadPoolExecutor
+
+    def oracle_symbols(e):
+        return oracle.decode(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes())
+
+    def check_whole(enc_list, idx, got_of, ref_of, what):
+        """Every element of the tensors `idx` of enc_list: got_of(i) is the GPU's output as a numpy array,
+        ref_of(e, q) the oracle's from the oracle-decoded symbols q (one oracle call per tensor and thread)."""
+        with ThreadPoolExecutor(default_threads()) as pool:
+            qs = list(pool.map(lambda i: oracle_symbols(enc_list[i]), idx))
+        for i, q in zip(idx, qs):
+            if not np.array_equal(got_of(i), ref_of(enc_list[i], q)):
+                print(f"bench.py: GPU output ({what}) differs from the oracle in tensor {enc_list[i].name}", file=sys.stderr)
+                sys.exit(1)
+        return len(idx)
+
+    def check_segments(enc_list, count, seed, got_of, ref_of, what):
+        """`count` segments drawn over all tensors: got_of(i, lo, hi) the GPU's output for symbols [lo, hi)."""
+        rng_s = np.random.default_rng(seed)
+        for _ in range(count):
+            i = int(rng_s.integers(0, len(enc_list)))
+            e = enc_list[i]
+            k = int(rng_s.integers(0, e.offsets.size - 1))
+            lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
+            q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
+                                     out=np.zeros(e.n, np.uint8))[lo:hi]
+            if not np.array_equal(got_of(i, lo, hi), ref_of(e, q)):
+                print(f"bench.py: GPU output ({what}) differs from the oracle in tensor {e.name} segment {k}", file=sys.stderr)
+                sys.exit(1)
+        return count
+
+    def bf16_ref(e, q):
+        return oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
+
+    def kinds_idx(enc_list):
+        """The first tensor of every kind (name without the layer) and the last tensor of the set."""
+        first = {}
+        for i, e in enumerate(enc_list):
+            first.setdefault(e.name.split(".", 1)[1], i)
+        return sorted(set(first.values()) | {len(enc_list) - 1})
+
+    whole_idx = kinds_idx(encs)
+    whole = check_whole(encs, whole_idx, lambda i: views[i].view(torch.int16).cpu().numpy().view(np.uint16), bf16_ref, "bf16")
+    checked = check_segments(encs, 24, 2024, lambda i, lo, hi: views[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16),
+                             bf16_ref, "bf16")
+    log(f"{whole} whole tensors ({sum(encs[i].n for i in whole_idx)} elements) and {checked} sampled segments match the oracle")
 
     # ------------------------- what this GPU's memory takes of a plain stream with the same read/write mix
     rb = (stream_bytes + offset_bytes + 15) // 16 * 16
     probe_src = torch.zeros(rb, dtype=torch.uint8, device=dev)
     probe_scratch = torch.zeros(16, dtype=torch.uint8, device=dev)
-    wp, kp = timed(lambda: E.entro_stream_probe(probe_src, rb, out_bf16, out_bytes, probe_scratch), args.steps, args.warmup)
+    wp, kp = timed(lambda: bench_kernels.stream_probe(probe_src, rb, out_bf16, out_bytes, probe_scratch), args.steps, args.warmup)
     ceiling = (rb + out_bytes) / (kp * 1e-3) / 1e9
     log(f"stream probe with the same byte counts: {kp:.3f} ms, {ceiling:.0f} GB/s")
     del probe_src
 
+    traffic, traffic_source = profiled_traffic() if args.layers == 32 else (None, None)
     result = {
         "metric": "decoded weights GB/s (entro_decode_dequant -> bf16, mistral-7B-shaped 8-bit set)",
         "value": round(decoded_gbps, 2),
@@ -171,16 +219,22 @@ def main():
                                "asymmetric 8-bit, chunks of 4096 symbols, decode+dequant to bf16",
                    "symbols": n_sym, "tensors": len(encs), "compressed_bytes": stream_bytes,
                    "mean_code_len_bits": round(mean_len, 4),
+                   "offset_table_bits_per_symbol": round(offset_bytes * 8 / n_sym, 4),
+                   "entry_points_inside_segments": {"every_symbols": args.sub_symbols,
+                                                    "bits_per_symbol": round(sub_bytes * 8 / n_sym, 4),
+                                                    "read_by": "launches too small to fill the device with whole segments "
+                                                               "(the dependent GEMV step) in full; large launches for the units "
+                                                               "left over behind a workgroup's last whole round"},
                    "bits_saved": round(E.entro_bits_saved(8, mean_len), 4),
                    "theoretical_speedup": round(E.entro_theoretical_speedup(8, mean_len), 4)},
         "symbols_per_s": round(n_sym / (wall_ms * 1e-3), 0),
         "compressed_GBps": round(stream_bytes / (wall_ms * 1e-3) / 1e9, 2),
         "hbm_fraction_wall": round(algo_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "verified_segments": checked,
-        "roofline": {"bound": "hbm", "kernel": "k_batch<bf16>", "achieved": round(achieved, 1),
+        "verified_whole_tensors": whole, "verified_segments": checked,
+        "roofline": {"bound": "hbm", "kernel": "k_batch<3> (entro_decode_dequant_batch -> bf16)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": round(kern_ms, 4),
-                     "traffic": measured_traffic() if args.layers == 32 else None},
+                     "traffic": traffic, "traffic_source": traffic_source},
         # a coalesced kernel that reads and writes the same byte counts, reads and writes interleaved in
         # their ratio: the rate memory takes a plain stream of this mix at, and the launch against it
         "stream_ceiling": {"GBps": round(ceiling, 1), "kernel_ms": round(kp, 4), "frac_of_peak": round(ceiling / HBM_PEAK_GBPS, 4),
@@ -202,19 +256,19 @@ def main():
         result["decode_u8"] = {"ms_per_step": round(w8, 4), "kernel_ms": round(k8, 4),
                                "symbols_per_s": round(n_sym / (w8 * 1e-3), 0),
                                "hbm_frac": round((stream_bytes + offset_bytes + n_sym) / (k8 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
-        # the product on those plain bytes: the uint8 model that the entropy-coded one is compared with
+        whole8 = check_whole(encs, whole_idx, lambda i: v8[i].cpu().numpy(), lambda e, q: q, "u8")
+        result["decode_u8"]["verified_whole_tensors"] = whole8
+        # the product on those plain bytes: the uint8 model that the entropy-coded one is compared with,
+        # all 224 products in one launch
         log("timing the plain uint8 GEMV on the decoded bytes (comparison)")
         xs_p = {c: torch.from_numpy(synth.make_x_bf16(0, c % 7, c).view(np.int16)).to(dev).view(torch.bfloat16)
                 for c in sorted({e.cols for e in encs})}
         ys_p = [torch.zeros(e.rows, dtype=torch.float32, device=dev) for e in encs]
-
-        def plain_token():
-            for e, v, y in zip(encs, v8, ys_p):
-                E.entro_gemv_u8_plain(v, e.rows, e.cols, e.qp, xs_p[e.cols], y)
-
-        wpl, kpl = timed(plain_token, max(3, args.steps // 2), 1)
+        plain = bench_kernels.PlainGemv([(v, e.rows, e.cols, e.qp.scale, e.qp.zero_point, xs_p[e.cols], y)
+                                         for e, v, y in zip(encs, v8, ys_p)], dev)
+        wpl, kpl = timed(plain.run, args.steps, args.warmup)
         rngp = np.random.default_rng(99)
-        for _ in range(4):
+        for _ in range(8):
             i = int(rngp.integers(0, len(encs)))
             e = encs[i]
             r = int(rngp.integers(0, e.rows))
@@ -227,13 +281,14 @@ def main():
                 print(f"bench.py: plain uint8 GEMV differs from the oracle, tensor {e.name} row {r}", file=sys.stderr)
                 sys.exit(1)
         result["gemv_plain_uint8"] = {"workload": "the same 224 products on the decoded weights stored one byte each (what the "
-                                                  "entropy-coded model is compared with), one launch per tensor",
+                                                  "entropy-coded model is compared with), all in one launch "
+                                                  "(bench_kernels/, not part of the library)",
                                       "us_per_layer": round(wpl * 1e3 / args.layers, 2),
                                       "kernel_us_per_layer": round(kpl * 1e3 / args.layers, 2),
                                       "weight_GBps": round(n_sym / (kpl * 1e-3) / 1e9, 1),
-                                      "hbm_frac": round(n_sym / (kpl * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "verified_rows": 4}
+                                      "hbm_frac": round(n_sym / (kpl * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "verified_rows": 8}
         log(f"plain uint8 gemv: {kpl * 1e3 / args.layers:.1f} us/layer")
-        del out_u8, v8, ts8, plan8, xs_p, ys_p
+        del out_u8, v8, ts8, plan8, xs_p, ys_p, plain
 
         log("timing entro_decode_gemv (batch-1 token step, 4 launches per layer)")
         groups = [(0, 3), (3, 4), (4, 6), (6, 7)]          # q,k,v | o | gate,up | down
@@ -260,6 +315,17 @@ def main():
                 E.entro_plan_run(p)
 
         wg, kg = timed(token_step, args.steps, args.warmup)
+        # the same launches recorded once into a HIP graph and replayed (plan runs only enqueue kernels)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            token_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            token_step()
+        wgr, kgr = timed(graph.replay, args.steps, args.warmup)
 
         def check_gemv(what):
             """A few rows of the first layer's `q` and the last layer's `down` against the oracle."""
@@ -279,9 +345,10 @@ def main():
                     print(f"bench.py: GEMV output ({what}) differs from the oracle in tensor {e.name}", file=sys.stderr)
                     sys.exit(1)
 
-        check_gemv("dependent launches")
+        check_gemv("dependent launches, graph replay")
         result["gemv"] = {"us_per_layer": round(wg * 1e3 / layers, 2), "kernel_us_per_layer": round(kg * 1e3 / layers, 2),
-                          "launches_per_layer": len(groups),
+                          "hip_graph_us_per_layer": round(wgr * 1e3 / layers, 2),
+                          "launches_per_layer": len(groups), "wide_tables": bool(plans[0].wide_tables),
                           "compressed_GBps": round(stream_bytes / (wg * 1e-3) / 1e9, 2),
                           "effective_uint8_GBps": round(n_sym / (wg * 1e-3) / 1e9, 2),
                           "hbm_frac": round((stream_bytes + offset_bytes) / (kg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
@@ -303,46 +370,6 @@ def main():
                                      "effective_uint8_GBps": round(n_sym / (wa * 1e-3) / 1e9, 2),
                                      "hbm_frac": round((stream_bytes + offset_bytes) / (ka * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         log(f"gemv, one launch: {result['gemv_one_launch']['us_per_layer']} us/layer")
-
-        # the dependent step again on layers encoded with segments of 512 symbols: eight times the lanes
-        # per launch, an eighth of the serial work per lane (segment size is a per-tensor encode choice)
-        small_layers = min(4, layers)
-        log(f"timing the dependent GEMV step with 512-symbol segments ({small_layers} layers)")
-        encs_s = prepare_config(4, layers=small_layers, chunk_symbols=512)
-        dts_s = [E.to_device(e, dev) for e in encs_s]
-        plans_s, keep_s = [], []
-        for layer in range(small_layers):
-            base = 7 * layer
-            for a, b in groups:
-                tl = []
-                for j in range(a, b):
-                    e = encs_s[base + j]
-                    x, y = pairs[base + j][0], torch.zeros(e.rows, dtype=torch.float32, device=dev)
-                    keep_s.append(y)
-                    tl.append(dts_s[base + j].ctensor(y, x))
-                wsg = torch.zeros(max(256, E.entro_workspace_bytes(tl, E.ENTRO_OP_GEMV)), dtype=torch.uint8, device=dev)
-                keep_s.append(wsg)
-                plans_s.append(E.entro_plan_init(tl, E.ENTRO_OP_GEMV, E.ENTRO_F32, wsg))
-
-        def token_step_small():
-            for p in plans_s:
-                E.entro_plan_run(p)
-
-        wsm, ksm = timed(token_step_small, args.steps, args.warmup)
-        # same weights, same x: the products must agree with the 4096-symbol run (rounding order apart)
-        y_small = torch.cat([k for k in keep_s if k.dtype == torch.float32])
-        y_big = torch.cat([pairs[i][1] for i in range(7 * small_layers)])
-        dev_rel = float((y_small - y_big).abs().max() / y_big.abs().max())
-        if dev_rel > 1e-4:
-            print(f"bench.py: GEMV with 512-symbol segments disagrees with the 4096-symbol run ({dev_rel})", file=sys.stderr)
-            sys.exit(1)
-        s_stream = sum(e.stream.size for e in encs_s)
-        s_sym = sum(e.n for e in encs_s)
-        result["gemv_segments_512"] = {"us_per_layer": round(wsm * 1e3 / small_layers, 2), "layers": small_layers,
-                                        "launches_per_layer": len(groups),
-                                        "mean_code_len_bits_incl_offsets": round((s_stream * 8 + sum(e.offsets.size for e in encs_s) * 64) / s_sym, 4),
-                                        "effective_uint8_GBps": round(s_sym / (wsm * 1e-3) / 1e9, 2)}
-        log(f"gemv, 512-symbol segments: {result['gemv_segments_512']['us_per_layer']} us/layer")
 
     # ------------------------------------------------ the headline set again with length-limited codebooks
     if not args.no_extras:
@@ -397,7 +424,8 @@ def main():
                                       (2, "configs[1]: smolLM-1.7B-shaped, 24 layers + norm gains -> u8", E.ENTRO_U8),
                                       (3, "configs[2]: phi3-mini-shaped, 32 layers, 4-bit -> packed u4", E.ENTRO_U4_PACKED)):
             log(f"preparing and timing {label}")
-            enc_c = prepare_config(cfg)
+            sub_c = args.sub_symbols * (2 if cfg == 3 else 1)        # segments of 8192 symbols hold at most 16 pieces
+            enc_c = prepare_config(cfg, sub_symbols=sub_c)
             dts_c = [E.to_device(e, dev) for e in enc_c]
             packed = dtype_out == E.ENTRO_U4_PACKED
             sizes = [(e.n + 1) // 2 if packed else e.n for e in enc_c]
@@ -411,36 +439,26 @@ def main():
             ws_c = torch.zeros(E.entro_workspace_bytes(ts_c, E.ENTRO_OP_DECODE), dtype=torch.uint8, device=dev)
             plan_c = E.entro_plan_init(ts_c, E.ENTRO_OP_DECODE, dtype_out, ws_c)
             wc, kc = timed(lambda: E.entro_plan_run(plan_c), args.steps, args.warmup)
-            # sampled segments against the oracle (config 1: the whole tensor)
-            rngc = np.random.default_rng(cfg)
-            n_checks = 0
-            for _ in range(12):
-                i = int(rngc.integers(0, len(enc_c)))
-                e = enc_c[i]
-                k = int(rngc.integers(0, e.offsets.size - 1))
-                lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
-                q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
-                                         out=np.zeros(e.n, np.uint8))[lo:hi]
-                if packed:
-                    ref = oracle.pack_u4(q)
-                    got = v_c[i][lo // 2:(hi + 1) // 2].cpu().numpy()
-                else:
-                    ref, got = q, v_c[i][lo:hi].cpu().numpy()
-                if not np.array_equal(got, ref):
-                    print(f"bench.py: GPU output differs from the oracle in {label}, tensor {e.name} segment {k}", file=sys.stderr)
-                    sys.exit(1)
-                n_checks += 1
+            # whole tensors of every kind and sampled segments of the rest against the oracle
+            idx_c = kinds_idx(enc_c)
+            if packed:
+                whole_c = check_whole(enc_c, idx_c, lambda i: v_c[i].cpu().numpy(), lambda e, q: oracle.pack_u4(q), label)
+                n_checks = check_segments(enc_c, 12, cfg, lambda i, lo, hi: v_c[i][lo // 2:(hi + 1) // 2].cpu().numpy(),
+                                          lambda e, q: oracle.pack_u4(q), label)
+            else:
+                whole_c = check_whole(enc_c, idx_c, lambda i: v_c[i].cpu().numpy(), lambda e, q: q, label)
+                n_checks = check_segments(enc_c, 12, cfg, lambda i, lo, hi: v_c[i][lo:hi].cpu().numpy(), lambda e, q: q, label)
             n_c = sum(e.n for e in enc_c)
             sb_c = sum(e.stream.size for e in enc_c)
             ob_c = sum(e.offsets.size * 8 for e in enc_c)
             bits_c = sum(e.total_bits for e in enc_c) / n_c
-            others[f"config{cfg}"] = {"workload": label, "symbols": n_c, "tensors": len(enc_c),
+            others[f"config{cfg}"] = {"workload": label, "symbols": n_c, "tensors": len(enc_c), "entry_points_every_symbols": sub_c,
                                       "mean_code_len_bits": round(bits_c, 4), "ms_per_step": round(wc, 4),
                                       "kernel_ms": round(kc, 4), "symbols_per_s": round(n_c / (wc * 1e-3), 0),
                                       "decoded_GBps": round(sum(sizes) / (wc * 1e-3) / 1e9, 2),
                                       "compressed_GBps": round(sb_c / (wc * 1e-3) / 1e9, 2),
                                       "hbm_frac": round((sb_c + ob_c + sum(sizes)) / (kc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                                      "verified_segments": n_checks}
+                                      "verified_whole_tensors": whole_c, "verified_segments": n_checks}
             log(f"config {cfg}: {wc:.3f} ms/step")
             if cfg == 3:
                 # the same 4-bit set dequantized to bf16 (what an inference engine asks for), sampled like the rest
@@ -453,24 +471,16 @@ def main():
                 ws_b = torch.zeros(E.entro_workspace_bytes(ts_b, E.ENTRO_OP_DEQUANT), dtype=torch.uint8, device=dev)
                 plan_b = E.entro_plan_init(ts_b, E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, ws_b)
                 wb, kb = timed(lambda: E.entro_plan_run(plan_b), args.steps, args.warmup)
-                for _ in range(12):
-                    i = int(rngc.integers(0, len(enc_c)))
-                    e = enc_c[i]
-                    k = int(rngc.integers(0, e.offsets.size - 1))
-                    lo, hi = k * e.chunk_symbols, min((k + 1) * e.chunk_symbols, e.n)
-                    q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1,
-                                             out=np.zeros(e.n, np.uint8))[lo:hi]
-                    ref = oracle.dequant_bf16(q, e.qp.scale, e.qp.zero_point)
-                    got = v_b[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
-                    if not np.array_equal(got, ref):
-                        print(f"bench.py: bf16 output differs from the oracle in {label}, tensor {e.name} segment {k}", file=sys.stderr)
-                        sys.exit(1)
+                whole_b = check_whole(enc_c, idx_c, lambda i: v_b[i].view(torch.int16).cpu().numpy().view(np.uint16), bf16_ref,
+                                      "configs[2] -> bf16")
+                check_segments(enc_c, 12, 33, lambda i, lo, hi: v_b[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16),
+                               bf16_ref, "configs[2] -> bf16")
                 others["config3_bf16"] = {"workload": "configs[2] tensors, entro_decode_dequant -> bf16", "symbols": n_c,
                                           "ms_per_step": round(wb, 4), "kernel_ms": round(kb, 4),
                                           "symbols_per_s": round(n_c / (wb * 1e-3), 0),
                                           "decoded_GBps": round(2 * n_c / (wb * 1e-3) / 1e9, 2),
                                           "hbm_frac": round((sb_c + ob_c + 2 * n_c) / (kb * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                                          "verified_segments": 12}
+                                          "verified_whole_tensors": whole_b, "verified_segments": 12}
                 log(f"config 3 -> bf16: {wb:.3f} ms/step")
                 del out_b, v_b, ts_b, plan_b, ws_b
                 # and multiplied into activation vectors (4-bit token generation; segments of 8192 symbols
@@ -486,6 +496,7 @@ def main():
                 ws_g = torch.zeros(max(256, E.entro_workspace_bytes(ts_g, E.ENTRO_OP_GEMV)), dtype=torch.uint8, device=dev)
                 plan_g = E.entro_plan_init(ts_g, E.ENTRO_OP_GEMV, E.ENTRO_F32, ws_g)
                 wg3, kg3 = timed(lambda: E.entro_plan_run(plan_g), args.steps, args.warmup)
+                rngc = np.random.default_rng(cfg)
                 for _ in range(8):
                     i = int(rngc.integers(0, len(enc_c)))
                     e = enc_c[i]

@@ -128,7 +128,7 @@ typedef struct {
     uint32_t count;       /* tensors */
     uint32_t n_items;     /* work items in the launch */
     uint32_t n_fix;       /* GEMV: rows that need the second-stage sum */
-    uint32_t item_units;  /* units (64 segments of one tensor) per work item */
+    uint32_t item_units;  /* units (the segments or pieces of one tensor that the 64 lanes of a wavefront take) per work item */
     uint32_t pair_tables; /* 1: every tensor holds 4-bit symbols, the kernels decode two per table lookup */
     uint32_t gemv_multirow; /* 1: a tensor's segments are longer than its matrix rows (information only) */
     uint32_t wide_tables; /* 1: GEMV over 8-bit tensors with zero-points in [-1, 256]: table entries hold the centred value */
@@ -347,22 +347,6 @@ entro_status entro_encode_device(const uint8_t *q, uint64_t n, const entro_codeb
  * ENTRO_ERR_SYMBOL (a symbol without a code), ENTRO_ERR_CAPACITY (stream_cap too
  * small), ENTRO_ERR_SIZE (the stream would reach 4 GiB). */
 entro_status entro_encode_device_status(uint32_t status_word);
-
-/* Calibration for the roofline figures, not part of the path: one kernel that reads
- * read_bytes from src and writes write_bytes to dst (device pointers, 16-byte
- * aligned, sizes multiples of 16), perfectly coalesced, reads and writes interleaved
- * in the ratio of the two sizes.  Timed by the caller, it gives the rate at which
- * this GPU's memory takes a plain stream with a decode launch's read/write mix.
- * scratch4: four bytes of device memory the kernel may write. */
-entro_status entro_stream_probe(const void *src, uint64_t read_bytes, void *dst, uint64_t write_bytes, void *scratch4,
-                                void *hip_stream);
-
-/* Comparison for the GEMV figures, not part of the path: y = s * W x on weights stored as plain bytes
- * (q: device, rows * cols symbols one per byte, row-major; cols a multiple of 16; x: device, bf16[cols];
- * y: device, float[rows]; all 16-byte aligned), the uint8 model that the paper's Table 3 compares the
- * entropy-coded one with.  Bound by reading rows * cols bytes. */
-entro_status entro_gemv_u8_plain(const uint8_t *q, uint32_t rows, uint32_t cols, const entro_qparams *qp, const void *x, float *y,
-                                 void *hip_stream);
 
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char *entro_last_device_error(void);

@@ -15,7 +15,7 @@ from .binding import (  # noqa: F401
     entro_decode, entro_decode_dequant, entro_decode_gemv, entro_decode_gemv_static, entro_gemv_workspace_bytes,
     entro_workspace_bytes, entro_plan_init, entro_plan_staging_bytes, entro_plan_init_staged, entro_plan_run,
     entro_decode_batch, entro_decode_dequant_batch, entro_decode_gemv_batch,
-    entro_last_device_error, entro_stream_probe, entro_gemv_u8_plain, encode_tensor, to_device,
+    entro_last_device_error, encode_tensor, to_device,
     entro_range_device, entro_qparams_from_range, entro_scheme_for_range, entro_quantize_device, entro_encoded_bytes,
     entro_encode_device, entro_encode_device_status, compress_on_device,
     ENTRO_UNSIGNED, ENTRO_ASYMMETRIC, ENTRO_U8, ENTRO_U4_PACKED, ENTRO_F32, ENTRO_BF16,

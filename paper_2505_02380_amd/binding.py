@@ -106,8 +106,6 @@ def lib():
         "entro_decode_dequant_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_decode_gemv_batch": (C.c_int, [tp, C.c_uint32, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
         "entro_last_device_error": (C.c_char_p, []),
-        "entro_stream_probe": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
-        "entro_gemv_u8_plain": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(QParams), C.c_void_p, C.c_void_p, C.c_void_p]),
         "entro_range_device": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
         "entro_qparams_from_range": (C.c_int, [C.c_float, C.c_float, C.c_uint32, C.c_int, C.c_int, C.POINTER(QParams)]),
         "entro_scheme_for_range": (C.c_int, [C.c_float, C.c_float]),
@@ -131,7 +129,7 @@ EXPORTED = ["entro_quantize", "entro_build_codebook", "entro_codebook_from_count
             "entro_decode", "entro_decode_dequant", "entro_gemv_workspace_bytes", "entro_decode_gemv", "entro_decode_gemv_static",
             "entro_workspace_bytes", "entro_plan_init", "entro_plan_staging_bytes", "entro_plan_init_staged", "entro_plan_run", "entro_decode_batch",
             "entro_decode_dequant_batch", "entro_decode_gemv_batch", "entro_last_device_error",
-            "entro_stream_probe", "entro_gemv_u8_plain", "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
+            "entro_range_device", "entro_qparams_from_range", "entro_scheme_for_range", "entro_quantize_device",
             "entro_encoded_bytes", "entro_encode_device", "entro_encode_device_status"]
 
 
@@ -299,7 +297,9 @@ class DeviceTensor:
         self.x = None
         self.out = None
 
-    def ctensor(self, out, x=None) -> CTensor:
+    def ctensor(self, out, x=None, entry_points: bool = True) -> CTensor:
+        """The tensor as the device entry points take it; entry_points=False leaves the entry points inside
+        the segments out (every lane then takes a whole segment)."""
         e = self.enc
         t = CTensor()
         t.stream = self.stream.data_ptr()
@@ -307,8 +307,8 @@ class DeviceTensor:
         t.offsets = self.offsets.data_ptr()
         t.n = e.n
         t.chunk_symbols = e.chunk_symbols
-        t.sub_symbols = e.sub_symbols
-        t.sub_bits = self.sub_bits.data_ptr() if self.sub_bits is not None else None
+        t.sub_symbols = e.sub_symbols if entry_points else 0
+        t.sub_bits = self.sub_bits.data_ptr() if (self.sub_bits is not None and entry_points) else None
         t.rows, t.cols = e.rows, e.cols
         t.cb = C.pointer(e.cb)
         t.qp = e.qp
@@ -397,18 +397,6 @@ def _batch(fn_name: str, ts, out_type, workspace, stream):
     fn = getattr(lib(), fn_name)
     _check(fn(arr, len(ts), out_type, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
               _stream_ptr(stream)), fn_name)
-
-
-def entro_stream_probe(src, read_bytes: int, dst, write_bytes: int, scratch, stream=None):
-    """Calibration kernel: read read_bytes of src, write write_bytes of dst (torch device tensors)."""
-    _check(lib().entro_stream_probe(src.data_ptr(), int(read_bytes), dst.data_ptr(), int(write_bytes), scratch.data_ptr(),
-                                    _stream_ptr(stream)), "entro_stream_probe")
-
-
-def entro_gemv_u8_plain(q, rows: int, cols: int, qp: QParams, x, y, stream=None):
-    """Comparison kernel: y = s * (q - z) x on plain uint8 weights (torch device tensors)."""
-    _check(lib().entro_gemv_u8_plain(q.data_ptr(), rows, cols, C.byref(qp), x.data_ptr(), y.data_ptr(), _stream_ptr(stream)),
-           "entro_gemv_u8_plain")
 
 
 # ------------------------------------------------------- device-side compression

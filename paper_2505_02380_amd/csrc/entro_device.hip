@@ -48,6 +48,7 @@ constexpr int kL2MaxPrefixes = 32;       // more long prefixes than this: second
 constexpr int kSingleBits = 9;             // pair tables: index bits of the table of single codes
 constexpr uint32_t kUnit = 64;           // segments a wavefront decodes at a time: one per lane
 constexpr int kGroup = 4;                // symbols per ring read: 63 valid bits >= 4 * 14
+constexpr uint32_t kTailShift = 4;       // a stretch's last round is drawn with lanes up to 2^this times finer
 constexpr int kTripGroups = 4;           // ring reads between two checks of the ring's fill
 constexpr int kScalarProbes = 2;         // scalar reader: symbols per 64-bit load, 33 valid bits >= 2 * kL1
 constexpr int kRingBits = 1024;          // a lane's ring: two 64-byte lines (eight 16-byte blocks)
@@ -81,6 +82,8 @@ struct DevTensor {
     int32_t zero_point;
     uint32_t max_len;
     uint32_t need_fix;
+    uint32_t fine;              // batched launches: index of the same tensor's description with finer lanes (0: none)
+    uint32_t fine_shift;        // log2 of how many of those lanes make one of this description's
     uint8_t len[256];
 };
 
@@ -1573,6 +1576,21 @@ __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors
         const uint32_t left_in_tensor = (t.n_chunks - it.first + kUnit - 1) / kUnit;
         const uint64_t share = static_cast<uint64_t>(hi - i) * item_units;
         const uint32_t n_units = left_in_tensor < share ? left_in_tensor : static_cast<uint32_t>(share);
+        // The units beyond the stretch's last whole round (a unit per wavefront), where the tensor is described
+        // a second time with finer lanes (t.fine): they are drawn as 2^fine_shift times as many short ones, so
+        // that the wavefronts run out of work at nearly the same time instead of most of them idling for the
+        // length of a whole segment.
+        const DevTensor *tf = &t;
+        uint32_t n_coarse = n_units, n_all = n_units, fine_first = 0;
+        if (t.fine) {
+            tf = &tensors[t.fine];
+            const uint32_t refined = n_units % static_cast<uint32_t>(Cfg<MODE>::waves);   // what does not fill a round
+            n_coarse = n_units - refined;
+            fine_first = (it.first + n_coarse * kUnit) << t.fine_shift;
+            uint64_t fine_end = static_cast<uint64_t>(it.first + n_units * kUnit) << t.fine_shift;
+            if (fine_end > tf->n_chunks) fine_end = tf->n_chunks;
+            n_all = n_coarse + static_cast<uint32_t>((fine_end - fine_first + kUnit - 1) / kUnit);
+        }
         __syncthreads();                                     // nobody reads the previous tables or the counter any more
         build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
         if (rows_fit<MODE>(t)) {
@@ -1582,11 +1600,14 @@ __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors
                 uint32_t u = 0;
                 if ((threadIdx.x & 63u) == 0) u = atomicAdd(&next_unit, 1u);
                 u = __builtin_amdgcn_readfirstlane(u);
-                if (u >= n_units) break;
-                if constexpr (wide_gemv(MODE)) gemv_direct2<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
-                else if constexpr (is_gemv(MODE)) gemv_direct<MODE>(t, sm.tb, sm.wm[threadIdx.x >> 6].ring, it.first + u * kUnit);
-                else if constexpr (short_ring(MODE)) decode_rows2<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
-                else decode_rows<MODE>(t, sm.tb, sm.wm, it.first + u * kUnit);
+                if (u >= n_all) break;
+                const bool fine = u >= n_coarse;
+                const DevTensor &d = fine ? *tf : t;
+                const uint32_t first = fine ? fine_first + (u - n_coarse) * kUnit : it.first + u * kUnit;
+                if constexpr (wide_gemv(MODE)) gemv_direct2<MODE>(d, sm.tb, sm.wm[threadIdx.x >> 6].ring, first);
+                else if constexpr (is_gemv(MODE)) gemv_direct<MODE>(d, sm.tb, sm.wm[threadIdx.x >> 6].ring, first);
+                else if constexpr (short_ring(MODE)) decode_rows2<MODE>(d, sm.tb, sm.wm, first);
+                else decode_rows<MODE>(d, sm.tb, sm.wm, first);
             }
         } else {
             const uint32_t end = it.first + n_units * kUnit;
@@ -1786,6 +1807,13 @@ unsigned wg_of(int mode) {
     return wg;
 }
 
+// Symbols per block of a mode's kernel: lanes must be whole blocks to go through its fast path.
+unsigned spb_of(int mode) {
+    unsigned spb = 64;
+    dispatch_mode(mode, [&](auto m) { spb = Cfg<decltype(m)::value>::spb; });
+    return spb;
+}
+
 // `pairs`: every tensor of the launch holds 4-bit symbols, so the tables can hold two codes per entry.
 // Does the GEMV of this tensor fit the wide tables?
 bool wide_ok(const DevTensor &dt) { return dt.bits == 8 && dt.zero_point >= -1 && dt.zero_point <= 256; }
@@ -1907,7 +1935,7 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
     L->n_items = static_cast<uint32_t>(items);
     L->n_fix = static_cast<uint32_t>(fix);
     L->off_tensors = 0;
-    L->off_items = align_up(sizeof(DevTensor) * static_cast<uint64_t>(count), 256);
+    L->off_items = align_up(sizeof(DevTensor) * 2 * static_cast<uint64_t>(count), 256);   // a tensor may be described at two lane sizes
     L->off_fix = L->off_items + align_up(sizeof(WorkItem) * items, 256);
     L->off_partials = L->off_fix + align_up(sizeof(WorkItem) * fix, 256);
     L->total = L->off_partials + align_up(sizeof(float) * partial_floats, 256);
@@ -1916,88 +1944,14 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
 
 }  // namespace
 
-// Calibration: read `rd` and write `wr` 16-byte blocks, perfectly coalesced (grid-stride), `ra` reads
-// then `wa` writes per round, so that the two streams advance in the ratio of their sizes.
-__global__ __launch_bounds__(1024) void k_stream_probe(const u32x4 *__restrict__ src, uint64_t rd, u32x4 *__restrict__ dst,
-                                                       uint64_t wr, uint32_t ra, uint32_t wa, uint32_t *sink) {
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-    uint64_t r = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x, w = r;
-    u32x4 acc = {1, 2, 3, 4};
-    while (r < rd || w < wr) {
-        for (uint32_t j = 0; j < ra && r < rd; ++j, r += stride) {
-            const u32x4 v = src[r];
-            acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
-        }
-        for (uint32_t j = 0; j < wa && w < wr; ++j, w += stride) __builtin_nontemporal_store(acc, dst + w);
-    }
-    if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u) *sink = acc.z;     // keeps the reads alive
-}
-
 // for the library's other device source: record a failed HIP call for entro_last_device_error
 void entro_detail_note_hip_error(const char *what, int hip_error) {
     hip_ok(static_cast<hipError_t>(hip_error), what);
 }
 
-// Comparison, not part of the path: the same product on weights that are stored as plain bytes.
-// One wavefront per matrix row, 16 weights per lane and load, the lanes' sums added by shuffles.
-__global__ __launch_bounds__(256) void k_gemv_u8_plain(const uint8_t *__restrict__ q, uint32_t rows, uint32_t cols, float scale,
-                                                       float zf, const uint16_t *__restrict__ x, float *__restrict__ y) {
-    const uint32_t lane = threadIdx.x & 63u;
-    for (uint32_t r = blockIdx.x * 4u + (threadIdx.x >> 6); r < rows; r += gridDim.x * 4u) {
-        const uint8_t *row = q + static_cast<uint64_t>(r) * cols;
-        float acc = 0.0f;
-#pragma unroll 4
-        for (uint32_t c = lane * 16u; c < cols; c += 1024u) {
-            const u32x4 w = *(global_u4_ptr)(row + c);
-            const u32x4 xa = *(global_u4_ptr)(x + c), xb = *(global_u4_ptr)(x + c + 8u);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4 xv = j < 2 ? xa : xb;
-                const uint32_t x01 = (j & 1) ? xv.z : xv.x, x23 = (j & 1) ? xv.w : xv.y;
-                acc = fmaf(static_cast<float>(w[j] & 0xffu) - zf, __uint_as_float(x01 << 16), acc);
-                acc = fmaf(static_cast<float>((w[j] >> 8) & 0xffu) - zf, __uint_as_float(x01 & 0xffff0000u), acc);
-                acc = fmaf(static_cast<float>((w[j] >> 16) & 0xffu) - zf, __uint_as_float(x23 << 16), acc);
-                acc = fmaf(static_cast<float>(w[j] >> 24) - zf, __uint_as_float(x23 & 0xffff0000u), acc);
-            }
-        }
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) acc += __shfl_xor(acc, m, 64);
-        if (lane == 0) y[r] = acc * scale;
-    }
-}
-
 extern "C" {
 
 const char *entro_last_device_error(void) { return g_last_error.c_str(); }
-
-entro_status entro_gemv_u8_plain(const uint8_t *q, uint32_t rows, uint32_t cols, const entro_qparams *qp, const void *x, float *y,
-                                 void *hip_stream) {
-    if (!q || !qp || !x || !y) return ENTRO_ERR_NULL;
-    if (rows == 0 || cols == 0 || (cols & 15u)) return ENTRO_ERR_SIZE;
-    if (!aligned16(q) || !aligned16(x) || !aligned16(y)) return ENTRO_ERR_ALIGN;
-    if (qp->zero_point > (1 << 24) || qp->zero_point < -(1 << 24)) return ENTRO_ERR_RANGE;
-    const unsigned grid = std::min<unsigned>((rows + 3u) / 4u, 256u * 8u);
-    hipLaunchKernelGGL(k_gemv_u8_plain, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream), q, rows, cols,
-                       qp->scale, static_cast<float>(qp->zero_point), static_cast<const uint16_t *>(x), y);
-    if (!hip_ok(hipGetLastError(), "launch plain GEMV")) return ENTRO_ERR_DEVICE;
-    return ENTRO_OK;
-}
-
-entro_status entro_stream_probe(const void *src, uint64_t read_bytes, void *dst, uint64_t write_bytes, void *scratch4,
-                                void *hip_stream) {
-    if (!src || !dst || !scratch4) return ENTRO_ERR_NULL;
-    if (!aligned16(src) || !aligned16(dst) || (read_bytes & 15u) || (write_bytes & 15u) || !read_bytes || !write_bytes)
-        return ENTRO_ERR_ALIGN;
-    const uint64_t rd = read_bytes / 16, wr = write_bytes / 16, mx = std::max(rd, wr);
-    const uint32_t ra = static_cast<uint32_t>(std::max<uint64_t>(1, (8 * rd + mx / 2) / mx));
-    const uint32_t wa = static_cast<uint32_t>(std::max<uint64_t>(1, (8 * wr + mx / 2) / mx));
-    // many small workgroups: the launch shape that streams fastest on this chip among those tried
-    hipLaunchKernelGGL(k_stream_probe, dim3(65536), dim3(1024), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const u32x4 *>(src), rd, static_cast<u32x4 *>(dst), wr, ra, wa,
-                       static_cast<uint32_t *>(scratch4));
-    if (!hip_ok(hipGetLastError(), "launch stream probe")) return ENTRO_ERR_DEVICE;
-    return ENTRO_OK;
-}
 
 entro_status entro_decode(const entro_tensor *t, entro_dtype out_type, void *hip_stream) {
     return launch_single(t, ENTRO_OP_DECODE, out_type, nullptr, hip_stream);
@@ -2080,13 +2034,34 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
         }
     }
     // A work item is what a workgroup takes in one round when the launch is large (a unit per
-    // wavefront), and less when the launch would not give every compute unit an item otherwise.
+    // wavefront: stretches of whole items end for all wavefronts together), and less when the launch
+    // would not give every compute unit an item otherwise.
     const int mode = mode0;
     const unsigned slots = slots0;
     const uint64_t waves = wg_of(mode) / 64u;
-    const uint32_t item_units = static_cast<uint32_t>(std::min<uint64_t>(waves, std::max<uint64_t>(1, total_units / slots)));
+    uint32_t item_units = static_cast<uint32_t>(std::min<uint64_t>(waves, std::max<uint64_t>(1, total_units / slots)));
+    // Tensors with entry points inside their segments are described a second time, with lanes up to
+    // 2^kTailShift times finer (as fine as still tiles into the kernel's blocks): the kernel draws what
+    // is left over behind the last whole round of a stretch from that description.  (Not for the GEMV: its partial sums are laid out per lane.)
+    uint32_t n_desc = count;
+    const uint32_t block = spb_of(mode);
+    for (uint32_t i = 0; i < count && op != ENTRO_OP_GEMV; ++i) {
+        uint32_t finer = std::min<uint32_t>(dts[i].sub_merge, kTailShift);
+        while (finer > 0 && ((dts[i].chunk_symbols >> finer) % block) != 0) --finer;
+        if (finer == 0 || dts[i].chunk_symbols % block != 0) continue;
+        entro_status st = fill_dev_tensor(&ts[i], op, out_type, dts[i].sub_merge - finer, &dts[n_desc]);
+        if (st != ENTRO_OK) return st;
+        dts[i].fine = n_desc++;
+        dts[i].fine_shift = finer;
+    }
+    // where every tensor has that second description a stretch may end anywhere at little cost: the
+    // workgroups' shares are made equal to within one unit
+    if (n_desc == 2 * count) item_units = 1;
     for (uint32_t i = 0; i < count; ++i)
-        for (uint32_t c = 0; c < dts[i].n_chunks; c += item_units * kUnit) items[n_items++] = WorkItem{i, c};
+        for (uint64_t c = 0; c < dts[i].n_chunks; c += static_cast<uint64_t>(item_units) * kUnit) {
+            if (n_items >= L.n_items) return ENTRO_ERR_SIZE;     // (the layout counts the same units: cannot happen)
+            items[n_items++] = WorkItem{i, static_cast<uint32_t>(c)};
+        }
     plan->workspace = workspace;
     plan->workspace_bytes = workspace_bytes;
     plan->op = op;

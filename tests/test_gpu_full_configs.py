@@ -34,7 +34,9 @@ def _say(msg):
 @lru_cache(maxsize=2)
 def _prepared(cfg):
     _say(f"preparing workload {cfg}")
-    encs = prepare_config(cfg)
+    # with entry points inside the segments (every 256 symbols; 512 in the segments of 8192), as bench.py
+    # prepares them: batched launches draw what is left over behind a stretch's whole rounds from those
+    encs = prepare_config(cfg, sub_symbols=512 if cfg == 3 else 256)
     return encs, [E.to_device(e, DEV) for e in encs]
 
 
@@ -107,6 +109,12 @@ def test_config2_smollm_shaped_u8_every_element():
     _compare_all(views, [lambda a=a: a for a in q], "config 2 -> u8", lambda v: v.cpu().numpy(), np.array_equal)
     _check_guards(buf, starts, sizes)
     _say("config 2: every element matches")
+    # and as the same launch without the entry points (every lane a whole segment)
+    buf.fill_(GUARD_BYTE)
+    _run_plan([d.ctensor(v, entry_points=False) for d, v in zip(dts, views)], E.ENTRO_OP_DECODE, E.ENTRO_U8)
+    _compare_all(views, [lambda a=a: a for a in q], "config 2 -> u8, whole segments", lambda v: v.cpu().numpy(), np.array_equal)
+    _check_guards(buf, starts, sizes)
+    _say("config 2 without entry points: every element matches")
 
 
 def test_config3_phi3_shaped_packed_u4_and_bf16_every_element():

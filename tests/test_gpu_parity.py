@@ -425,6 +425,49 @@ def test_large_launch_merges_pieces_into_coarser_lanes():
     assert _bf16_ulp_diff(_gpu_dequant(enc, E.ENTRO_BF16, False), oracle.dequant_bf16(sym, enc.qp.scale, enc.qp.zero_point)).max() <= 1
 
 
+def test_last_round_of_every_stretch_is_drawn_with_finer_lanes_every_output():
+    """A launch of several rounds per workgroup over tensors with entry points inside their segments: the last
+    round of every stretch is decoded by lanes that take pieces instead of segments (and as before for the
+    tensor that has no entry points); every output element, guard bytes between the outputs."""
+    rng = np.random.default_rng(61)
+    chunk = 256
+    shapes = [(2500, 64), (1125, 64), (2125, 128), (37, 0), (750, 32)]     # (units of 64 segments, entry-point spacing)
+    encs, refs = [], []
+    for i, (units, sub) in enumerate(shapes):
+        n = units * 64 * chunk - (0 if i != 2 else 21 * chunk + 5)          # tensor 2 ends inside a segment
+        sym = np.minimum(rng.geometric(0.12 + 0.05 * i, n) - 1, 255).astype(np.uint8)
+        encs.append(_oracle_encoded(sym, 8, chunk, s=np.float32(0.01), z=2 + i, sub=sub))
+        refs.append(sym)
+    dts = [E.to_device(e, DEV) for e in encs]
+    for op, out_type, dtype, width in ((E.ENTRO_OP_DECODE, E.ENTRO_U8, torch.uint8, 1),
+                                       (E.ENTRO_OP_DEQUANT, E.ENTRO_BF16, torch.bfloat16, 2),
+                                       (E.ENTRO_OP_DEQUANT, E.ENTRO_F32, torch.float32, 4)):
+        guard = 64 // width
+        sizes = [(e.n + guard - 1) // guard * guard + guard for e in encs]   # every output 64-byte aligned, a guard behind it
+        buf = torch.full((sum(sizes),), 7, dtype=dtype, device=DEV)
+        outs, pos = [], 0
+        for e, sz in zip(encs, sizes):
+            outs.append(buf[pos:pos + e.n])
+            pos += sz
+        ts = [d.ctensor(o) for d, o in zip(dts, outs)]
+        ws = torch.zeros(E.entro_workspace_bytes(ts, op), dtype=torch.uint8, device=DEV)
+        plan = E.entro_plan_init(ts, op, out_type, ws)
+        E.entro_plan_run(plan)
+        torch.cuda.synchronize()
+        pos = 0
+        for e, r, o, sz in zip(encs, refs, outs, sizes):
+            if dtype == torch.uint8:
+                assert np.array_equal(o.cpu().numpy(), r)
+            elif dtype == torch.bfloat16:
+                assert np.array_equal(o.view(torch.int16).cpu().numpy().view(np.uint16),
+                                      oracle.dequant_bf16(r, e.qp.scale, e.qp.zero_point))
+            else:
+                assert np.array_equal(o.view(torch.int32).cpu().numpy().view(np.uint32),
+                                      oracle.dequant_f32(r, e.qp.scale, e.qp.zero_point).view(np.uint32))
+            assert bool((buf[pos + e.n:pos + sz] == 7).all()), "a guard element was written"
+            pos += sz
+
+
 def test_staged_plan_init_does_not_block_and_batch_calls_return_before_their_kernel_ends():
     from paper_2505_02380_amd.workload import prepare_config
     encs = prepare_config(4, layers=8)
@@ -672,14 +715,22 @@ def test_prepared_launches_replay_in_a_hip_graph():
 
 
 def test_plain_uint8_gemv_comparison_kernel_matches_the_oracle():
-    for rows, cols in [(300, 4096), (7, 14336), (1000, 64), (33, 1040)]:
+    """bench.py's comparison kernel (its own shared object, not the library): all products in one launch."""
+    import bench_kernels
+    shapes = [(300, 4096), (7, 14336), (1000, 64), (33, 1040), (1, 16)]
+    products, refs = [], []
+    for rows, cols in shapes:
         rng = np.random.default_rng(rows)
         q = np.minimum(rng.geometric(0.05, rows * cols) - 1, 255).astype(np.uint8)
         xb = synth.make_x_bf16(2, rows % 5, cols)
         y_ref, _ = oracle.gemv(q, rows, cols, np.float32(0.013), 21, xb)
         y = torch.full((rows + 4,), 9.0, dtype=torch.float32, device=DEV)
-        E.entro_gemv_u8_plain(torch.from_numpy(q).to(DEV), rows, cols, B.QParams(np.float32(0.013), 21, 8, 1),
-                              torch.from_numpy(xb.view(np.int16)).to(DEV).view(torch.bfloat16), y)
+        products.append((torch.from_numpy(q).to(DEV), rows, cols, np.float32(0.013), 21,
+                         torch.from_numpy(xb.view(np.int16)).to(DEV).view(torch.bfloat16), y))
+        refs.append(y_ref)
+    bench_kernels.PlainGemv(products, DEV).run()
+    torch.cuda.synchronize()
+    for (q, rows, cols, s, z, x, y), y_ref in zip(products, refs):
         got = y.cpu().numpy()
         assert np.all(got[rows:] == 9.0)
         _assert_gemv_close(got[:rows].astype(np.float64), y_ref)
