@@ -26,7 +26,7 @@ typedef struct bench_gemv_item {
     float *y;            /* float[rows] */
     uint32_t rows, cols; /* cols a multiple of 16 */
     float scale, zero_point;
-    uint32_t first_task; /* tasks (pairs of rows) of the items before this one */
+    uint32_t first_task; /* tasks (four rows each) of the items before this one */
     uint32_t reserved;
 } bench_gemv_item;
 

@@ -26,22 +26,23 @@ __global__ __launch_bounds__(1024) void k_stream_probe(const u32x4 *__restrict__
     if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u) *sink = acc.z;     // keeps the reads alive
 }
 
-// sixteen weights of one row times sixteen activations (bf16 pairs in xa, xb)
-__device__ __forceinline__ float dot16(const u32x4 w, const u32x4 xa, const u32x4 xb, float zf, float acc) {
+// Sixteen weights of one row (as they are stored, zero-point not yet taken off) times sixteen activations.
+__device__ __forceinline__ float dot16(const u32x4 w, const float (&xf)[16], float acc) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const u32x4 xv = j < 2 ? xa : xb;
-        const uint32_t x01 = (j & 1) ? xv.z : xv.x, x23 = (j & 1) ? xv.w : xv.y;
-        acc = fmaf(static_cast<float>(w[j] & 0xffu) - zf, __uint_as_float(x01 << 16), acc);
-        acc = fmaf(static_cast<float>((w[j] >> 8) & 0xffu) - zf, __uint_as_float(x01 & 0xffff0000u), acc);
-        acc = fmaf(static_cast<float>((w[j] >> 16) & 0xffu) - zf, __uint_as_float(x23 << 16), acc);
-        acc = fmaf(static_cast<float>(w[j] >> 24) - zf, __uint_as_float(x23 & 0xffff0000u), acc);
+        acc = fmaf(static_cast<float>(w[j] & 0xffu), xf[4 * j], acc);
+        acc = fmaf(static_cast<float>((w[j] >> 8) & 0xffu), xf[4 * j + 1], acc);
+        acc = fmaf(static_cast<float>((w[j] >> 16) & 0xffu), xf[4 * j + 2], acc);
+        acc = fmaf(static_cast<float>(w[j] >> 24), xf[4 * j + 3], acc);
     }
     return acc;
 }
 
-// One wavefront per task (two matrix rows), 16 weights per lane, row and load; the lanes' sums are added
-// by shuffles.  Wavefronts stride over the tasks of all matrices, so one launch keeps the whole chip reading.
+constexpr uint32_t kRowsPerTask = 4;
+
+// One wavefront per task (four matrix rows), 16 weights per lane, row and load; sum(Q x) and sum(x) are
+// kept apart, y = s * (sum(Q x) - z * sum(x)), and the lanes' sums are added by shuffles.  Wavefronts
+// stride over the tasks of all matrices, so one launch keeps the whole chip reading.
 __global__ __launch_bounds__(256) void k_gemv_u8_plain(const bench_gemv_item *__restrict__ items, uint32_t count, uint32_t total_tasks) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t waves = gridDim.x * 4u;
@@ -53,28 +54,42 @@ __global__ __launch_bounds__(256) void k_gemv_u8_plain(const bench_gemv_item *__
             if (items[mid].first_task <= task) lo = mid; else hi = mid;
         }
         const bench_gemv_item it = items[lo];
-        const uint32_t r0 = 2u * (task - it.first_task);
-        const bool two = r0 + 1u < it.rows;
-        const uint8_t *row0 = it.q + static_cast<uint64_t>(r0) * it.cols;
-        const uint8_t *row1 = two ? row0 + it.cols : row0;
+        const uint32_t r0 = kRowsPerTask * (task - it.first_task);
+        const uint8_t *row[kRowsPerTask];
+#pragma unroll
+        for (uint32_t r = 0; r < kRowsPerTask; ++r)         // rows behind the last one read it again; nothing of them is stored
+            row[r] = it.q + static_cast<uint64_t>(r0 + r < it.rows ? r0 + r : it.rows - 1u) * it.cols;
         const uint16_t *x = static_cast<const uint16_t *>(it.x);
-        float a0 = 0.0f, a1 = 0.0f;
+        float acc[kRowsPerTask] = {0.0f, 0.0f, 0.0f, 0.0f}, xsum = 0.0f;
 #pragma unroll 2
         for (uint32_t c = lane * 16u; c < it.cols; c += 1024u) {
-            const u32x4 w0 = __builtin_nontemporal_load((global_u4_ptr)(row0 + c));
-            const u32x4 w1 = __builtin_nontemporal_load((global_u4_ptr)(row1 + c));
+            u32x4 w[kRowsPerTask];
+#pragma unroll
+            for (uint32_t r = 0; r < kRowsPerTask; ++r) w[r] = __builtin_nontemporal_load((global_u4_ptr)(row[r] + c));
             const u32x4 xa = *(global_u4_ptr)(x + c), xb = *(global_u4_ptr)(x + c + 8u);
-            a0 = dot16(w0, xa, xb, it.zero_point, a0);
-            a1 = dot16(w1, xa, xb, it.zero_point, a1);
+            float xf[16];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                xf[2 * j] = __uint_as_float(xa[j] << 16);
+                xf[2 * j + 1] = __uint_as_float(xa[j] & 0xffff0000u);
+                xf[8 + 2 * j] = __uint_as_float(xb[j] << 16);
+                xf[8 + 2 * j + 1] = __uint_as_float(xb[j] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) xsum += xf[j];
+#pragma unroll
+            for (uint32_t r = 0; r < kRowsPerTask; ++r) acc[r] = dot16(w[r], xf, acc[r]);
         }
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) {
-            a0 += __shfl_xor(a0, m, 64);
-            a1 += __shfl_xor(a1, m, 64);
+            xsum += __shfl_xor(xsum, m, 64);
+#pragma unroll
+            for (uint32_t r = 0; r < kRowsPerTask; ++r) acc[r] += __shfl_xor(acc[r], m, 64);
         }
         if (lane == 0) {
-            it.y[r0] = a0 * it.scale;
-            if (two) it.y[r0 + 1u] = a1 * it.scale;
+#pragma unroll
+            for (uint32_t r = 0; r < kRowsPerTask; ++r)
+                if (r0 + r < it.rows) it.y[r0 + r] = (acc[r] - it.zero_point * xsum) * it.scale;
         }
     }
 }
@@ -85,7 +100,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 extern "C" {
 
-uint32_t bench_gemv_tasks(uint32_t rows) { return (rows + 1u) / 2u; }
+uint32_t bench_gemv_tasks(uint32_t rows) { return (rows + kRowsPerTask - 1u) / kRowsPerTask; }
 
 int bench_gemv_u8_plain(const bench_gemv_item *items, uint32_t count, uint32_t total_tasks, void *hip_stream) {
     if (!items || count == 0 || total_tasks == 0) return 1;

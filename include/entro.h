@@ -152,11 +152,11 @@ entro_status entro_quantize(const float *w, uint64_t n, int bits, entro_scheme s
  * q: host, n symbols one per byte, each < 2^bits.  A lone symbol gets a 1-bit code. */
 entro_status entro_build_codebook(const uint8_t *q, uint64_t n, int bits, entro_codebook *cb);
 
-/* Same, from a ready histogram of 2^bits counts. */
+/* The same ("Huffman weight encoding"), from a ready histogram of 2^bits counts. */
 entro_status entro_codebook_from_counts(const uint64_t *counts, int bits, entro_codebook *cb);
 
-/* Length-limited variants (an extension towards the hardware-aware coding the
- * paper's conclusions name as future work): the cheapest prefix code none of
+/* Length-limited variants of "Huffman weight encoding" (an extension towards the
+ * hardware-aware coding the paper's conclusions name as future work): the cheapest prefix code none of
  * whose codes is longer than max_len bits (package-merge), so that a decoder's
  * single-level table of max_len index bits holds every code and the slow path for
  * long codes never runs.  1 <= max_len <= ENTRO_MAX_CODE_LEN; the alphabet must
@@ -167,17 +167,22 @@ entro_status entro_codebook_from_counts(const uint64_t *counts, int bits, entro_
 entro_status entro_codebook_from_counts_limited(const uint64_t *counts, int bits, int max_len, entro_codebook *cb);
 entro_status entro_build_codebook_limited(const uint8_t *q, uint64_t n, int bits, int max_len, entro_codebook *cb);
 
-/* Canonical code values for given lengths (0 = absent).  Rejects lengths above
- * ENTRO_MAX_CODE_LEN and length sets whose Kraft sum exceeds 1. */
+/* Canonical code values for given lengths (0 = absent): the codebook of "Huffman
+ * weight encoding" as it is stored with a model, the lengths alone.  Rejects lengths
+ * above ENTRO_MAX_CODE_LEN and length sets whose Kraft sum exceeds 1. */
 entro_status entro_codebook_from_lengths(const uint8_t *len, int bits, entro_codebook *cb);
 
-/* ceil(n / chunk_symbols); 0 if chunk_symbols == 0. */
+/* Number of segments of "Segmentation for parallel Huffman decoding" (Fig. 3):
+ * ceil(n / chunk_symbols); 0 if chunk_symbols == 0. */
 uint64_t entro_num_chunks(uint64_t n, uint32_t chunk_symbols);
 
-/* Upper bound in bytes (padding included) of the stream entro_encode writes; 0 on bad arguments. */
+/* Upper bound in bytes (padding included) of the stream entro_encode writes ("Huffman
+ * weight encoding": no symbol takes more than the longest code); 0 on bad arguments. */
 uint64_t entro_encode_bound(uint64_t n, const entro_codebook *cb);
 
-/* Encode q (host, n symbols) into stream (host, stream_cap bytes) and fill
+/* "Huffman weight encoding" into the independently decodable segments of
+ * "Segmentation for parallel Huffman decoding" (Fig. 3): encode q (host, n symbols)
+ * into stream (host, stream_cap bytes) and fill
  * offsets (host, entro_num_chunks + 1 entries).  *stream_bytes receives the
  * padded size.  ENTRO_ERR_SYMBOL if a symbol has no code, ENTRO_ERR_CAPACITY
  * if stream_cap is too small (nothing useful is written then). */
@@ -200,7 +205,7 @@ entro_status entro_encode(const uint8_t *q, uint64_t n, const entro_codebook *cb
 entro_status entro_sub_index(const uint8_t *q, uint64_t n, const entro_codebook *cb, uint32_t chunk_symbols,
                              uint32_t sub_symbols, uint16_t *sub_bits);
 
-/* Consistency check of a host copy of an offset table against a stream size:
+/* Consistency check of a host copy of the offset table of Fig. 3's segments against a stream size:
  * offsets[0] == 0, non-decreasing, each segment no longer than
  * chunk_symbols * max_len bits and no shorter than its symbol count times the
  * shortest code, last offset within stream_bytes minus the 16 trailing pad
@@ -214,26 +219,31 @@ entro_status entro_check_offsets(const uint64_t *offsets, uint64_t n, uint32_t c
 double entro_bits_saved(int bits, double mean_code_len);
 double entro_theoretical_speedup(int bits, double mean_code_len);
 
+/* Text for a status code (error reporting; no passage of the paper defines it). */
 const char *entro_status_string(entro_status s);
 
 /* ---------------------------------------------------------------- device side
  * One tensor per call, descriptor passed in kernel arguments (no workspace
  * needed except for the GEMV's second-stage sum). */
 
-/* Segment-parallel decode back to integers.  out_type: ENTRO_U8 (one symbol
+/* Segment-parallel decode back to integers ("Segmentation for parallel Huffman
+ * decoding", Fig. 3, lower half: every segment by a worker of its own).  out_type: ENTRO_U8 (one symbol
  * per byte) or ENTRO_U4_PACKED (4-bit codebooks only; symbol 2i in the low
  * nibble of byte i, 2i+1 in the high nibble, last high nibble zero if n is odd). */
 entro_status entro_decode(const entro_tensor *t, entro_dtype out_type, void *hip_stream);
 
-/* Decode fused with the inverse grid map w = (q - z) * s (integer difference,
+/* Decode (Fig. 3) fused with the inverse of Eq. 1's grid map, w = (q - z) * s (integer difference,
  * exact conversion, one binary32 multiply).  out_type: ENTRO_F32 (bit-exact)
  * or ENTRO_BF16 (the binary32 value rounded to nearest even). */
 entro_status entro_decode_dequant(const entro_tensor *t, entro_dtype out_type, void *hip_stream);
 
-/* Bytes of device workspace entro_decode_gemv needs for this tensor (may be 0). */
+/* Bytes of device workspace entro_decode_gemv ("Latency Reduction from Huffman Coding")
+ * needs for this tensor (may be 0). */
 uint64_t entro_gemv_workspace_bytes(const entro_tensor *t);
 
-/* y = W x for batch-1 token generation without materialising W:
+/* y = W x for batch-1 token generation without materialising W ("Latency Reduction from
+ * Huffman Coding", Table 3: the phase is bound by the weight bytes read, and the coded
+ * stream is fewer bytes):
  * y[r] = s * sum_j (q[r][j] - z) * x[j], fp32 accumulation, x bf16, W row-major.
  * y_type: ENTRO_F32 or ENTRO_BF16.  Rows that straddle segments are summed in
  * segment order by a second small kernel (deterministic). */
@@ -251,12 +261,13 @@ entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *
 #define ENTRO_STATIC_GEMV_MAX_SEGMENTS 65536
 entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type, void *hip_stream);
 
-/* Batched forms: ONE launch over `count` tensors (a single tensor has too few
- * segments to fill 256 compute units).  The descriptor table, the work list
+/* Batched forms: ONE launch over `count` tensors (a single tensor has too few of
+ * Fig. 3's segments to fill 256 compute units).  The descriptor table, the work list
  * and the GEMV partial sums live in `workspace` (device). */
 uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
 
-/* Validate, build the table on the host and copy it into the workspace.  BLOCKS until
+/* Prepare a batched launch of Fig. 3's segment-parallel decode (or of the fused forms above):
+ * validate, build the table on the host and copy it into the workspace.  BLOCKS until
  * the copy, and with it everything enqueued on hip_stream before, has completed (the
  * table is staged in memory that dies with the call); entro_plan_init_staged does not.
  * The tensors' device buffers are referenced, not copied.
@@ -269,7 +280,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
                              entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
                              void *hip_stream);
 
-/* The same without waiting: the table is built in `staging` (host memory of the caller's,
+/* The same (Fig. 3's decode, prepared for many tensors) without waiting: the table is built in `staging` (host memory of the caller's,
  * at least entro_plan_staging_bytes, pinned -- hipHostMalloc -- if the copy is to be
  * asynchronous) and copied from there on hip_stream.  The caller keeps `staging` alive
  * and unchanged until that copy has completed (a stream or event wait of its own).
@@ -279,10 +290,12 @@ entro_status entro_plan_init_staged(entro_plan *plan, const entro_tensor *ts, ui
                                     entro_dtype out_type, void *workspace, uint64_t workspace_bytes, void *staging,
                                     uint64_t staging_bytes, void *hip_stream);
 
-/* Enqueue the prepared launch; no host-side table work, no copies, no waiting. */
+/* Enqueue the prepared launch (Fig. 3: all segments of all its tensors at once); no host-side
+ * table work, no copies, no waiting. */
 entro_status entro_plan_run(const entro_plan *plan, void *hip_stream);
 
-/* entro_plan_init followed by entro_plan_run (so these wait for the stream once, before
+/* Fig. 3's decode, the inverse of Eq. 1 and the product of "Latency Reduction from Huffman
+ * Coding" over many tensors: entro_plan_init followed by entro_plan_run (so these wait for the stream once, before
  * their kernel is enqueued; they return without waiting for the kernel). */
 entro_status entro_decode_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,
                                 void *workspace, uint64_t workspace_bytes, void *hip_stream);
@@ -300,7 +313,8 @@ entro_status entro_decode_gemv_batch(const entro_tensor *ts, uint32_t count, ent
  * them, on values the caller copies back.  Results are those of entro_quantize
  * and entro_encode, bit for bit.  All calls only enqueue work on hip_stream. */
 
-/* range16 (device, 16 bytes, 16-byte aligned) receives { float min, float max,
+/* The extrema Eq. 1's scale and zero-point are computed from:
+ * range16 (device, 16 bytes, 16-byte aligned) receives { float min, float max,
  * uint32 nonfinite (1 if a NaN or Inf occurs, NaNs do not enter min / max),
  * uint32 0 } of w (device, n floats, 16-byte aligned). */
 entro_status entro_range_device(const float *w, uint64_t n, void *range16, void *hip_stream);
@@ -319,8 +333,8 @@ entro_status entro_qparams_from_range(float min, float max, uint32_t nonfinite, 
  * negative (norm gains, for instance); the asymmetric grid otherwise. */
 entro_scheme entro_scheme_for_range(float min, float max);
 
-/* q[i] = clamp(rint(w[i] / s) + z, 0, 2^bits - 1), one symbol per byte, and the
- * histogram of the symbols.  w: device, n floats; q: device, n bytes; counts:
+/* Eq. 1's grid map, q[i] = clamp(rint(w[i] / s) + z, 0, 2^bits - 1), one symbol per byte, and the
+ * histogram of the symbols ("Huffman weight encoding" starts from it).  w: device, n floats; q: device, n bytes; counts:
  * device, 256 entries, overwritten (entries at and above 2^bits end up 0); all
  * 16-byte aligned.  qp: host.  ENTRO_ERR_RANGE if |zero_point| > 2^24 (the
  * decoders take no such tensor either).  A NaN weight, which entro_range_device
@@ -329,10 +343,11 @@ entro_status entro_quantize_device(const float *w, uint64_t n, const entro_qpara
                                    void *hip_stream);
 
 /* Host: exact size in bytes (padding included) of the stream that symbols with
- * this histogram make under this codebook; 0 if a counted symbol has no code. */
+ * this histogram make under this codebook ("Huffman weight encoding": sum of count times length); 0 if a counted symbol has no code. */
 uint64_t entro_encoded_bytes(const uint64_t *counts, const entro_codebook *cb);
 
-/* Encode q (device, n symbols one per byte) into stream (device, stream_cap
+/* "Huffman weight encoding" into Fig. 3's segments on the device: encode q (device, n symbols
+ * one per byte) into stream (device, stream_cap
  * bytes, a multiple of 16) and fill offsets (device, entro_num_chunks + 1
  * entries), in the format described at the top; the padded size is
  * entro_encoded_bytes, or follows from offsets[n_chunks].  cb: host.
@@ -343,12 +358,13 @@ uint64_t entro_encoded_bytes(const uint64_t *counts, const entro_codebook *cb);
 entro_status entro_encode_device(const uint8_t *q, uint64_t n, const entro_codebook *cb, uint32_t chunk_symbols, void *stream,
                                  uint64_t stream_cap, uint64_t *offsets, uint32_t *status, void *hip_stream);
 
-/* Host: the meaning of a status word of entro_encode_device: ENTRO_OK,
+/* Host: the meaning of a status word of entro_encode_device (Fig. 3's encode side): ENTRO_OK,
  * ENTRO_ERR_SYMBOL (a symbol without a code), ENTRO_ERR_CAPACITY (stream_cap too
  * small), ENTRO_ERR_SIZE (the stream would reach 4 GiB). */
 entro_status entro_encode_device_status(uint32_t status_word);
 
-/* Text of the last HIP error seen by the calling thread ("" if none). */
+/* Text of the last HIP error seen by the calling thread ("" if none) (error reporting; no
+ * passage of the paper defines it). */
 const char *entro_last_device_error(void);
 
 #ifdef __cplusplus

@@ -29,6 +29,40 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert set(B.EXPORTED) == declared
 
 
+def test_every_declaration_cites_the_passage_that_defines_it():
+    """Each exported call's own comment names the section, equation, figure or table of the paper that defines
+    what it computes; the two error-reporting calls say that none does, and the entry point that allocates
+    nothing names the callers it is for."""
+    lines = open(os.path.join(ROOT, "include", "entro.h")).read().split("\n")
+    cite = re.compile(r'Eq\. 1|Fig\. [23]|Table [23]|"Huffman weight encoding"|"Segmentation for parallel Huffman decoding"'
+                      r'|"Latency Reduction from Huffman Coding"|"Mixed Quantization Scheme"')
+    decl = re.compile(r"^(?:entro_status|entro_scheme|uint64_t|uint32_t|double|const char \*)\s*(entro_[a-z0-9_]+)\(")
+    comment, in_comment, attached, seen = "", False, False, {}
+    for ln in lines:
+        if in_comment or ln.lstrip().startswith("/*"):
+            if not in_comment:
+                comment, in_comment = "", True
+            comment += " " + ln.strip().lstrip("/*").strip()
+            if "*/" in ln:
+                in_comment, attached = False, True
+                comment = re.sub(r"\s+", " ", comment.replace("*/", ""))
+            continue
+        m = decl.match(ln)
+        if m:
+            assert attached, f"{m.group(1)} has no comment of its own"
+            seen[m.group(1)] = comment
+        elif ln.strip() == "":
+            attached = False                                  # a blank line ends a comment's reach
+    assert set(seen) == set(B.EXPORTED), set(B.EXPORTED) ^ set(seen)
+    for name, text in seen.items():
+        if name in ("entro_status_string", "entro_last_device_error"):
+            assert "no passage of the paper defines it" in text, name
+        elif name == "entro_decode_gemv_static":
+            assert "cannot allocate" in text, name
+        else:
+            assert cite.search(text), f"{name}: no citation in its comment: {text[:80]}"
+
+
 def test_struct_layouts_match_header():
     assert C.sizeof(B.QParams) == 16
     assert C.sizeof(B.Codebook) == 16 + 256 + 1024
