@@ -263,11 +263,12 @@ entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type,
 
 /* Batched forms: ONE launch over `count` tensors (a single tensor has too few of
  * Fig. 3's segments to fill 256 compute units).  The descriptor table, the work list
- * and the GEMV partial sums live in `workspace` (device). */
+ * the tensors' lookup tables and the GEMV partial sums live in `workspace` (device). */
 uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
 
 /* Prepare a batched launch of Fig. 3's segment-parallel decode (or of the fused forms above):
- * validate, build the table on the host and copy it into the workspace.  BLOCKS until
+ * validate, build the table on the host, copy it into the workspace and enqueue a small kernel
+ * that builds every tensor's lookup tables there (so that the launches need not).  BLOCKS until
  * the copy, and with it everything enqueued on hip_stream before, has completed (the
  * table is staged in memory that dies with the call); entro_plan_init_staged does not.
  * The tensors' device buffers are referenced, not copied.

@@ -69,6 +69,7 @@ struct DevTensor {
     const uint16_t *x;
     float *partials;            // GEMV: head/tail partial sums, 2 per segment
     const uint16_t *sub;        // entry points inside the segments: stream bits of every piece (or null)
+    void *tables;               // batched launches: the tensor's lookup tables as k_tables left them (or null: build them)
     uint64_t n;
     uint32_t stream_bytes;
     uint32_t chunk_symbols;     // symbols one lane decodes: a piece, where the tensor has entry points, else a segment
@@ -82,6 +83,7 @@ struct DevTensor {
     int32_t zero_point;
     uint32_t max_len;
     uint32_t need_fix;
+    uint32_t row_lanes;         // GEMV: lanes per matrix row where a wavefront sums its rows by itself (0: not so)
     uint32_t fine;              // batched launches: index of the same tensor's description with finer lanes (0: none)
     uint32_t fine_shift;        // log2 of how many of those lanes make one of this description's
     uint8_t len[256];
@@ -1250,6 +1252,24 @@ __device__ __forceinline__ void gemv_segment(const DevTensor &t, const TB &tb, u
     }
 }
 
+// Lanes that take pieces of a row, t.row_lanes (a power of two, 2..64) side by side in one wavefront: every
+// lane's piece lies inside one row and `mine` is its sum; the row's lanes add theirs up in a fixed tree and
+// the first of them stores the row.  Neither partial sums in memory nor a second kernel are needed then.
+template <int MODE>
+__device__ __forceinline__ void wave_row_sums(const DevTensor &t, uint32_t k, bool full, float mine) {
+    const uint32_t rl = t.row_lanes;
+    float v = full ? mine : 0.0f;                          // (lanes behind the tensor's end)
+#pragma unroll
+    for (uint32_t m = 1; m < 64u; m <<= 1)
+        if (m < rl) v += __shfl_xor(v, static_cast<int>(m), 64);
+    if (full && (k & (rl - 1u)) == 0) {
+        const float y = v * t.scale;
+        const uint32_t row = k / rl;
+        if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
+        else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
+    }
+}
+
 // GEMV: the lane that decodes a segment also multiplies it into x, a group of symbols at a time as
 // they come out of the table; there is no tile and no flush, which leaves LDS for 14 wavefronts.
 // All lanes are at the same place of their segments, so where segments and rows coincide the lanes
@@ -1357,7 +1377,9 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
         if (h + 1 < halves) ask_x(col);
         if (!PAIR || (h & 1u)) ring_topup(r);              // once per block of 16 groups
     }
-    if (fast) {
+    if (t.row_lanes) {
+        wave_row_sums<MODE>(t, k, fast, crossed ? first : acc);
+    } else if (fast) {
         if (!crossed) {
             t.partials[2 * static_cast<uint64_t>(k)] = acc;              // the segment lies inside one row
         } else {
@@ -1479,7 +1501,9 @@ __device__ __forceinline__ void gemv_direct2(const DevTensor &t, const Tables32 
         if (h + 1 < halves) ask_x(col);
         ring2_topup(r);
     }
-    if (fast) {
+    if (t.row_lanes) {
+        wave_row_sums<MODE>(t, k, fast, crossed ? first : acc);
+    } else if (fast) {
         if (!crossed) {
             t.partials[2 * static_cast<uint64_t>(k)] = acc;              // the segment lies inside one row
         } else {
@@ -1592,7 +1616,15 @@ __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors
             n_all = n_coarse + static_cast<uint32_t>((fine_end - fine_first + kUnit - 1) / kUnit);
         }
         __syncthreads();                                     // nobody reads the previous tables or the counter any more
-        build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+        if (t.tables) {
+            // built once when the launch was prepared: 16 bytes per lane and step from memory into LDS
+            const u32x4 *src = static_cast<const u32x4 *>(t.tables);
+            u32x4 *dst = reinterpret_cast<u32x4 *>(&sm.tb);
+            for (uint32_t j = threadIdx.x; j < sizeof(sm.tb) / 16u; j += WG) dst[j] = src[j];
+            __syncthreads();
+        } else {
+            build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+        }
         if (rows_fit<MODE>(t)) {
             if (threadIdx.x == 0) next_unit = 0;
             __syncthreads();
@@ -1626,6 +1658,20 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_batch(const DevTensor
                                                                  const WorkItem *__restrict__ items, uint32_t n_items,
                                                                  uint32_t item_units) {
     batch_body<MODE>(tensors, items, n_items, item_units);
+}
+
+// The lookup tables of the tensors of a prepared launch, built once (workgroup b: tensor b) and kept in
+// memory for the launch's workgroups to load.
+template <int MODE>
+__global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_tables(const DevTensor *__restrict__ tensors) {
+    constexpr uint32_t WG = 64 * Cfg<MODE>::waves;
+    __shared__ SmemFor<MODE> sm;
+    const DevTensor &t = tensors[blockIdx.x];
+    build_tables<WG, kPairMode<MODE>>(t, sm.tb, reinterpret_cast<uint32_t *>(sm.wm));
+    static_assert(sizeof(sm.tb) % 16 == 0, "copied in 16-byte steps");
+    const u32x4 *src = reinterpret_cast<const u32x4 *>(&sm.tb);
+    u32x4 *dst = static_cast<u32x4 *>(t.tables);
+    for (uint32_t j = threadIdx.x; j < sizeof(sm.tb) / 16u; j += WG) dst[j] = src[j];
 }
 
 // Second stage of the GEMV: rows that straddle segments are summed in segment order.
@@ -1777,6 +1823,15 @@ entro_status fill_dev_tensor(const entro_tensor *t, entro_op op, entro_dtype d, 
     dt->zero_point = t->qp.zero_point;
     dt->max_len = static_cast<uint32_t>(t->cb->max_len);
     dt->need_fix = (op == ENTRO_OP_GEMV && (lane_symbols % t->cols) != 0) ? 1u : 0u;
+    // rows cut into a power of two of lanes (at most a wavefront's 64) that all go through the kernels' block
+    // path: the wavefront adds the row up itself
+    if (dt->need_fix && t->cols % lane_symbols == 0 && lane_symbols % 128u == 0) {
+        const uint32_t per_row = t->cols / lane_symbols;
+        if (per_row <= 64u && (per_row & (per_row - 1u)) == 0) {
+            dt->row_lanes = per_row;
+            dt->need_fix = 0;
+        }
+    }
     std::memcpy(dt->len, t->cb->len, 256);
     return ENTRO_OK;
 }
@@ -1915,9 +1970,11 @@ uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 uint32_t lane_symbols_of(const entro_tensor &t) { return t.sub_symbols ? t.sub_symbols : t.chunk_symbols; }
 
 struct Layout {
-    uint64_t off_tensors, off_items, off_fix, off_partials, total;
+    uint64_t off_tensors, off_items, off_fix, off_partials, off_tables, total;
     uint32_t n_items, n_fix;
 };
+// room for one tensor's lookup tables in the workspace (the larger kind, whichever the launch uses)
+constexpr uint64_t kTablesStride = (sizeof(Tables32) + 255) / 256 * 256;
 
 // Workspace layout shared by entro_workspace_bytes and entro_plan_init.
 bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L) {
@@ -1938,7 +1995,8 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
     L->off_items = align_up(sizeof(DevTensor) * 2 * static_cast<uint64_t>(count), 256);   // a tensor may be described at two lane sizes
     L->off_fix = L->off_items + align_up(sizeof(WorkItem) * items, 256);
     L->off_partials = L->off_fix + align_up(sizeof(WorkItem) * fix, 256);
-    L->total = L->off_partials + align_up(sizeof(float) * partial_floats, 256);
+    L->off_tables = L->off_partials + align_up(sizeof(float) * partial_floats, 256);
+    L->total = L->off_tables + kTablesStride * count;
     return true;
 }
 
@@ -2024,6 +2082,7 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
     for (uint32_t i = 0; i < count; ++i) {
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, level, &dts[i]);
         if (st != ENTRO_OK) return st;
+        dts[i].tables = static_cast<unsigned char *>(workspace) + L.off_tables + kTablesStride * i;
         total_units += (dts[i].n_chunks + kUnit - 1) / kUnit;
         pairs = pairs && dts[i].bits == 4;
         multirow = multirow || (op == ENTRO_OP_GEMV && dts[i].cols < dts[i].chunk_symbols);
@@ -2051,6 +2110,7 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
         if (finer == 0 || dts[i].chunk_symbols % block != 0) continue;
         entro_status st = fill_dev_tensor(&ts[i], op, out_type, dts[i].sub_merge - finer, &dts[n_desc]);
         if (st != ENTRO_OK) return st;
+        dts[n_desc].tables = dts[i].tables;
         dts[i].fine = n_desc++;
         dts[i].fine_shift = finer;
     }
@@ -2091,6 +2151,19 @@ static entro_status plan_checks(entro_plan *plan, const entro_tensor *ts, uint32
     return ENTRO_OK;
 }
 
+// Enqueue the kernel that builds every tensor's lookup tables into the workspace (behind the copy of the
+// descriptor table on the same stream).
+static entro_status enqueue_tables(const entro_plan *plan, hipStream_t s) {
+    const DevTensor *dts = reinterpret_cast<const DevTensor *>(static_cast<const unsigned char *>(plan->workspace) + plan->off_tensors);
+    const int mode = mode_of(static_cast<entro_op>(plan->op), static_cast<entro_dtype>(plan->out), plan->pair_tables != 0,
+                             plan->wide_tables != 0);
+    dispatch_mode(mode, [&](auto m) {
+        constexpr int M = decltype(m)::value;
+        hipLaunchKernelGGL(k_tables<M>, dim3(plan->count), dim3(wg_of(mode)), 0, s, dts);
+    });
+    return hip_ok(hipGetLastError(), "launch table kernel") ? ENTRO_OK : ENTRO_ERR_DEVICE;
+}
+
 uint64_t entro_plan_staging_bytes(const entro_tensor *ts, uint32_t count, entro_op op) {
     Layout L;
     if (!ts || count == 0 || !plan_layout(ts, count, op, &L)) return 0;
@@ -2110,7 +2183,7 @@ entro_status entro_plan_init_staged(entro_plan *plan, const entro_tensor *ts, ui
     if (!hip_ok(hipMemcpyAsync(workspace, staging, L.off_partials, hipMemcpyHostToDevice, static_cast<hipStream_t>(hip_stream)),
                 "copy plan table"))
         return ENTRO_ERR_DEVICE;
-    return ENTRO_OK;
+    return enqueue_tables(plan, static_cast<hipStream_t>(hip_stream));
 }
 
 entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
@@ -2127,7 +2200,7 @@ entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t 
         return ENTRO_ERR_DEVICE;
     // the staging vector dies with this call, so wait for the copy
     if (!hip_ok(hipStreamSynchronize(s), "wait for plan table")) return ENTRO_ERR_DEVICE;
-    return ENTRO_OK;
+    return enqueue_tables(plan, s);
 }
 
 entro_status entro_plan_run(const entro_plan *plan, void *hip_stream) {

@@ -401,7 +401,8 @@ def test_entry_points_inside_segments_every_output(bits, chunk, sub, n, batch):
 
 @pytest.mark.parametrize("batch", [False, True])
 @pytest.mark.parametrize("rows,cols,chunk,sub", [(128, 4096, 4096, 256), (96, 14336, 4096, 256), (300, 1024, 4096, 512), (65, 1536, 2048, 128),
-                                                 (40, 200, 1024, 64), (520, 128, 4096, 1024)])
+                                                 (40, 200, 1024, 64), (520, 128, 4096, 1024), (67, 8192, 2048, 128),
+                                                 (200, 2048, 2048, 128)])
 def test_gemv_with_entry_points_inside_segments(rows, cols, chunk, sub, batch):
     rng = np.random.default_rng(rows * cols + sub)
     sym = np.clip(np.rint(rng.standard_t(5, rows * cols) * 6 + 128), 0, 255).astype(np.uint8)
