@@ -1674,37 +1674,44 @@ __global__ __launch_bounds__(64 * Cfg<MODE>::waves) void k_tables(const DevTenso
     for (uint32_t j = threadIdx.x; j < sizeof(sm.tb) / 16u; j += WG) dst[j] = src[j];
 }
 
-// Second stage of the GEMV: rows that straddle segments are summed in segment order.
+// Second stage of the GEMV: the partial sums of a row that straddles lanes are added up by sixteen lanes,
+// lane j taking every sixteenth of them in segment order, then the sixteen in a fixed tree (the same sum
+// in the same order on every run).
+constexpr int kFixWG = 256;                                   // threads of a workgroup
+constexpr int kFixRows = kFixWG / 16;                         // and the rows it sums
+
 template <int MODE>
-__device__ __forceinline__ void fix_row(const DevTensor &t, uint32_t row) {
-    if (row >= t.rows) return;
-    const uint64_t lo = static_cast<uint64_t>(row) * t.cols;
-    const uint64_t hi = lo + t.cols - 1;
-    const uint32_t k_lo = static_cast<uint32_t>(lo / t.chunk_symbols);
-    const uint32_t k_hi = static_cast<uint32_t>(hi / t.chunk_symbols);
-    if (k_lo == k_hi) return;                                 // whole row inside one segment: already stored
-    float acc = 0.0f;
-    for (uint32_t k = k_lo; k <= k_hi; ++k) {
-        const uint32_t first_row = static_cast<uint32_t>((static_cast<uint64_t>(k) * t.chunk_symbols) / t.cols);
-        acc += t.partials[2 * static_cast<uint64_t>(k) + (first_row == row ? 0 : 1)];
+__device__ __forceinline__ void fix_row(const DevTensor &t, uint32_t row, uint32_t j) {
+    const bool live = row < t.rows;
+    uint32_t k_lo = 1, k_hi = 0;
+    if (live) {
+        const uint64_t lo = static_cast<uint64_t>(row) * t.cols;
+        k_lo = static_cast<uint32_t>(lo / t.chunk_symbols);
+        k_hi = static_cast<uint32_t>((lo + t.cols - 1) / t.chunk_symbols);
     }
+    float acc = 0.0f;
+    for (uint64_t k = static_cast<uint64_t>(k_lo) + j; k <= k_hi; k += 16u) {
+        const uint32_t first_row = static_cast<uint32_t>((k * t.chunk_symbols) / t.cols);
+        acc += t.partials[2 * k + (first_row == row ? 0 : 1)];
+    }
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) acc += __shfl_xor(acc, m, 64);
+    if (!live || k_lo == k_hi || j != 0) return;             // (a whole row inside one lane's segment is stored already)
     const float y = acc * t.scale;
     if (gemv_f32(MODE)) reinterpret_cast<float *>(t.out)[row] = y;
     else reinterpret_cast<uint16_t *>(t.out)[row] = static_cast<uint16_t>(bf16_bits(y));
 }
 
-constexpr int kFixWG = 256;
-
 template <int MODE>
 __global__ __launch_bounds__(kFixWG) void k_fix_single(const DevTensor t) {
-    fix_row<MODE>(t, blockIdx.x * kFixWG + threadIdx.x);
+    fix_row<MODE>(t, blockIdx.x * kFixRows + threadIdx.x / 16u, threadIdx.x & 15u);
 }
 
 template <int MODE>
 __global__ __launch_bounds__(kFixWG) void k_fix_batch(const DevTensor *__restrict__ tensors,
                                                    const WorkItem *__restrict__ items) {
     const WorkItem it = items[blockIdx.x];
-    fix_row<MODE>(tensors[it.tensor], it.first + threadIdx.x);
+    fix_row<MODE>(tensors[it.tensor], it.first + threadIdx.x / 16u, threadIdx.x & 15u);
 }
 
 // ------------------------------------------------------------------ host glue
@@ -1935,7 +1942,7 @@ entro_status launch_single(const entro_tensor *t, entro_op op, entro_dtype d, fl
     });
     if (!hip_ok(hipGetLastError(), "launch decode kernel")) return ENTRO_ERR_DEVICE;
     if (dt.need_fix) {
-        const unsigned g2 = (dt.rows + kFixWG - 1) / kFixWG;
+        const unsigned g2 = (dt.rows + kFixRows - 1) / kFixRows;
         if (gemv_f32(mode)) hipLaunchKernelGGL(k_fix_single<kModeGemvF32>, dim3(g2), dim3(kFixWG), 0, s, dt);
         else hipLaunchKernelGGL(k_fix_single<kModeGemvBF16>, dim3(g2), dim3(kFixWG), 0, s, dt);
         if (!hip_ok(hipGetLastError(), "launch row-sum kernel")) return ENTRO_ERR_DEVICE;
@@ -1984,7 +1991,7 @@ bool plan_layout(const entro_tensor *ts, uint32_t count, entro_op op, Layout *L)
         const uint64_t nc = entro_num_chunks(ts[i].n, lane_symbols_of(ts[i]));
         items += (nc + kUnit - 1) / kUnit;
         if (op == ENTRO_OP_GEMV && ts[i].cols && (lane_symbols_of(ts[i]) % ts[i].cols) != 0) {
-            fix += (static_cast<uint64_t>(ts[i].rows) + kFixWG - 1) / kFixWG;
+            fix += (static_cast<uint64_t>(ts[i].rows) + kFixRows - 1) / kFixRows;
             partial_floats += 2 * nc;
         }
     }
@@ -2089,7 +2096,7 @@ static entro_status build_plan(entro_plan *plan, const entro_tensor *ts, uint32_
         if (dts[i].need_fix) {
             dts[i].partials = partials_base + partial_floats;
             partial_floats += 2 * static_cast<uint64_t>(dts[i].n_chunks);
-            for (uint32_t r = 0; r < dts[i].rows; r += kFixWG) fix[n_fix++] = WorkItem{i, r};
+            for (uint32_t r = 0; r < dts[i].rows; r += kFixRows) fix[n_fix++] = WorkItem{i, r};
         }
     }
     // A work item is what a workgroup takes in one round when the launch is large (a unit per
