@@ -1606,7 +1606,7 @@ __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors
         // length of a whole segment.
         const DevTensor *tf = &t;
         uint32_t n_coarse = n_units, n_all = n_units, fine_first = 0;
-        if (t.fine) {
+        if (!is_gemv(MODE) && t.fine) {                      // (the GEMV's descriptions have none)
             tf = &tensors[t.fine];
             const uint32_t refined = n_units % static_cast<uint32_t>(Cfg<MODE>::waves);   // what does not fill a round
             n_coarse = n_units - refined;
@@ -1633,7 +1633,7 @@ __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors
                 if ((threadIdx.x & 63u) == 0) u = atomicAdd(&next_unit, 1u);
                 u = __builtin_amdgcn_readfirstlane(u);
                 if (u >= n_all) break;
-                const bool fine = u >= n_coarse;
+                const bool fine = !is_gemv(MODE) && u >= n_coarse;
                 const DevTensor &d = fine ? *tf : t;
                 const uint32_t first = fine ? fine_first + (u - n_coarse) * kUnit : it.first + u * kUnit;
                 if constexpr (wide_gemv(MODE)) gemv_direct2<MODE>(d, sm.tb, sm.wm[threadIdx.x >> 6].ring, first);
@@ -1770,7 +1770,7 @@ uint32_t choose_level(const entro_tensor *ts, uint32_t count, uint64_t lane_slot
         uint64_t lanes = 0;
         for (uint32_t i = 0; i < count; ++i)
             if (ts[i].chunk_symbols) lanes += (ts[i].n + lane_symbols_at(ts[i], level) - 1) / lane_symbols_at(ts[i], level);
-        if (lanes >= lane_slots) return level;
+        if (lanes * 8 >= lane_slots * 7) return level;        // (seven eighths of the slots: one unit per wavefront beats two for most)
     }
     return 0;
 }
