@@ -53,12 +53,14 @@ def log(msg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=32, help="layers of the mistral-7B-shaped set (32 = the full workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the u8 and GEMV legs")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the legs on configs[0..2]")
+    ap.add_argument("--no-limited", action="store_true", help="skip the leg with length-limited codebooks")
+    ap.add_argument("--no-compress", action="store_true", help="skip the compression kernels' leg")
     ap.add_argument("--sub-symbols", type=int, default=256,
                     help="entry points inside the segments every this many symbols (0: none)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -372,7 +374,7 @@ def main():
         log(f"gemv, one launch: {result['gemv_one_launch']['us_per_layer']} us/layer")
 
     # ------------------------------------------------ the headline set again with length-limited codebooks
-    if not args.no_extras:
+    if not args.no_extras and not args.no_limited:
         # no code longer than the decoder's first-level table is wide: the slow path for long codes never
         # runs; what it costs in bits is reported beside what it gains
         log("preparing the headline set with codes of at most 14 bits")
@@ -522,7 +524,7 @@ def main():
         result["other_configs"] = others
 
     # ------------------------------------------------ the steps before the path, on the GPU
-    if not args.no_extras:
+    if not args.no_extras and not args.no_compress:
         log("timing the compression kernels on layer 0's fp32 weights")
         specs0 = synth.config_tensors(4, layers=1)
         comp = {"workload": "layer 0 of the mistral-7B-shaped set, fp32 weights resident in HBM: range, quantise + count, "

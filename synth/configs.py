@@ -184,8 +184,11 @@ def adversarial_symbol_cases(bits: int = 8):
     yield "chunk_plus_1", geo[:4097], 4096
     yield "ragged_tail", geo[:3 * 4096 + 17], 4096
     yield "odd_n", geo[:10001], 2048
-    # Fibonacci-weighted counts give the deepest possible Huffman tree: with
-    # min(A, 33) symbols the longest code has min(A, 33) - 1 <= 32 bits.
+    # Fibonacci-weighted counts give the deepest possible Huffman tree (m symbols: the
+    # longest code has m - 1 bits).  The counts are capped at 200000 below to keep the case
+    # small, which flattens the top of the tree: with 8-bit symbols the longest code comes
+    # out at 28 bits, not 32 (codes of exactly 32 bits are exercised through
+    # codebooks given by their lengths instead); with 4-bit symbols, 15 bits.
     m = min(A, 33)
     fib = [1, 1]
     while len(fib) < m:

@@ -362,7 +362,7 @@ def test_gemv_4bit_two_symbols_per_lookup(rows, cols, chunk, batch):
     xb = synth.make_x_bf16(1, rows % 4, cols)
     y_ref, _ = oracle.gemv(sym, rows, cols, enc.qp.scale, 6, xb)
     _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), y_ref)
-    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_BF16, batch), y_ref, tol=8e-3)   # y itself rounded to bf16
+    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_BF16, batch), y_ref, tol=3e-3)   # y itself rounded to bf16: half an ulp, 2^-9, on top of the 1e-3
 
 
 def test_gemv_unit_vector_picks_a_column_exactly():
@@ -632,7 +632,7 @@ def test_mistral_layer_launch_shape_sampled_against_oracle():
     rng = np.random.default_rng(0)
     for e, o in zip(encs, outs):
         n_chunks = e.offsets.size - 1
-        picks = sorted(set([0, n_chunks - 1] + rng.integers(0, n_chunks, 3).tolist()))
+        picks = sorted(set([0, n_chunks - 1] + rng.integers(0, n_chunks, 6).tolist()))
         host = o.view(torch.int16).cpu().numpy().view(np.uint16)
         for k in picks:
             q = oracle.decode_chunks(e.stream, e.offsets, e.n, e.chunk_symbols, e.cb.lengths(), e.cb.codes(), k, 1)
@@ -648,7 +648,7 @@ def test_mistral_layer_launch_shape_sampled_against_oracle():
     E.entro_decode_gemv_batch(ts, E.ENTRO_F32, ws)
     torch.cuda.synchronize()
     for i, (e, y) in enumerate(zip(encs, ys)):
-        rows = sorted(set([0, e.rows - 1] + rng.integers(0, e.rows, 2).tolist()))
+        rows = sorted(set([0, e.rows - 1] + rng.integers(0, e.rows, 4).tolist()))
         yh = y.cpu().numpy().astype(np.float64)
         xb = synth.make_x_bf16(i // 7, i % 7, e.cols)
         sub = np.empty((len(rows), e.cols), np.uint8)

@@ -389,7 +389,7 @@ def test_round_trip_identity_on_adversarial_streams(bits):
     # the deep case really is deep
     cases = {n: s for n, s, _ in synth.adversarial_symbol_cases(8)}
     ln, _, _ = oracle.codebook_from_symbols(cases["fibonacci_deep"], 8)
-    assert ln.max() >= 24
+    assert ln.max() == 28          # (not 32: the case caps its counts; 32-bit codes come from given lengths elsewhere)
 
 
 def test_round_trip_identity_config1():
