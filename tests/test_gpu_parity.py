@@ -362,7 +362,7 @@ def test_gemv_4bit_two_symbols_per_lookup(rows, cols, chunk, batch):
     xb = synth.make_x_bf16(1, rows % 4, cols)
     y_ref, _ = oracle.gemv(sym, rows, cols, enc.qp.scale, 6, xb)
     _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_F32, batch), y_ref)
-    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_BF16, batch), y_ref, tol=3e-3)   # y itself rounded to bf16: half an ulp, 2^-9, on top of the 1e-3
+    _assert_gemv_close(_gpu_gemv(enc, xb, E.ENTRO_BF16, batch), y_ref, tol=5e-3)   # y itself rounded to bf16: half an ulp, up to 2^-8 of the value, on top of the 1e-3
 
 
 def test_gemv_unit_vector_picks_a_column_exactly():

@@ -29,6 +29,24 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert set(B.EXPORTED) == declared
 
 
+def test_comparison_kernels_live_in_their_own_library():
+    """The memory probe and the plain uint8 GEMV that bench.py times are not part of libentro: they are built
+    into bench_kernels/libentro_bench.so, which exports what its header declares."""
+    import bench_kernels
+    header = open(os.path.join(ROOT, "bench_kernels", "entro_bench.h")).read()
+    declared = set(re.findall(r"\b(bench_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(bench_kernels.EXPORTED)
+    if not os.path.exists(bench_kernels.LIB):
+        bench_kernels.build()
+    extra = C.CDLL(bench_kernels.LIB)
+    for name in sorted(declared):
+        assert hasattr(extra, name), name
+    assert C.sizeof(C.c_void_p) * 3 + 4 * 6 == bench_kernels.ITEM.itemsize       # bench_gemv_item
+    assert bench_kernels.lib().bench_gemv_tasks(9) == 3 and bench_kernels.lib().bench_gemv_tasks(8) == 2
+    L = E.lib()
+    assert not hasattr(L, "entro_stream_probe") and not hasattr(L, "entro_gemv_u8_plain")
+
+
 def test_every_declaration_cites_the_passage_that_defines_it():
     """Each exported call's own comment names the section, equation, figure or table of the paper that defines
     what it computes; the two error-reporting calls say that none does, and the entry point that allocates
