@@ -555,12 +555,11 @@ __device__ void decode_scalar(const DevTensor &t, const TB &tb, uint32_t k, uint
 }
 
 // ------------------------------------------------------------------ ring reader
-// Each lane keeps up to 128 bytes of its segment in a ring in LDS (eight 16-byte
-// blocks, block j in slot j & 7) and the line that follows the ring's contents
-// in registers: a lane asks memory for a whole line at a time, 128 bytes in the
-// kernels that write their output (the lanes' requests are scattered over the
-// stream, and memory serves two neighbouring 64-byte halves together far better
-// than one now and one later), 64 bytes in the GEMV.  Dwords
+// The long ring (gemv_direct, i.e. the GEMV of tensors that do not fit the wide tables; the
+// other kernels use the short ring below).  Each lane keeps up to 128 bytes of its segment
+// in a ring in LDS (eight 16-byte blocks, block j in slot j & 7) and the line that follows
+// the ring's contents in registers: a lane asks memory for a whole line at a time (LB
+// blocks; gemv_direct takes 64 bytes).  Dwords
 // 32 and 33 of the lane's ring mirror dwords 0 and 1, so a three-dword read
 // starting in the last ring dwords needs no wrap.
 // Positions are bits relative to line 0, the line in which the segment starts.  The lane tracks q = p - 1, p being its position: a window read at bit
@@ -1088,8 +1087,8 @@ __device__ __forceinline__ void decode_rows(const DevTensor &t, const Tables &tb
     if (rest) decode_scalar_from<MODE>(t, tb, tail_pos, static_cast<uint64_t>(k) * C + my_blocks * SPB, rest);
 }
 
-// decode_rows for the fp32 and bf16 outputs, on the short ring: sixteen wavefronts per workgroup
-// instead of ten.  A block of 64 symbols per lane is decoded and flushed in two halves of 32.  A
+// decode_rows for the fp32 and bf16 outputs with a tile of half a block: sixteen wavefronts per
+// workgroup instead of fourteen.  A block of 64 symbols per lane is decoded and flushed in two halves of 32.  A
 // half makes 128 bytes of fp32 per row, which go out as they are; of bf16 it makes 64, so the first
 // half's symbols wait in registers (in the lanes that will convert them) and the second half's flush
 // writes whole 128-byte rows.
@@ -1391,20 +1390,13 @@ __device__ __forceinline__ void gemv_direct(const DevTensor &t, const Tables &tb
     }
 }
 
-// The same on wide tables and the short ring (8-bit symbols whose zero-point lies in [-1, 256], so that
-// symbol - zero_point is a bf16): sixteen wavefronts, two products per instruction, no conversion per symbol.
-// GEMV: the lane that decodes a segment also multiplies it into x, a group of symbols at a time as
-// they come out of the table; there is no tile and no flush, which leaves LDS for 14 wavefronts.
-// All lanes are at the same place of their segments, so where segments and rows coincide the lanes
-// of a wave ask for the same piece of x (one request); elsewhere they ask for a handful of
-// different ones.  The 64 activations of a half block are requested one half block ahead, before
-// the stream lines that ring_topup asks for: loads return in order, and a wait for x must not
-// become a wait for the stream.
-// A segment may begin and end anywhere in a row and hold any number of row ends (cols >= 64, so a
-// half block holds at most one): the sum up to the first row end is the head fragment (or a whole
-// row, if the segment starts one), every further row end completes a whole row, which the lane
-// stores itself, and what is left at the end is the tail fragment; the fragments go to the
-// segment's two partial sums, which the second stage adds up per row.
+// gemv_direct on wide tables and the short ring (8-bit symbols whose zero-point lies in [-1, 256], so that
+// symbol - zero_point is a bf16 as it stands): the table entry carries that value, two v_perm gather a group's
+// four values into two bf16 pairs and two v_dot2c_f32_bf16 multiply them into x; no conversion and no
+// subtraction per symbol.  The 64 KB table and a ring of 64 bytes per lane leave LDS for sixteen wavefronts.
+// The ring is topped up after every eight groups.  Row ends, fragments and the request for x one half block
+// ahead are gemv_direct's; lanes that cut a row into a power of two of pieces add the row up themselves
+// (wave_row_sums) instead of writing partial sums.
 template <int MODE>
 __device__ __forceinline__ void gemv_direct2(const DevTensor &t, const Tables32 &tb, uint32_t *ring_mem, uint32_t wave_first) {
     constexpr int GPH = 16;                                // groups of four symbols per half block of 64 symbols
@@ -1579,11 +1571,11 @@ __device__ __forceinline__ void single_body(const DevTensor &t, uint32_t wg_unit
 // what a wavefront decodes at a time.  The work list has one item per
 // `item_units` units of a tensor (fewer at the tensor's end), in tensor order;
 // workgroup b of G takes the items [b * n / G, (b + 1) * n / G): a few stretches
-// of one tensor each.  Per stretch it builds the tensor's tables once, then its
-// wavefronts draw units from a counter in LDS until the stretch is used up.  The
-// wavefronts of a workgroup do not run equally fast (ten of them share four
-// SIMDs, three on two of them and two on the others), so a fixed split would
-// leave the faster ones waiting.
+// of one tensor each.  Per stretch it loads the tensor's tables (or builds them, if the
+// launch was not prepared with them), then its wavefronts draw units from a counter in
+// LDS until the stretch is used up.  The wavefronts of a workgroup do not run equally
+// fast (fourteen of them share four SIMDs unevenly; lanes meet long codes at different
+// times), so a fixed split would leave the faster ones waiting.
 template <int MODE>
 __device__ __forceinline__ void batch_body(const DevTensor *__restrict__ tensors, const WorkItem *__restrict__ items,
                                            uint32_t n_items, uint32_t item_units) {
