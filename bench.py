@@ -194,6 +194,40 @@ def main():
                              bf16_ref, "bf16")
     log(f"{whole} whole tensors ({sum(encs[i].n for i in whole_idx)} elements) and {checked} sampled segments match the oracle")
 
+    # ------------------------- batch > 1 ("pre-fill"): the weights are decoded once, then multiplied as dense matrices
+    prefill = None
+    if not args.no_extras:
+        batch = 256
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        n0 = min(7, len(encs))
+        xs_b = {c: torch.randn(batch, c, device=dev, generator=gen).to(torch.bfloat16) for c in sorted({e.cols for e in encs[:n0]})}
+        w0 = [views[i].view(encs[i].rows, encs[i].cols) for i in range(n0)]
+
+        def layer_gemms():
+            return [torch.matmul(xs_b[w.shape[1]], w.t()) for w in w0]            # library GEMMs on the decoded bf16 weights
+
+        wpf, kpf = timed(layer_gemms, args.steps, args.warmup)
+        ys_b = layer_gemms()
+        # one token's row of two products against the oracle's GEMV on the exact weights (the dense path multiplies
+        # weights rounded to bf16 and rounds y to bf16: 2^-8 relative per factor, averaged over the row)
+        for i in (0, n0 - 1):
+            e = encs[i]
+            q = oracle_symbols(e)
+            xb = xs_b[e.cols][5].view(torch.int16).cpu().numpy().view(np.uint16)
+            y_ref, _ = oracle.gemv(q, e.rows, e.cols, e.qp.scale, e.qp.zero_point, xb)
+            yh = ys_b[i][5].float().cpu().numpy().astype(np.float64)
+            if np.max(np.abs(yh - y_ref)) > 1e-2 * max(np.max(np.abs(y_ref)), 1e-30):
+                print(f"bench.py: dense product on the decoded weights of {e.name} differs from the oracle", file=sys.stderr)
+                sys.exit(1)
+        prefill = {"workload": f"layer 0 at batch {batch}: entro_decode_dequant -> bf16 once, then the layer's seven products as "
+                               "library GEMMs (torch.matmul) on the decoded weights",
+                   "decode_ms_per_layer": round(wall_ms / args.layers, 4), "dense_gemms_ms_per_layer": round(kpf, 4),
+                   "decode_share_of_a_prefill_layer": round((wall_ms / args.layers) / (wall_ms / args.layers + kpf), 3),
+                   "verified_rows": 2}
+        log(f"pre-fill: decode {wall_ms / args.layers:.3f} ms per layer, dense GEMMs at batch {batch} {kpf:.3f} ms per layer")
+        del xs_b, w0, ys_b
+
     # ------------------------- what this GPU's memory takes of a plain stream with the same read/write mix
     rb = (stream_bytes + offset_bytes + 15) // 16 * 16
     probe_src = torch.zeros(rb, dtype=torch.uint8, device=dev)
@@ -242,6 +276,9 @@ def main():
         "stream_ceiling": {"GBps": round(ceiling, 1), "kernel_ms": round(kp, 4), "frac_of_peak": round(ceiling / HBM_PEAK_GBPS, 4),
                            "launch_frac_of_ceiling": round(achieved / ceiling, 4)},
     }
+
+    if prefill:
+        result["prefill"] = prefill
 
     # ------------------------------------------------------------ extra legs: u8 and GEMV
     if not args.no_extras:
