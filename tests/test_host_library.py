@@ -379,7 +379,13 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     t.sub_symbols = 1
     assert L.entro_decode(C.byref(t), E.ENTRO_U8, None) == B.ENTRO_ERR_SIZE           # 32 pieces per segment
     t.sub_symbols, t.sub_bits = 0, None
-    assert L.entro_workspace_bytes(C.byref(t), 1, E.ENTRO_OP_DECODE) > 0
+    ws1 = L.entro_workspace_bytes(C.byref(t), 1, E.ENTRO_OP_DECODE)
+    st1 = L.entro_plan_staging_bytes(C.byref(t), 1, E.ENTRO_OP_DECODE)
+    # the workspace holds what is staged on the host (descriptors, work list) and, behind it, room for the
+    # tensor's lookup tables (the wider kind: 2^14 entries of four bytes and the side tables)
+    assert 0 < st1 < ws1 and ws1 - st1 >= (1 << 14) * 4 and ws1 % 256 == 0
+    two = (B.CTensor * 2)(t, t)
+    assert L.entro_workspace_bytes(two, 2, E.ENTRO_OP_DECODE) - ws1 >= (1 << 14) * 4
     plan = B.Plan()
     assert L.entro_plan_init(C.byref(plan), C.byref(t), 1, E.ENTRO_OP_DECODE, E.ENTRO_U8, 4096, 16, None) \
         == B.ENTRO_ERR_CAPACITY
