@@ -262,8 +262,9 @@ entro_status entro_decode_gemv(const entro_tensor *t, entro_dtype y_type, void *
 entro_status entro_decode_gemv_static(const entro_tensor *t, entro_dtype y_type, void *hip_stream);
 
 /* Batched forms: ONE launch over `count` tensors (a single tensor has too few of
- * Fig. 3's segments to fill 256 compute units).  The descriptor table, the work list
- * the tensors' lookup tables and the GEMV partial sums live in `workspace` (device). */
+ * Fig. 3's segments to fill 256 compute units).  The descriptor table, the work list,
+ * the tensors' lookup tables (about 68 KB per tensor) and the GEMV partial sums live
+ * in `workspace` (device). */
 uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op op);
 
 /* Prepare a batched launch of Fig. 3's segment-parallel decode (or of the fused forms above):
@@ -273,16 +274,20 @@ uint64_t entro_workspace_bytes(const entro_tensor *ts, uint32_t count, entro_op 
  * table is staged in memory that dies with the call); entro_plan_init_staged does not.
  * The tensors' device buffers are referenced, not copied.
  * The work list is cut for the current device (its number of compute units
- * decides how many units a work item holds): run the plan on the device it was
- * prepared on.  The launch is one workgroup per compute unit at most; inside a
- * workgroup the wavefronts draw their segments from a counter, so which
- * wavefront decodes which segment differs from run to run, the result does not. */
+ * decides how many units a work item holds and, for tensors with entry points
+ * inside their segments, how many pieces a lane takes: as coarse as still gives
+ * the device's lanes work): run the plan on the device it was prepared on.  The
+ * launch is one workgroup per compute unit at most; inside a workgroup the
+ * wavefronts draw their segments from a counter, so which wavefront decodes which
+ * segment differs from run to run, the result does not.  (A GEMV's sums are taken
+ * in an order that depends on how rows are cut into lanes, i.e. on the launch, never
+ * on the run.) */
 entro_status entro_plan_init(entro_plan *plan, const entro_tensor *ts, uint32_t count, entro_op op,
                              entro_dtype out_type, void *workspace, uint64_t workspace_bytes,
                              void *hip_stream);
 
-/* The same (Fig. 3's decode, prepared for many tensors) without waiting: the table is built in `staging` (host memory of the caller's,
- * at least entro_plan_staging_bytes, pinned -- hipHostMalloc -- if the copy is to be
+/* The same (Fig. 3's decode, prepared for many tensors) without waiting: the table is built
+ * in `staging` (host memory of the caller's, at least entro_plan_staging_bytes, pinned -- hipHostMalloc -- if the copy is to be
  * asynchronous) and copied from there on hip_stream.  The caller keeps `staging` alive
  * and unchanged until that copy has completed (a stream or event wait of its own).
  * ENTRO_ERR_CAPACITY if staging_bytes is too small. */
@@ -296,8 +301,8 @@ entro_status entro_plan_init_staged(entro_plan *plan, const entro_tensor *ts, ui
 entro_status entro_plan_run(const entro_plan *plan, void *hip_stream);
 
 /* Fig. 3's decode, the inverse of Eq. 1 and the product of "Latency Reduction from Huffman
- * Coding" over many tensors: entro_plan_init followed by entro_plan_run (so these wait for the stream once, before
- * their kernel is enqueued; they return without waiting for the kernel). */
+ * Coding" over many tensors: entro_plan_init followed by entro_plan_run (so these wait for
+ * the stream once, before their kernel is enqueued; they return without waiting for the kernel). */
 entro_status entro_decode_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,
                                 void *workspace, uint64_t workspace_bytes, void *hip_stream);
 entro_status entro_decode_dequant_batch(const entro_tensor *ts, uint32_t count, entro_dtype out_type,
